@@ -1,0 +1,140 @@
+/*
+ * mmse.h -- C ABI of the MI355X (gfx950) MMSE INT4 scale-search library.
+ *
+ * Method: "Low-bit Quantization of Neural Networks for Efficient Inference"
+ * (arXiv 1902.06822).  A tensor T is approximated linearly as alpha * Q with Q
+ * integer in Z_p (Section 3.1, Eq. 1); alpha minimises the constrained squared
+ * error ||T - alpha*[T/alpha]_Zp||^2 (Section 3.4, Eq. 7-8) by an exact line
+ * search over a grid of a few hundred points; weights get one alpha per
+ * output-channel kernel (Section 3.3), activations one per layer (Section 3.7,
+ * Eq. 15); badly approximated layers get a second INT4 tensor fitted to the
+ * residual (Section 3.5, Algorithm 1, first sweep; Eq. 16).
+ *
+ * General conventions
+ *   - every *_dev pointer is DEVICE memory owned by the caller; the library
+ *     allocates nothing, keeps no state between calls and never synchronises:
+ *     all work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and results are valid once the stream has drained.
+ *   - weight tensors are fp32, row-major [K][n]: K kernels of n elements
+ *     (n = c*w*h of Section 3.1).  Activation tensors are flat fp32 [N].
+ *   - return value: MMSE_OK or a negative mmse_status_t.  All argument checks
+ *     happen before anything is enqueued, so a failed call has no side effect.
+ *   - inputs must be finite.  A problem whose max |T| is below 2^-60 is coded
+ *     as all-zero (scale 1, idx 0, sse = sum T^2); one whose max |T| exceeds
+ *     2^60 or holds inf/NaN is rejected on the device: scale = NaN, idx = -1,
+ *     sse = NaN for that problem, codes unspecified.
+ *   - "sse" is the SUM of squared errors (the paper omits the mean factor,
+ *     Section 3.2), accumulated as documented in mmse_kernels.hip.
+ */
+#ifndef MMSE_H_
+#define MMSE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mmse_status_t {
+    MMSE_OK = 0,
+    MMSE_ERR_NULL = -1,        /* a required pointer is NULL                           */
+    MMSE_ERR_SIZE = -2,        /* K, n or N <= 0, or beyond the limits below           */
+    MMSE_ERR_PARAMS = -3,      /* bad quantization range, grid size or refine count    */
+    MMSE_ERR_WORKSPACE = -4,   /* ws_dev NULL / misaligned / ws_bytes too small        */
+    MMSE_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch                     */
+    MMSE_ERR_ALIGN = -6        /* a device pointer is not aligned to its element type  */
+} mmse_status_t;
+
+/* Limits (checked; MMSE_ERR_SIZE / MMSE_ERR_PARAMS otherwise). */
+#define MMSE_MAX_KERNEL_ELEMS 65536      /* n of one weight kernel                     */
+#define MMSE_MAX_GRID_POINTS 2048        /* G                                           */
+#define MMSE_MAX_REFINE_ITERS 64
+#define MMSE_MAX_TENSOR_ELEMS 2147483647 /* K*n and N                                   */
+
+/* Search parameters.
+ *   qmin,qmax     integer range Z_p of Section 3.1: -8,7 (signed INT4) or 0,15
+ *                 (unsigned, no offset term); any qmin <= 0 < qmax with
+ *                 qmax - qmin <= 15 is accepted.
+ *   grid_points   G >= 1 candidates alpha_j = (max|T|/qmax) * (j+1)/G, j = 0..G-1;
+ *                 the last one is the max-abs scale of Section 3.1.
+ *   refine_iters  golden-section iterations applied between the grid neighbours
+ *                 of the argmin (0 = return the grid point).
+ *   cands_per_lane  tuning only, never changes a result: grid candidates each
+ *                 lane of the sweep kernel carries (0 = automatic; 1, 2 or 4). */
+typedef struct mmse_params_t {
+    int32_t qmin, qmax;
+    int32_t grid_points;
+    int32_t refine_iters;
+    int32_t cands_per_lane;
+} mmse_params_t;
+
+/* One weight tensor of a batched call.  Outputs as in mmse_scale_search_kernelwise;
+ * scale1_dev and packed_dev are optional (NULL):
+ *   scale1_dev != NULL  search the residual w - scale1*[w/scale1] (second tensor of
+ *                       Section 3.5) instead of w itself;
+ *   packed_dev != NULL  also emit the packed INT4 codes of the searched tensor. */
+typedef struct mmse_tensor_desc_t {
+    const float *w_dev;        /* [K][n]                                   */
+    int64_t K, n;
+    const float *scale1_dev;   /* [K] or NULL                              */
+    float *scale_dev;          /* [K]                                      */
+    int32_t *idx_dev;          /* [K]                                      */
+    double *sse_dev;           /* [K]                                      */
+    uint8_t *packed_dev;       /* ceil(K*n/2) bytes or NULL                */
+} mmse_tensor_desc_t;
+
+/* Workspace sizes (bytes; host call, nothing enqueued).  ws_dev must be aligned
+ * to 256 bytes.  For a batched call pass the sum of K over all tensors as K and
+ * any n. */
+int mmse_workspace_bytes_kernelwise(int64_t K, int64_t n, const mmse_params_t *p, size_t *bytes_out);
+int mmse_workspace_bytes_activation(int64_t N, const mmse_params_t *p, size_t *bytes_out);
+
+/* Kernel-wise search (Sections 3.3-3.4): for every row k of w_dev,
+ *   scale_dev[k]  the chosen alpha_k
+ *   idx_dev[k]    grid argmin j*_k (lowest index among equal minima)
+ *   sse_dev[k]    sum_i (w_ki - alpha_k*[w_ki/alpha_k])^2 at the returned scale. */
+int mmse_scale_search_kernelwise(const float *w_dev, int64_t K, int64_t n, const mmse_params_t *p,
+                                 float *scale_dev, int32_t *idx_dev, double *sse_dev,
+                                 void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Per-layer search for calibration activations (Section 3.7, Eq. 15): one problem
+ * of N elements; scale_dev, idx_dev, sse_dev hold one element each. */
+int mmse_scale_search_activation(const float *x_dev, int64_t N, const mmse_params_t *p,
+                                 float *scale_dev, int32_t *idx_dev, double *sse_dev,
+                                 void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Q = [x/scale]_Zp (Section 3.4) for a [K][n] tensor with one scale per row, packed
+ * two codes per byte in memory order over the whole tensor: element 2m in the low
+ * nibble of byte m, element 2m+1 in the high nibble, two's-complement nibbles, a
+ * missing last element leaves the high nibble 0.  packed_dev: ceil(K*n/2) bytes.
+ * (The paper defines no storage layout; this one is this library's.) */
+int quantize_pack_int4(const float *x_dev, int64_t K, int64_t n, const float *scale_dev,
+                       int32_t qmin, int32_t qmax, uint8_t *packed_dev, void *stream);
+
+/* Second tensor for a key layer (Section 3.5, Algorithm 1 with j = 2 after j = 1;
+ * same mechanism as Eq. 16): R = w - scale1*[w/scale1] is formed on the fly, then
+ * searched and coded exactly like a weight tensor.  packed2_dev may be NULL. */
+int residual_quantize(const float *w_dev, int64_t K, int64_t n, const float *scale1_dev,
+                      const mmse_params_t *p, float *scale2_dev, int32_t *idx2_dev, double *sse2_dev,
+                      uint8_t *packed2_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Whole network in a handful of launches: `count` weight tensors described in HOST
+ * memory (the descriptors are consumed before the call returns).  Semantics per
+ * tensor are those of mmse_scale_search_kernelwise / residual_quantize /
+ * quantize_pack_int4.  Workspace: mmse_workspace_bytes_kernelwise(sum K, ...). */
+int mmse_scale_search_batched(const mmse_tensor_desc_t *descs_host, int32_t count,
+                              const mmse_params_t *p, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* The grid evaluation alone (the f(alpha_j) of Eq. 8 for every candidate):
+ * absmax_dev[k] = max_i |w_ki|, grid_sse_dev[k*G + j] = f_k(alpha_kj).  Used to
+ * check and to time the candidate sweep by itself. */
+int mmse_grid_sse_kernelwise(const float *w_dev, int64_t K, int64_t n, const mmse_params_t *p,
+                             float *absmax_dev, double *grid_sse_dev, void *stream);
+
+const char *mmse_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMSE_H_ */

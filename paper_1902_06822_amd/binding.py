@@ -1,0 +1,233 @@
+"""Thin ctypes binding of ``libmmse_hip.so`` (see ``include/mmse.h``).
+
+Argument marshalling only: every step of the search runs in the HIP kernels.
+PyTorch supplies device memory and the current stream.  There is no CPU
+fallback: if the library is missing, or a call fails, a RuntimeError is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch  # loaded first so that the HIP runtime torch ships is the one the library binds to
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmmse_hip.so")
+
+EXPORTS = (
+    "mmse_workspace_bytes_kernelwise", "mmse_workspace_bytes_activation",
+    "mmse_scale_search_kernelwise", "mmse_scale_search_activation",
+    "quantize_pack_int4", "residual_quantize", "mmse_scale_search_batched",
+    "mmse_grid_sse_kernelwise", "mmse_status_string",
+)
+
+
+class MmseParams(C.Structure):
+    _fields_ = [("qmin", C.c_int32), ("qmax", C.c_int32), ("grid_points", C.c_int32),
+                ("refine_iters", C.c_int32), ("cands_per_lane", C.c_int32)]
+
+
+class MmseTensorDesc(C.Structure):
+    _fields_ = [("w_dev", C.c_void_p), ("K", C.c_int64), ("n", C.c_int64),
+                ("scale1_dev", C.c_void_p), ("scale_dev", C.c_void_p), ("idx_dev", C.c_void_p),
+                ("sse_dev", C.c_void_p), ("packed_dev", C.c_void_p)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load the HIP library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1902_06822_amd.build` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, i32, szp = C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_size_t)
+    pp = C.POINTER(MmseParams)
+    lib.mmse_workspace_bytes_kernelwise.argtypes = [i64, i64, pp, szp]
+    lib.mmse_workspace_bytes_activation.argtypes = [i64, pp, szp]
+    lib.mmse_scale_search_kernelwise.argtypes = [vp, i64, i64, pp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.mmse_scale_search_activation.argtypes = [vp, i64, pp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.quantize_pack_int4.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp]
+    lib.residual_quantize.argtypes = [vp, i64, i64, vp, pp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.mmse_scale_search_batched.argtypes = [C.POINTER(MmseTensorDesc), i32, pp, vp, C.c_size_t, vp]
+    lib.mmse_grid_sse_kernelwise.argtypes = [vp, i64, i64, pp, vp, vp, vp]
+    lib.mmse_status_string.argtypes = [C.c_int]
+    lib.mmse_status_string.restype = C.c_char_p
+    for name in EXPORTS[:-1]:
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(rc: int) -> str:
+    return load_library().mmse_status_string(rc).decode()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise RuntimeError(f"{what} failed: {status_string(rc)} ({rc})")
+
+
+def params(qmin: int, qmax: int, grid_points: int, refine_iters: int, cands_per_lane: int = 0) -> MmseParams:
+    return MmseParams(qmin, qmax, grid_points, refine_iters, cands_per_lane)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"expected a contiguous {dtype} device tensor, got {t.dtype} on {t.device}")
+    return t
+
+
+def mmse_workspace_bytes_kernelwise(K: int, n: int, p: MmseParams) -> int:
+    out = C.c_size_t(0)
+    _check(load_library().mmse_workspace_bytes_kernelwise(K, n, C.byref(p), C.byref(out)),
+           "mmse_workspace_bytes_kernelwise")
+    return out.value
+
+
+def mmse_workspace_bytes_activation(N: int, p: MmseParams) -> int:
+    out = C.c_size_t(0)
+    _check(load_library().mmse_workspace_bytes_activation(N, C.byref(p), C.byref(out)),
+           "mmse_workspace_bytes_activation")
+    return out.value
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+@dataclass
+class SearchResult:
+    scale: torch.Tensor     # fp32 [K]
+    idx: torch.Tensor       # int32 [K]
+    sse: torch.Tensor       # fp64 [K]
+    packed: Optional[torch.Tensor] = None   # uint8 [ceil(K*n/2)]
+
+
+def _outputs(K: int, device) -> SearchResult:
+    return SearchResult(torch.empty(K, dtype=torch.float32, device=device),
+                        torch.empty(K, dtype=torch.int32, device=device),
+                        torch.empty(K, dtype=torch.float64, device=device))
+
+
+def mmse_scale_search_kernelwise(w: torch.Tensor, p: MmseParams, ws: Optional[torch.Tensor] = None,
+                                 out: Optional[SearchResult] = None) -> SearchResult:
+    _dev(w, torch.float32)
+    K, n = w.shape
+    if ws is None:
+        ws = alloc_workspace(mmse_workspace_bytes_kernelwise(K, n, p), w.device)
+    if out is None:
+        out = _outputs(K, w.device)
+    _check(load_library().mmse_scale_search_kernelwise(
+        w.data_ptr(), K, n, C.byref(p), out.scale.data_ptr(), out.idx.data_ptr(), out.sse.data_ptr(),
+        ws.data_ptr(), ws.numel(), _stream()), "mmse_scale_search_kernelwise")
+    return out
+
+
+def mmse_scale_search_activation(x: torch.Tensor, p: MmseParams, ws: Optional[torch.Tensor] = None,
+                                 out: Optional[SearchResult] = None) -> SearchResult:
+    _dev(x, torch.float32)
+    N = x.numel()
+    if ws is None:
+        ws = alloc_workspace(mmse_workspace_bytes_activation(N, p), x.device)
+    if out is None:
+        out = _outputs(1, x.device)
+    _check(load_library().mmse_scale_search_activation(
+        x.data_ptr(), N, C.byref(p), out.scale.data_ptr(), out.idx.data_ptr(), out.sse.data_ptr(),
+        ws.data_ptr(), ws.numel(), _stream()), "mmse_scale_search_activation")
+    return out
+
+
+def quantize_pack_int4(x: torch.Tensor, scale: torch.Tensor, qmin: int, qmax: int,
+                       packed: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(x, torch.float32)
+    _dev(scale, torch.float32)
+    if x.dim() == 1:
+        K, n = 1, x.numel()
+    else:
+        K, n = x.shape
+    if scale.numel() != K:
+        raise ValueError("one scale per row expected")
+    if packed is None:
+        packed = torch.empty((K * n + 1) // 2, dtype=torch.uint8, device=x.device)
+    _check(load_library().quantize_pack_int4(x.data_ptr(), K, n, scale.data_ptr(), qmin, qmax,
+                                             packed.data_ptr(), _stream()), "quantize_pack_int4")
+    return packed
+
+
+def residual_quantize(w: torch.Tensor, scale1: torch.Tensor, p: MmseParams,
+                      ws: Optional[torch.Tensor] = None, want_packed: bool = True) -> SearchResult:
+    _dev(w, torch.float32)
+    _dev(scale1, torch.float32)
+    K, n = w.shape
+    if ws is None:
+        ws = alloc_workspace(mmse_workspace_bytes_kernelwise(K, n, p), w.device)
+    out = _outputs(K, w.device)
+    if want_packed:
+        out.packed = torch.empty((K * n + 1) // 2, dtype=torch.uint8, device=w.device)
+    _check(load_library().residual_quantize(
+        w.data_ptr(), K, n, scale1.data_ptr(), C.byref(p), out.scale.data_ptr(), out.idx.data_ptr(),
+        out.sse.data_ptr(), _ptr(out.packed), ws.data_ptr(), ws.numel(), _stream()), "residual_quantize")
+    return out
+
+
+class BatchedPlan:
+    """Host-side descriptor table for ``mmse_scale_search_batched`` (buffers allocated once)."""
+
+    def __init__(self, weights: Sequence[torch.Tensor], p: MmseParams, want_packed: bool = True,
+                 scale1: Optional[Sequence[Optional[torch.Tensor]]] = None):
+        self.p = p
+        self.weights = list(weights)
+        self.results: List[SearchResult] = []
+        descs = (MmseTensorDesc * len(self.weights))()
+        sumK = 0
+        for i, w in enumerate(self.weights):
+            _dev(w, torch.float32)
+            K, n = w.shape
+            r = _outputs(K, w.device)
+            if want_packed:
+                r.packed = torch.empty((K * n + 1) // 2, dtype=torch.uint8, device=w.device)
+            self.results.append(r)
+            s1 = None if scale1 is None else scale1[i]
+            descs[i] = MmseTensorDesc(w.data_ptr(), K, n, _ptr(s1), r.scale.data_ptr(), r.idx.data_ptr(),
+                                      r.sse.data_ptr(), _ptr(r.packed))
+            sumK += K
+        self._scale1 = scale1
+        self.descs = descs
+        self.ws = alloc_workspace(mmse_workspace_bytes_kernelwise(sumK, 1, p), self.weights[0].device)
+
+    def run(self) -> List[SearchResult]:
+        _check(load_library().mmse_scale_search_batched(self.descs, len(self.weights), C.byref(self.p),
+                                                        self.ws.data_ptr(), self.ws.numel(), _stream()),
+               "mmse_scale_search_batched")
+        return self.results
+
+
+def mmse_scale_search_batched(weights: Sequence[torch.Tensor], p: MmseParams, want_packed: bool = True,
+                              scale1: Optional[Sequence[Optional[torch.Tensor]]] = None) -> List[SearchResult]:
+    return BatchedPlan(weights, p, want_packed, scale1).run()
+
+
+def mmse_grid_sse_kernelwise(w: torch.Tensor, p: MmseParams):
+    _dev(w, torch.float32)
+    K, n = w.shape
+    absmax = torch.empty(K, dtype=torch.float32, device=w.device)
+    grid = torch.empty((K, p.grid_points), dtype=torch.float64, device=w.device)
+    _check(load_library().mmse_grid_sse_kernelwise(w.data_ptr(), K, n, C.byref(p), absmax.data_ptr(),
+                                                   grid.data_ptr(), _stream()), "mmse_grid_sse_kernelwise")
+    return absmax, grid

@@ -1,0 +1,1156 @@
+// mmse_kernels.hip -- gfx950 (MI355X) kernels and C ABI of the MMSE INT4 scale search.
+//
+// Method: arXiv 1902.06822.  For a tensor T and integer range Z_p the scale alpha
+// minimises f(alpha) = sum_i (T_i - alpha*[T_i/alpha]_Zp)^2 (Section 3.4, Eq. 7-8),
+// found by evaluating f on a grid of G candidates in parallel and taking the argmin;
+// weights are searched per output-channel kernel (Section 3.3), activations per
+// layer (Section 3.7, Eq. 15); the residual of a first fit can be fitted again
+// (Section 3.5, Algorithm 1; Eq. 16).
+//
+// Arithmetic contract (what every kernel below computes, bit for bit):
+//   inv = 1.0f/alpha;  q = clamp(rint(x*inv), qmin, qmax);  r = fma(-alpha, q, x);
+//   s   = fma(r, r, s) sequentially over a chunk of 64 consecutive elements (fp32);
+//   f   = pairwise fp64 sum of the chunk sums (adjacent pairs, level by level; a value
+//         without a partner is carried up unchanged).
+// Chunk sums are >= +0, so padding a chunk with zeros or a tree level with 0.0 never
+// changes a bit; the kernels use that freely.  Nothing is ever accumulated with
+// floating-point atomics: every result is independent of scheduling.
+//
+// Kernel map
+//   k_sweep_kernelwise   one workgroup per weight kernel: slice staged in LDS (abs-max
+//                        and the optional residual transform fused into the staging),
+//                        waves split the grid, lanes own candidates, elements are
+//                        broadcast from LDS; binary-counter tree of fp64 partials in
+//                        registers; argmin with lowest-index tie-break.
+//   k_refine_kernelwise  golden-section refinement, lane = (kernel, 64-element chunk)
+//                        packed densely so that 9-element depthwise kernels use one
+//                        lane each; chunk held in registers across the 22 probes.
+//   k_pack_int4          fused quantize + INT4 pack, 8 elements per thread.
+//   k_act_*              one activation tensor spread over the whole GPU.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <limits.h>
+
+#include "mmse.h"
+
+namespace {
+
+constexpr int kChunk = 64;             // elements per sequential fp32 chunk
+constexpr int kMaxBatch = 32;          // tensors per launch (descriptor table lives in kernarg)
+constexpr int kTile = 8192;            // floats of one kernel staged in LDS at a time
+constexpr int kLevelsKW = 11;          // binary-counter levels for <= 1024 chunks
+constexpr int kBlockChunks = 64;       // activation block = 64 chunks = 4096 elements
+constexpr int kBlockElems = kBlockChunks * kChunk;
+constexpr int kLevelsBlk = 7;          // levels for 64 chunks
+constexpr float kTiny = 0x1p-60f;
+constexpr float kHuge = 0x1p+60f;
+constexpr float kPhi = 0.6180339887f;
+constexpr int kPackPerThread = 8;
+constexpr int kPackThreads = 256;
+
+struct TensorArgs {
+    const float* w;
+    const float* scale1;     // nullptr, or first-tensor scales (search/pack the residual)
+    float* scale;
+    int32_t* idx;
+    double* sse;
+    float* absmax;           // workspace [K]
+    double* grid_sse;        // optional [K][G]
+    uint8_t* packed;
+    int K;
+    int n;
+};
+
+struct Batch {
+    TensorArgs t[kMaxBatch];
+    int start[kMaxBatch + 1];   // prefix sum of workgroups per tensor
+    int count;
+    int G;
+    int qmax;
+    int iters;
+    float lo, hi;               // (float)qmin, (float)qmax
+};
+
+// ---------------------------------------------------------------------------------
+// element arithmetic
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float code_of(float x, float inv, float lo, float hi)
+{
+    return __builtin_amdgcn_fmed3f(__builtin_rintf(x * inv), lo, hi);
+}
+
+__device__ __forceinline__ float sq_err_acc(float x, float alpha, float inv, float lo, float hi, float s)
+{
+    const float q = code_of(x, inv, lo, hi);
+    const float r = __builtin_fmaf(-alpha, q, x);
+    return __builtin_fmaf(r, r, s);
+}
+
+// Grid candidate j: (absmax/qmax) * ((j+1)/G), three correctly rounded fp32 operations.
+__device__ __forceinline__ float grid_alpha(float absmax, float qmaxf, float Gf, int j)
+{
+    const float smax = absmax / qmaxf;
+    const float frac = (float)(j + 1) / Gf;
+    return smax * frac;
+}
+
+// One input element, optionally turned into the residual of a first quantization.
+__device__ __forceinline__ float residual_of(float v, bool resid, float s1, float inv1, float lo, float hi)
+{
+    if (resid) v = __builtin_fmaf(-s1, code_of(v, inv1, lo, hi), v);
+    return v;
+}
+
+__device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned o = (unsigned)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// (value, index) minimum over a wave; the lower index wins among equal values.
+__device__ __forceinline__ void wave_argmin(double& e, int& j)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double oe = __shfl_xor(e, off, 64);
+        const int oj = __shfl_xor(j, off, 64);
+        if (oe < e || (oe == e && oj < j)) { e = oe; j = oj; }
+    }
+}
+
+// Binary-counter form of the pairwise sum: after chunk number ci has been pushed,
+// st[.][l] holds the sum of a complete aligned group of 2^l chunks whenever bit l of
+// (ci+1) is set.  ci is wave-uniform, so the ladder is scalar control flow.
+template <int C, int L, int l>
+__device__ __forceinline__ void tree_push_level(double (&st)[C][L], double (&t)[C], unsigned ci)
+{
+    if constexpr (l < L) {
+        if ((ci >> l) & 1u) {
+#pragma unroll
+            for (int u = 0; u < C; ++u) t[u] = st[u][l] + t[u];
+            tree_push_level<C, L, l + 1>(st, t, ci);
+        } else {
+#pragma unroll
+            for (int u = 0; u < C; ++u) st[u][l] = t[u];
+        }
+    }
+}
+
+template <int C, int L>
+__device__ __forceinline__ void tree_push(double (&st)[C][L], double (&t)[C], unsigned ci)
+{
+    tree_push_level<C, L, 0>(st, t, ci);
+}
+
+// Sum of the m chunks pushed so far (carries the unpaired partial groups upward).
+template <int C, int L>
+__device__ __forceinline__ void tree_fold(const double (&st)[C][L], unsigned m, double (&out)[C])
+{
+#pragma unroll
+    for (int u = 0; u < C; ++u) out[u] = 0.0;
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        if ((m >> l) & 1u) {
+#pragma unroll
+            for (int u = 0; u < C; ++u) out[u] = st[u][l] + out[u];
+        }
+    }
+}
+
+// Sweep `nchunks` chunks that sit in LDS at `slice` for the C candidates of this lane.
+template <int C, int L>
+__device__ __forceinline__ void sweep_slice(const float* slice, int nchunks, unsigned& ci,
+                                            const float (&alpha)[C], const float (&inv)[C],
+                                            float lo, float hi, double (&st)[C][L])
+{
+    const float4* s4 = reinterpret_cast<const float4*>(slice);
+    for (int c = 0; c < nchunks; ++c, ++ci) {
+        float s[C];
+#pragma unroll
+        for (int u = 0; u < C; ++u) s[u] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < kChunk / 4; ++e) {
+            const float4 v = s4[c * (kChunk / 4) + e];     // same address in every lane: LDS broadcast
+#pragma unroll
+            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.x, alpha[u], inv[u], lo, hi, s[u]);
+#pragma unroll
+            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.y, alpha[u], inv[u], lo, hi, s[u]);
+#pragma unroll
+            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.z, alpha[u], inv[u], lo, hi, s[u]);
+#pragma unroll
+            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.w, alpha[u], inv[u], lo, hi, s[u]);
+        }
+        double t[C];
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[u] = (double)s[u];
+        tree_push<C, L>(st, t, ci);
+    }
+}
+
+__device__ __forceinline__ int find_tensor(const Batch& B, int bid)
+{
+    int t = 0;
+    while (t + 1 < B.count && bid >= B.start[t + 1]) ++t;
+    return t;
+}
+
+// ---------------------------------------------------------------------------------
+// k_sweep_kernelwise: abs-max + grid sweep + argmin, one workgroup per weight kernel
+// ---------------------------------------------------------------------------------
+template <int C>
+__global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
+{
+    extern __shared__ float4 smem4[];
+    float* slice = reinterpret_cast<float*>(smem4);
+    __shared__ unsigned s_amax[16];
+    __shared__ double s_bestE[16];
+    __shared__ int s_bestJ[16];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+    const int t = find_tensor(B, blockIdx.x);
+    const TensorArgs& A = B.t[t];
+    const int k = blockIdx.x - B.start[t];
+    const int n = A.n;
+    const float* __restrict__ src = A.w + (size_t)k * n;
+    const float lo = B.lo, hi = B.hi;
+    const bool resid = A.scale1 != nullptr;
+    float s1 = 1.0f, inv1 = 1.0f;
+    if (resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+
+    const int npad = (n + kChunk - 1) & ~(kChunk - 1);
+    const bool single = npad <= kTile;
+
+    // ---- pass 1: abs-max (and, when the kernel fits one tile, the LDS staging)
+    unsigned amax = 0;
+    if (single) {
+        for (int i = tid; i < npad; i += nthreads) {
+            const float v = residual_of(i < n ? src[i] : 0.0f, resid, s1, inv1, lo, hi);
+            slice[i] = v;
+            const unsigned b = abs_bits(v);
+            amax = b > amax ? b : amax;
+        }
+    } else {
+        for (int i = tid; i < n; i += nthreads) {
+            const unsigned b = abs_bits(residual_of(src[i], resid, s1, inv1, lo, hi));
+            amax = b > amax ? b : amax;
+        }
+    }
+    amax = wave_max_u32(amax);
+    if (lane == 0) s_amax[wave] = amax;
+    __syncthreads();
+    unsigned am = 0;
+    for (int w = 0; w < nwaves; ++w) am = s_amax[w] > am ? s_amax[w] : am;
+    const float a = __uint_as_float(am);      // bit pattern order == value order for |x|; inf/NaN sort last
+
+    const int G = B.G;
+    if (!(a <= kHuge)) {                      // inf, NaN or too large: rejected
+        if (tid == 0) {
+            const float nanf_ = __uint_as_float(0x7fc00000u);
+            if (A.absmax) A.absmax[k] = a;
+            if (A.scale) A.scale[k] = nanf_;
+            if (A.idx) A.idx[k] = -1;
+            if (A.sse) A.sse[k] = (double)nanf_;
+        }
+        if (A.grid_sse)
+            for (int j = tid; j < G; j += nthreads) A.grid_sse[(size_t)k * G + j] = (double)__uint_as_float(0x7fc00000u);
+        return;
+    }
+    const bool tiny = a < kTiny;              // coded as all-zero with scale 1
+    const float qmaxf = (float)B.qmax, Gf = (float)G;
+
+    // ---- candidates of this lane: j = wave*64*C + u*64 + lane
+    float alpha[C], inv[C];
+    int jcand[C];
+#pragma unroll
+    for (int u = 0; u < C; ++u) {
+        const int j = (wave * C + u) * 64 + lane;
+        jcand[u] = j;
+        const int jj = j < G ? j : G - 1;
+        alpha[u] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, jj);
+        inv[u] = 1.0f / alpha[u];
+    }
+
+    // ---- pass 2: sweep
+    double st[C][kLevelsKW];
+#pragma unroll
+    for (int u = 0; u < C; ++u)
+#pragma unroll
+        for (int l = 0; l < kLevelsKW; ++l) st[u][l] = 0.0;
+    unsigned ci = 0;
+    if (single) {
+        sweep_slice<C, kLevelsKW>(slice, npad / kChunk, ci, alpha, inv, lo, hi, st);
+    } else {
+        for (int t0 = 0; t0 < npad; t0 += kTile) {
+            const int tlen = (npad - t0) < kTile ? (npad - t0) : kTile;
+            __syncthreads();
+            for (int i = tid; i < tlen; i += nthreads) {
+                const int gi = t0 + i;
+                slice[i] = residual_of(gi < n ? src[gi] : 0.0f, resid, s1, inv1, lo, hi);
+            }
+            __syncthreads();
+            sweep_slice<C, kLevelsKW>(slice, tlen / kChunk, ci, alpha, inv, lo, hi, st);
+        }
+    }
+    double E[C];
+    tree_fold<C, kLevelsKW>(st, ci, E);
+
+    if (A.grid_sse) {
+#pragma unroll
+        for (int u = 0; u < C; ++u)
+            if (jcand[u] < G) A.grid_sse[(size_t)k * G + jcand[u]] = E[u];
+    }
+
+    // ---- argmin, lowest index among equal minima
+    double bE = __longlong_as_double(0x7ff0000000000000LL);
+    int bJ = INT_MAX;
+#pragma unroll
+    for (int u = 0; u < C; ++u)
+        if (jcand[u] < G && E[u] < bE) { bE = E[u]; bJ = jcand[u]; }
+    wave_argmin(bE, bJ);
+    if (lane == 0) { s_bestE[wave] = bE; s_bestJ[wave] = bJ; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < nwaves; ++w) {
+            const double oe = s_bestE[w];
+            const int oj = s_bestJ[w];
+            if (oe < bE || (oe == bE && oj < bJ)) { bE = oe; bJ = oj; }
+        }
+        if (bJ == INT_MAX) bJ = 0;            // only if every f overflowed to inf
+        if (A.absmax) A.absmax[k] = a;
+        if (A.idx) A.idx[k] = bJ;
+        if (A.sse) A.sse[k] = bE;
+        if (A.scale) A.scale[k] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, bJ);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// k_refine_kernelwise: golden-section refinement between the grid neighbours of j*
+// ---------------------------------------------------------------------------------
+// Pairwise sum across the m lanes (chunks) of one kernel through LDS, three tree levels
+// per barrier.  v: this lane's chunk sum; c: chunk number; l0: first lane of the kernel.
+// All lanes of the workgroup call it together.  `par` alternates the buffer so that
+// a call never overwrites what a slower lane is still reading from the previous call.
+__device__ __forceinline__ double tree_combine(double v, int c, int m, int l0, bool active,
+                                               double (*buf)[1024], int& par)
+{
+    if (m == 1) return v;                     // m is uniform over the workgroup
+    int pb = par;
+    if (active) buf[pb][l0 + c] = v;
+    __syncthreads();
+    int cnt = m;
+    while (cnt > 1) {
+        const int ncnt = (cnt + 7) >> 3;
+        if (active && c < ncnt) {
+            double e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = (8 * c + i < cnt) ? buf[pb][l0 + 8 * c + i] : 0.0;
+            buf[pb ^ 1][l0 + c] = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+        }
+        __syncthreads();
+        pb ^= 1;
+        cnt = ncnt;
+    }
+    par = pb ^ 1;
+    return active ? buf[pb][l0] : 0.0;
+}
+
+template <int CL>   // element slots per lane: 64 (general) or 16 (kernels of <= 16 elements)
+__global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B)
+{
+    __shared__ double buf[2][1024];
+    const int tid = threadIdx.x;
+    const int t = find_tensor(B, blockIdx.x);
+    const TensorArgs& A = B.t[t];
+    const int g = blockIdx.x - B.start[t];
+    const int n = A.n;
+    const int m = (CL == kChunk) ? (n + kChunk - 1) / kChunk : 1;
+    const int cpw = blockDim.x / m;           // kernels per workgroup (host guarantees m <= blockDim)
+    const int ch = tid / m, c = tid - ch * m;
+    const int k = g * cpw + ch;
+    const float lo = B.lo, hi = B.hi;
+    bool active = (ch < cpw) && (k < A.K);
+
+    float a = 0.0f;
+    int j = 0;
+    double Ej = 0.0;
+    if (active) { a = A.absmax[k]; j = A.idx[k]; Ej = A.sse[k]; }
+    if (!(a <= kHuge) || a < kTiny) active = false;       // rejected or all-zero: nothing to refine
+
+    // this lane's chunk, kept in registers for all probes (zeros beyond the end are exact no-ops)
+    float x[CL];
+    {
+        const bool resid = A.scale1 != nullptr;
+        float s1 = 1.0f, inv1 = 1.0f;
+        if (active && resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+        const int e0 = c * kChunk;
+        const int len = active ? ((n - e0) < CL ? (n - e0) : CL) : 0;
+        const float* __restrict__ src = A.w + ((size_t)(active ? k : 0) * n + (active ? e0 : 0));
+        const bool vec = ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) && (len == CL);
+        if (vec) {
+            const float4* s4 = reinterpret_cast<const float4*>(src);
+#pragma unroll
+            for (int i = 0; i < CL / 4; ++i) {
+                const float4 v = s4[i];
+                x[4 * i + 0] = v.x; x[4 * i + 1] = v.y; x[4 * i + 2] = v.z; x[4 * i + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CL; ++i) x[i] = (i < len) ? src[i] : 0.0f;
+        }
+        if (resid) {
+#pragma unroll
+            for (int i = 0; i < CL; ++i) x[i] = residual_of(x[i], true, s1, inv1, lo, hi);
+        }
+    }
+
+    const int G = B.G;
+    const float qmaxf = (float)B.qmax, Gf = (float)G;
+    const int l0 = tid - c;
+    int par = 0;
+
+    auto eval = [&](float alpha) -> double {
+        const float inv = 1.0f / alpha;
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < CL; ++i) s = sq_err_acc(x[i], alpha, inv, lo, hi, s);
+        return tree_combine((double)s, c, m, l0, active, buf, par);
+    };
+
+    const float aj = active ? grid_alpha(a, qmaxf, Gf, j) : 1.0f;
+    float best_a = aj;
+    double best = Ej;
+    if (B.iters > 0) {
+        float lo_a = (!active || j == 0) ? 0.0f : grid_alpha(a, qmaxf, Gf, j - 1);
+        float hi_a = (!active || j == G - 1) ? aj : grid_alpha(a, qmaxf, Gf, j + 1);
+        float w = hi_a - lo_a;
+        float pc = __builtin_fmaf(-kPhi, w, hi_a);
+        float pd = __builtin_fmaf(kPhi, w, lo_a);
+        if (!active) { pc = 1.0f; pd = 1.0f; }
+        double ec = eval(pc);
+        double ed = eval(pd);
+        if (ec < best) { best = ec; best_a = pc; }
+        if (ed < best) { best = ed; best_a = pd; }
+        for (int it = 0; it < B.iters; ++it) {
+            const bool left = ec <= ed;       // keep [lo, d]: the new probe is a new c
+            float probe;
+            if (left) {
+                hi_a = pd; pd = pc; ed = ec;
+                w = hi_a - lo_a;
+                pc = __builtin_fmaf(-kPhi, w, hi_a);
+                probe = pc;
+            } else {
+                lo_a = pc; pc = pd; ec = ed;
+                w = hi_a - lo_a;
+                pd = __builtin_fmaf(kPhi, w, lo_a);
+                probe = pd;
+            }
+            if (!active) probe = 1.0f;
+            const double e = eval(probe);
+            if (left) ec = e; else ed = e;
+            if (e < best) { best = e; best_a = probe; }
+        }
+    }
+    if (active && c == 0) {
+        A.scale[k] = best_a;
+        A.sse[k] = best;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// k_pack_int4: codes [x/scale]_Zp, two per byte in memory order over the whole tensor
+// ---------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
+{
+    const int t = find_tensor(B, blockIdx.x);
+    const TensorArgs& A = B.t[t];
+    const int g = blockIdx.x - B.start[t];
+    const int n = A.n;
+    const long long total = (long long)A.K * n;
+    const long long e0 = ((long long)g * kPackThreads + threadIdx.x) * kPackPerThread;
+    if (e0 >= total) return;
+    const float lo = B.lo, hi = B.hi;
+    const bool resid = A.scale1 != nullptr;
+    const float* __restrict__ src = A.w;
+    const float* __restrict__ scale = A.scale;
+
+    const int cnt = (total - e0) < kPackPerThread ? (int)(total - e0) : kPackPerThread;
+    float v[kPackPerThread];
+    if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+        const float4 p0 = reinterpret_cast<const float4*>(src + e0)[0];
+        const float4 p1 = reinterpret_cast<const float4*>(src + e0)[1];
+        v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w;
+        v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < kPackPerThread; ++i) v[i] = (i < cnt) ? src[e0 + i] : 0.0f;
+    }
+
+    int k = (int)((unsigned)e0 / (unsigned)n);          // K*n < 2^31: 32-bit division is enough
+    int r = (int)((unsigned)e0 - (unsigned)k * (unsigned)n);   // position inside kernel k
+    float inv = 1.0f / scale[k];
+    float s1 = 1.0f, inv1 = 1.0f;
+    if (resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+    unsigned word = 0;
+#pragma unroll
+    for (int i = 0; i < kPackPerThread; ++i) {
+        if (i < cnt) {
+            if (r == n) {                     // crossed into the next kernel
+                r = 0; ++k;
+                inv = 1.0f / scale[k];
+                if (resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+            }
+            const float x = residual_of(v[i], resid, s1, inv1, lo, hi);
+            const int q = (int)code_of(x, inv, lo, hi);
+            word |= ((unsigned)q & 0xFu) << (4 * i);
+            ++r;
+        }
+    }
+    uint8_t* dst = A.packed + (e0 >> 1);
+    if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(A.packed) & 3u) == 0) {
+        *reinterpret_cast<unsigned*>(dst) = word;
+    } else {
+        const int nbytes = (cnt + 1) >> 1;
+        for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// activation tensor: one problem of N elements over the whole GPU
+// ---------------------------------------------------------------------------------
+// Workspace layout (all offsets multiples of 256 bytes):
+//   ActState                              scalars of the search
+//   part0[nb][G] doubles                  per-block tree sums of the grid sweep
+//   part1[ceil(nb/64)][G], part2, ...     upper tree levels, 64 blocks at a time
+//   probe0[nb], probe1[...], ...          same hierarchy for one refinement probe
+struct ActState {
+    unsigned absmax_bits;
+    int status;              // 0 normal, 1 all-zero (scale 1), 2 rejected
+    int j;
+    int it;
+    float absmax;
+    float lo_a, hi_a, pc, pd, probe, best_a;
+    int left;
+    double ec, ed, best;
+};
+
+__global__ void k_act_init(ActState* S)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        S->absmax_bits = 0; S->status = 0; S->j = 0; S->it = 0; S->absmax = 0.0f;
+        S->lo_a = S->hi_a = S->pc = S->pd = S->probe = S->best_a = 1.0f;
+        S->left = 0; S->ec = S->ed = S->best = 0.0;
+    }
+}
+
+__global__ void __launch_bounds__(256) k_act_absmax(const float* __restrict__ x, long long N, ActState* S)
+{
+    __shared__ unsigned s_amax[4];
+    const long long stride = (long long)gridDim.x * blockDim.x * 4;
+    unsigned amax = 0;
+    const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+    for (long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < N; i += stride) {
+        if (aligned && i + 4 <= N) {
+            const float4 v = *reinterpret_cast<const float4*>(x + i);
+            unsigned b = abs_bits(v.x); amax = b > amax ? b : amax;
+            b = abs_bits(v.y); amax = b > amax ? b : amax;
+            b = abs_bits(v.z); amax = b > amax ? b : amax;
+            b = abs_bits(v.w); amax = b > amax ? b : amax;
+        } else {
+            for (int u = 0; u < 4 && i + u < N; ++u) {
+                const unsigned b = abs_bits(x[i + u]);
+                amax = b > amax ? b : amax;
+            }
+        }
+    }
+    amax = wave_max_u32(amax);
+    if ((threadIdx.x & 63) == 0) s_amax[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned am = s_amax[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) am = s_amax[w] > am ? s_amax[w] : am;
+        atomicMax(&S->absmax_bits, am);       // integer max: exact and order-free
+    }
+}
+
+// Grid sweep of one 4096-element block per workgroup; waves split the candidates.
+template <int C>
+__global__ void __launch_bounds__(512) k_act_sweep(const float* __restrict__ x, long long N, int G, int qmax,
+                                                    float lo, float hi, const ActState* S, double* part0)
+{
+    __shared__ float4 slice4[kBlockElems / 4];
+    float* slice = reinterpret_cast<float*>(slice4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const float a = __uint_as_float(S->absmax_bits);
+    if (!(a <= kHuge)) return;                // rejected: k_act_argmin reports it
+    const bool tiny = a < kTiny;
+    const long long base = (long long)blockIdx.x * kBlockElems;
+    const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
+    const int npad = (len + kChunk - 1) & ~(kChunk - 1);
+    for (int i = tid; i < npad; i += nthreads) slice[i] = i < len ? x[base + i] : 0.0f;
+    __syncthreads();
+
+    const float qmaxf = (float)qmax, Gf = (float)G;
+    float alpha[C], inv[C];
+    int jcand[C];
+#pragma unroll
+    for (int u = 0; u < C; ++u) {
+        const int j = (wave * C + u) * 64 + lane;
+        jcand[u] = j;
+        const int jj = j < G ? j : G - 1;
+        alpha[u] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, jj);
+        inv[u] = 1.0f / alpha[u];
+    }
+    double st[C][kLevelsBlk];
+#pragma unroll
+    for (int u = 0; u < C; ++u)
+#pragma unroll
+        for (int l = 0; l < kLevelsBlk; ++l) st[u][l] = 0.0;
+    unsigned ci = 0;
+    sweep_slice<C, kLevelsBlk>(slice, npad / kChunk, ci, alpha, inv, lo, hi, st);
+    double E[C];
+    tree_fold<C, kLevelsBlk>(st, ci, E);
+#pragma unroll
+    for (int u = 0; u < C; ++u)
+        if (jcand[u] < G) part0[(size_t)blockIdx.x * G + jcand[u]] = E[u];
+}
+
+// One tree stage over blocks: out[g][j] = pairwise sum of in[64g .. 64g+63][j].
+// When a stage leaves a single row and fin != nullptr the caller continues with it.
+__global__ void __launch_bounds__(256) k_act_reduce64(const double* __restrict__ in, int rows, int G,
+                                                      double* __restrict__ out)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int g = blockIdx.y;
+    if (j >= G) return;
+    double v[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+        const int r = g * 64 + i;
+        v[i] = r < rows ? in[(size_t)r * G + j] : 0.0;
+    }
+#pragma unroll
+    for (int w = 1; w < 64; w <<= 1)
+#pragma unroll
+        for (int i = 0; i < 64; i += 2 * w) v[i] = v[i] + v[i + w];
+    out[(size_t)g * G + j] = v[0];
+}
+
+// Argmin over the G grid sums (one workgroup) and set-up of the refinement state.
+__global__ void __launch_bounds__(1024) k_act_argmin(const double* __restrict__ tot, int G, int qmax, int iters,
+                                                     ActState* S, float* scale, int32_t* idx, double* sse)
+{
+    __shared__ double s_bestE[16];
+    __shared__ int s_bestJ[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const float a = __uint_as_float(S->absmax_bits);
+    if (!(a <= kHuge)) {
+        if (tid == 0) {
+            const float nanf_ = __uint_as_float(0x7fc00000u);
+            S->status = 2; S->absmax = a;
+            *scale = nanf_; *idx = -1; *sse = (double)nanf_;
+        }
+        return;
+    }
+    double bE = __longlong_as_double(0x7ff0000000000000LL);
+    int bJ = INT_MAX;
+    for (int j = tid; j < G; j += blockDim.x) {
+        const double e = tot[j];
+        if (e < bE) { bE = e; bJ = j; }       // ascending j per thread: strict < keeps the lowest
+    }
+    wave_argmin(bE, bJ);
+    if (lane == 0) { s_bestE[wave] = bE; s_bestJ[wave] = bJ; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < nwaves; ++w) {
+            const double oe = s_bestE[w];
+            const int oj = s_bestJ[w];
+            if (oe < bE || (oe == bE && oj < bJ)) { bE = oe; bJ = oj; }
+        }
+        if (bJ == INT_MAX) bJ = 0;
+        const bool tiny = a < kTiny;
+        const float qmaxf = (float)qmax, Gf = (float)G;
+        const float aj = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, bJ);
+        S->absmax = a; S->j = bJ; S->status = tiny ? 1 : 0; S->it = 0;
+        S->best = bE; S->best_a = aj;
+        *idx = bJ; *scale = aj; *sse = bE;
+        if (!tiny && iters > 0) {
+            const float lo_a = bJ == 0 ? 0.0f : grid_alpha(a, qmaxf, Gf, bJ - 1);
+            const float hi_a = bJ == G - 1 ? aj : grid_alpha(a, qmaxf, Gf, bJ + 1);
+            const float w = hi_a - lo_a;
+            S->lo_a = lo_a; S->hi_a = hi_a;
+            S->pc = __builtin_fmaf(-kPhi, w, hi_a);
+            S->pd = __builtin_fmaf(kPhi, w, lo_a);
+            S->probe = S->pc;
+        }
+    }
+}
+
+// One refinement probe: lane = chunk, wave = block (64 chunks): fp32 chunk sums, then the
+// first six tree levels inside the wave.
+__global__ void __launch_bounds__(256) k_act_probe(const float* __restrict__ x, long long N, float lo, float hi,
+                                                   const ActState* S, double* probe0)
+{
+    if (S->status != 0) return;
+    const float alpha = S->probe;
+    const float inv = 1.0f / alpha;
+    const long long chunk = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long e0 = chunk * kChunk;
+    float s = 0.0f;
+    if (e0 < N) {
+        const float* __restrict__ src = x + e0;
+        const int len = (N - e0) < kChunk ? (int)(N - e0) : kChunk;
+        if (len == kChunk && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+            const float4* s4 = reinterpret_cast<const float4*>(src);
+#pragma unroll
+            for (int i = 0; i < kChunk / 4; ++i) {
+                const float4 v = s4[i];
+                s = sq_err_acc(v.x, alpha, inv, lo, hi, s);
+                s = sq_err_acc(v.y, alpha, inv, lo, hi, s);
+                s = sq_err_acc(v.z, alpha, inv, lo, hi, s);
+                s = sq_err_acc(v.w, alpha, inv, lo, hi, s);
+            }
+        } else {
+            for (int i = 0; i < len; ++i) s = sq_err_acc(src[i], alpha, inv, lo, hi, s);
+        }
+    }
+    double v = (double)s;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) v = v + __shfl_xor(v, off, 64);   // pairwise tree, same in all lanes
+    if ((threadIdx.x & 63) == 0) {
+        const long long blk = chunk >> 6;
+        if (blk * (long long)kBlockElems < N) probe0[blk] = v;
+    }
+}
+
+// Golden-section bookkeeping after the probe value is known (single thread).
+__global__ void k_act_update(const double* __restrict__ tot, int iters, ActState* S, float* scale, double* sse)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0 || S->status != 0) return;
+    const double e = tot[0];
+    const float probe = S->probe;
+    int it = S->it;                           // 0: probe was c0, 1: probe was d0, >= 2: iteration it-2
+    float lo_a = S->lo_a, hi_a = S->hi_a, pc = S->pc, pd = S->pd;
+    double ec = S->ec, ed = S->ed, best = S->best;
+    float best_a = S->best_a;
+    if (it == 0) { ec = e; }
+    else if (it == 1) { ed = e; }
+    else if (S->left) { ec = e; }
+    else { ed = e; }
+    if (e < best) { best = e; best_a = probe; }
+    float next = pd;                          // after c0 comes d0
+    int left = 0;
+    if (it >= 1 && it - 1 < iters) {          // choose the next probe of iteration it-1
+        left = ec <= ed;
+        if (left) {
+            hi_a = pd; pd = pc; ed = ec;
+            const float w = hi_a - lo_a;
+            pc = __builtin_fmaf(-kPhi, w, hi_a);
+            next = pc;
+        } else {
+            lo_a = pc; pc = pd; ec = ed;
+            const float w = hi_a - lo_a;
+            pd = __builtin_fmaf(kPhi, w, lo_a);
+            next = pd;
+        }
+    }
+    S->lo_a = lo_a; S->hi_a = hi_a; S->pc = pc; S->pd = pd; S->ec = ec; S->ed = ed;
+    S->best = best; S->best_a = best_a; S->left = left; S->probe = next; S->it = it + 1;
+    *scale = best_a;
+    *sse = best;
+}
+
+// ---------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int check_params(const mmse_params_t* p)
+{
+    if (!p) return MMSE_ERR_NULL;
+    if (!(p->qmin <= 0 && p->qmax > 0 && p->qmax - p->qmin <= 15)) return MMSE_ERR_PARAMS;
+    if (p->grid_points < 1 || p->grid_points > MMSE_MAX_GRID_POINTS) return MMSE_ERR_PARAMS;
+    if (p->refine_iters < 0 || p->refine_iters > MMSE_MAX_REFINE_ITERS) return MMSE_ERR_PARAMS;
+    const int c = p->cands_per_lane;
+    if (!(c == 0 || c == 1 || c == 2 || c == 4)) return MMSE_ERR_PARAMS;
+    if (c != 0 && (p->grid_points + 64 * c - 1) / (64 * c) > 8) return MMSE_ERR_PARAMS;
+    return MMSE_OK;
+}
+
+int pick_cands(const mmse_params_t* p)
+{
+    if (p->cands_per_lane) return p->cands_per_lane;
+    const int G = p->grid_points;
+    if (G <= 128) return 1;
+    if (G <= 1024) return 2;
+    return 4;
+}
+
+bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_tensor(const mmse_tensor_desc_t& d, bool need_outputs)
+{
+    if (!d.w_dev) return MMSE_ERR_NULL;
+    if (need_outputs && (!d.scale_dev || !d.idx_dev || !d.sse_dev)) return MMSE_ERR_NULL;
+    if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS) return MMSE_ERR_SIZE;
+    if (d.K > MMSE_MAX_TENSOR_ELEMS / d.n) return MMSE_ERR_SIZE;
+    if (!aligned_to(d.w_dev, 4) || !aligned_to(d.scale_dev, 4) || !aligned_to(d.idx_dev, 4) ||
+        !aligned_to(d.sse_dev, 8) || !aligned_to(d.scale1_dev, 4))
+        return MMSE_ERR_ALIGN;
+    return MMSE_OK;
+}
+
+void fill_common(Batch& B, const mmse_params_t* p)
+{
+    B.G = p->grid_points;
+    B.qmax = p->qmax;
+    B.iters = p->refine_iters;
+    B.lo = (float)p->qmin;
+    B.hi = (float)p->qmax;
+}
+
+template <int C>
+int launch_sweep(const Batch& B, int nwg, int G, int max_npad, hipStream_t s)
+{
+    const int waves = (G + 64 * C - 1) / (64 * C);
+    const size_t lds = (size_t)(max_npad < kTile ? max_npad : kTile) * sizeof(float);
+    hipLaunchKernelGGL(k_sweep_kernelwise<C>, dim3(nwg), dim3(64 * waves), lds, s, B);
+    return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+}
+
+int launch_sweep_any(int C, const Batch& B, int nwg, int G, int max_npad, hipStream_t s)
+{
+    if (C == 1) return launch_sweep<1>(B, nwg, G, max_npad, s);
+    if (C == 2) return launch_sweep<2>(B, nwg, G, max_npad, s);
+    return launch_sweep<4>(B, nwg, G, max_npad, s);
+}
+
+struct Item {              // one tensor of a batched call, host side
+    TensorArgs a;
+    int order;
+};
+
+// The three stages for a list of tensors (already validated): sweep, refine, pack.
+int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_search, hipStream_t s)
+{
+    const int G = p->grid_points;
+    const int C = pick_cands(p);
+    // largest kernels first: the hardware dispatcher hands out workgroups in order, so the
+    // long ones start early and the short ones fill the tail.
+    for (int i = 1; i < count; ++i) {
+        Item it = items[i];
+        int j = i - 1;
+        while (j >= 0 && items[j].a.n < it.a.n) { items[j + 1] = items[j]; --j; }
+        items[j + 1] = it;
+    }
+    if (do_search) {
+        for (int b0 = 0; b0 < count; b0 += kMaxBatch) {
+            Batch B{};
+            fill_common(B, p);
+            const int nb = (count - b0) < kMaxBatch ? (count - b0) : kMaxBatch;
+            int wg = 0, max_npad = 0;
+            for (int i = 0; i < nb; ++i) {
+                B.t[i] = items[b0 + i].a;
+                B.start[i] = wg;
+                wg += B.t[i].K;
+                const int npad = (B.t[i].n + kChunk - 1) & ~(kChunk - 1);
+                max_npad = npad > max_npad ? npad : max_npad;
+            }
+            B.start[nb] = wg;
+            B.count = nb;
+            const int rc = launch_sweep_any(C, B, wg, G, max_npad, s);
+            if (rc) return rc;
+        }
+        if (p->refine_iters > 0) {
+            // classes: kernels of <= 16 elements (one lane each, 16 slots), then by lanes per kernel
+            for (int cls = 0; cls < 4; ++cls) {
+                const int threads = cls == 3 ? 1024 : (cls == 2 ? 512 : 256);
+                Batch B{};
+                fill_common(B, p);
+                int nb = 0, wg = 0;
+                auto flush = [&]() -> int {
+                    if (nb == 0) return MMSE_OK;
+                    B.start[nb] = wg;
+                    B.count = nb;
+                    if (cls == 0) hipLaunchKernelGGL(k_refine_kernelwise<16>, dim3(wg), dim3(threads), 0, s, B);
+                    else hipLaunchKernelGGL(k_refine_kernelwise<kChunk>, dim3(wg), dim3(threads), 0, s, B);
+                    nb = 0; wg = 0;
+                    return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+                };
+                for (int i = 0; i < count; ++i) {
+                    const TensorArgs& a = items[i].a;
+                    const int m = (a.n + kChunk - 1) / kChunk;
+                    const int c = a.n <= 16 ? 0 : (m <= 256 ? 1 : (m <= 512 ? 2 : 3));
+                    if (c != cls) continue;
+                    const int lanes = cls == 0 ? 1 : m;
+                    const int cpw = threads / lanes;
+                    B.t[nb] = a;
+                    B.start[nb] = wg;
+                    wg += (a.K + cpw - 1) / cpw;
+                    if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
+                }
+                const int rc = flush();
+                if (rc) return rc;
+            }
+        }
+    }
+    // pack
+    {
+        Batch B{};
+        fill_common(B, p);
+        int nb = 0, wg = 0;
+        auto flush = [&]() -> int {
+            if (nb == 0) return MMSE_OK;
+            B.start[nb] = wg;
+            B.count = nb;
+            hipLaunchKernelGGL(k_pack_int4, dim3(wg), dim3(kPackThreads), 0, s, B);
+            nb = 0; wg = 0;
+            return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+        };
+        for (int i = 0; i < count; ++i) {
+            const TensorArgs& a = items[i].a;
+            if (!a.packed) continue;
+            const long long total = (long long)a.K * a.n;
+            const long long per_wg = (long long)kPackThreads * kPackPerThread;
+            B.t[nb] = a;
+            B.start[nb] = wg;
+            wg += (int)((total + per_wg - 1) / per_wg);
+            if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
+        }
+        const int rc = flush();
+        if (rc) return rc;
+    }
+    return MMSE_OK;
+}
+
+struct ActPlan {
+    int nb;                 // blocks of 4096 elements
+    int levels;             // number of reduce64 stages until one row is left
+    int rows[8];            // rows[0] = nb, rows[i+1] = ceil(rows[i]/64)
+    size_t off_part[8];     // byte offsets of the grid-sum levels
+    size_t off_probe[8];    // byte offsets of the probe levels
+    size_t bytes;
+};
+
+ActPlan plan_activation(long long N, int G)
+{
+    ActPlan P{};
+    P.nb = (int)((N + kBlockElems - 1) / kBlockElems);
+    P.rows[0] = P.nb;
+    P.levels = 0;
+    while (P.rows[P.levels] > 1) { P.rows[P.levels + 1] = (P.rows[P.levels] + 63) / 64; ++P.levels; }
+    size_t off = round256(sizeof(ActState));
+    for (int l = 0; l <= P.levels; ++l) { P.off_part[l] = off; off += round256((size_t)P.rows[l] * G * sizeof(double)); }
+    for (int l = 0; l <= P.levels; ++l) { P.off_probe[l] = off; off += round256((size_t)P.rows[l] * sizeof(double)); }
+    P.bytes = off;
+    return P;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------
+extern "C" {
+
+const char* mmse_status_string(int status)
+{
+    switch (status) {
+        case MMSE_OK: return "ok";
+        case MMSE_ERR_NULL: return "a required pointer is NULL";
+        case MMSE_ERR_SIZE: return "tensor size is not positive or exceeds the documented limits";
+        case MMSE_ERR_PARAMS: return "bad quantization range, grid size, refinement count or tuning value";
+        case MMSE_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
+        case MMSE_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+        case MMSE_ERR_ALIGN: return "a device pointer is not aligned to its element type";
+        default: return "unknown status";
+    }
+}
+
+int mmse_workspace_bytes_kernelwise(int64_t K, int64_t n, const mmse_params_t* p, size_t* bytes_out)
+{
+    if (!bytes_out) return MMSE_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc) return rc;
+    if (K <= 0 || n <= 0 || K > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
+    *bytes_out = round256((size_t)K * sizeof(float));
+    return MMSE_OK;
+}
+
+int mmse_workspace_bytes_activation(int64_t N, const mmse_params_t* p, size_t* bytes_out)
+{
+    if (!bytes_out) return MMSE_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc) return rc;
+    if (N <= 0 || N > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
+    *bytes_out = plan_activation(N, p->grid_points).bytes;
+    return MMSE_OK;
+}
+
+int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t count, const mmse_params_t* p,
+                              void* ws_dev, size_t ws_bytes, void* stream)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (!descs_host) return MMSE_ERR_NULL;
+    if (count <= 0 || count > 4096) return MMSE_ERR_SIZE;
+    long long sumK = 0;
+    for (int i = 0; i < count; ++i) {
+        rc = check_tensor(descs_host[i], true);
+        if (rc) return rc;
+        sumK += descs_host[i].K;
+    }
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < round256((size_t)sumK * sizeof(float)))
+        return MMSE_ERR_WORKSPACE;
+    Item* items = new Item[count];
+    float* ws = static_cast<float*>(ws_dev);
+    long long off = 0;
+    for (int i = 0; i < count; ++i) {
+        const mmse_tensor_desc_t& d = descs_host[i];
+        TensorArgs& a = items[i].a;
+        a.w = d.w_dev; a.scale1 = d.scale1_dev; a.scale = d.scale_dev; a.idx = d.idx_dev; a.sse = d.sse_dev;
+        a.absmax = ws + off; a.grid_sse = nullptr; a.packed = d.packed_dev;
+        a.K = (int)d.K; a.n = (int)d.n;
+        items[i].order = i;
+        off += d.K;
+    }
+    rc = run_weight_tensors(items, count, p, true, static_cast<hipStream_t>(stream));
+    delete[] items;
+    return rc;
+}
+
+int mmse_scale_search_kernelwise(const float* w_dev, int64_t K, int64_t n, const mmse_params_t* p,
+                                 float* scale_dev, int32_t* idx_dev, double* sse_dev,
+                                 void* ws_dev, size_t ws_bytes, void* stream)
+{
+    mmse_tensor_desc_t d{};
+    d.w_dev = w_dev; d.K = K; d.n = n; d.scale1_dev = nullptr;
+    d.scale_dev = scale_dev; d.idx_dev = idx_dev; d.sse_dev = sse_dev; d.packed_dev = nullptr;
+    return mmse_scale_search_batched(&d, 1, p, ws_dev, ws_bytes, stream);
+}
+
+int residual_quantize(const float* w_dev, int64_t K, int64_t n, const float* scale1_dev,
+                      const mmse_params_t* p, float* scale2_dev, int32_t* idx2_dev, double* sse2_dev,
+                      uint8_t* packed2_dev, void* ws_dev, size_t ws_bytes, void* stream)
+{
+    if (!scale1_dev) return MMSE_ERR_NULL;
+    mmse_tensor_desc_t d{};
+    d.w_dev = w_dev; d.K = K; d.n = n; d.scale1_dev = scale1_dev;
+    d.scale_dev = scale2_dev; d.idx_dev = idx2_dev; d.sse_dev = sse2_dev; d.packed_dev = packed2_dev;
+    return mmse_scale_search_batched(&d, 1, p, ws_dev, ws_bytes, stream);
+}
+
+int quantize_pack_int4(const float* x_dev, int64_t K, int64_t n, const float* scale_dev,
+                       int32_t qmin, int32_t qmax, uint8_t* packed_dev, void* stream)
+{
+    if (!x_dev || !scale_dev || !packed_dev) return MMSE_ERR_NULL;
+    if (K <= 0 || n <= 0 || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (!(qmin <= 0 && qmax > 0 && qmax - qmin <= 15)) return MMSE_ERR_PARAMS;
+    if (!aligned_to(x_dev, 4) || !aligned_to(scale_dev, 4)) return MMSE_ERR_ALIGN;
+    mmse_params_t p{qmin, qmax, 1, 0, 0};
+    Item it{};
+    it.a.w = x_dev; it.a.scale = const_cast<float*>(scale_dev); it.a.packed = packed_dev;
+    it.a.K = (int)K; it.a.n = (int)n;
+    // the pack kernel indexes by flat element, so any n is fine here (one activation tensor is K = 1)
+    return run_weight_tensors(&it, 1, &p, false, static_cast<hipStream_t>(stream));
+}
+
+int mmse_grid_sse_kernelwise(const float* w_dev, int64_t K, int64_t n, const mmse_params_t* p,
+                             float* absmax_dev, double* grid_sse_dev, void* stream)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (!w_dev || !absmax_dev || !grid_sse_dev) return MMSE_ERR_NULL;
+    mmse_tensor_desc_t d{};
+    d.w_dev = w_dev; d.K = K; d.n = n;
+    rc = check_tensor(d, false);
+    if (rc) return rc;
+    if (!aligned_to(absmax_dev, 4) || !aligned_to(grid_sse_dev, 8)) return MMSE_ERR_ALIGN;
+    mmse_params_t q = *p;
+    q.refine_iters = 0;
+    Item it{};
+    it.a.w = w_dev; it.a.absmax = absmax_dev; it.a.grid_sse = grid_sse_dev;
+    it.a.K = (int)K; it.a.n = (int)n;
+    return run_weight_tensors(&it, 1, &q, true, static_cast<hipStream_t>(stream));
+}
+
+int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_params_t* p,
+                                 float* scale_dev, int32_t* idx_dev, double* sse_dev,
+                                 void* ws_dev, size_t ws_bytes, void* stream)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (!x_dev || !scale_dev || !idx_dev || !sse_dev) return MMSE_ERR_NULL;
+    if (N <= 0 || N > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
+    if (!aligned_to(x_dev, 4) || !aligned_to(scale_dev, 4) || !aligned_to(idx_dev, 4) || !aligned_to(sse_dev, 8))
+        return MMSE_ERR_ALIGN;
+    const int G = p->grid_points;
+    const ActPlan P = plan_activation(N, G);
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < P.bytes) return MMSE_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(ws_dev);
+    ActState* S = reinterpret_cast<ActState*>(ws);
+    const float lo = (float)p->qmin, hi = (float)p->qmax;
+#define MMSE_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH; } while (0)
+
+    hipLaunchKernelGGL(k_act_init, dim3(1), dim3(64), 0, s, S);
+    MMSE_CHECK_LAUNCH();
+    {
+        long long want = (N + 1023) / 1024;               // 256 threads x 4 elements per pass
+        const int grid = (int)(want < 2048 ? (want < 1 ? 1 : want) : 2048);
+        hipLaunchKernelGGL(k_act_absmax, dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S);
+        MMSE_CHECK_LAUNCH();
+    }
+    {
+        const int C = pick_cands(p);
+        const int waves = (G + 64 * C - 1) / (64 * C);
+        double* part0 = reinterpret_cast<double*>(ws + P.off_part[0]);
+        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0);
+        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0);
+        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0);
+        MMSE_CHECK_LAUNCH();
+    }
+    for (int l = 0; l < P.levels; ++l) {
+        hipLaunchKernelGGL(k_act_reduce64, dim3((G + 255) / 256, P.rows[l + 1]), dim3(256), 0, s,
+                           reinterpret_cast<const double*>(ws + P.off_part[l]), P.rows[l], G,
+                           reinterpret_cast<double*>(ws + P.off_part[l + 1]));
+        MMSE_CHECK_LAUNCH();
+    }
+    {
+        int threads = ((G + 63) / 64) * 64;
+        if (threads > 1024) threads = 1024;
+        hipLaunchKernelGGL(k_act_argmin, dim3(1), dim3(threads), 0, s,
+                           reinterpret_cast<const double*>(ws + P.off_part[P.levels]), G, p->qmax, p->refine_iters,
+                           S, scale_dev, idx_dev, sse_dev);
+        MMSE_CHECK_LAUNCH();
+    }
+    if (p->refine_iters > 0) {
+        const long long nchunks = (N + kChunk - 1) / kChunk;
+        const int pgrid = (int)((nchunks + 255) / 256);
+        for (int e = 0; e < 2 + p->refine_iters; ++e) {
+            hipLaunchKernelGGL(k_act_probe, dim3(pgrid), dim3(256), 0, s, x_dev, (long long)N, lo, hi, S,
+                               reinterpret_cast<double*>(ws + P.off_probe[0]));
+            MMSE_CHECK_LAUNCH();
+            for (int l = 0; l < P.levels; ++l) {
+                hipLaunchKernelGGL(k_act_reduce64, dim3(1, P.rows[l + 1]), dim3(64), 0, s,
+                                   reinterpret_cast<const double*>(ws + P.off_probe[l]), P.rows[l], 1,
+                                   reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
+                MMSE_CHECK_LAUNCH();
+            }
+            hipLaunchKernelGGL(k_act_update, dim3(1), dim3(64), 0, s,
+                               reinterpret_cast<const double*>(ws + P.off_probe[P.levels]), p->refine_iters,
+                               S, scale_dev, sse_dev);
+            MMSE_CHECK_LAUNCH();
+        }
+    }
+#undef MMSE_CHECK_LAUNCH
+    return MMSE_OK;
+}
+
+}  // extern "C"

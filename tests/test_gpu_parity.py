@@ -1,0 +1,256 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars (from the benchmark spec): INT4 codes and grid argmin indices bit-exact, scales
+within 1e-6 relative, squared errors within 1e-4 relative.  Because both sides follow
+the same written arithmetic, scale and error are in fact compared for exact equality
+first; the tolerance form is what is asserted if that ever has to be relaxed.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1902_06822_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+SIGNED = (-8, 7)
+UNSIGNED = (0, 15)
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1902_06822_amd import binding
+    binding.load_library()          # fail loudly if the HIP library is missing
+    return binding
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def to_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def assert_search_equal(got_scale, got_idx, got_sse, ref_scale, ref_idx, ref_sse, tag=""):
+    got_scale, got_idx, got_sse = (np.asarray(v) for v in (got_scale, got_idx, got_sse))
+    np.testing.assert_array_equal(got_idx, ref_idx, err_msg=f"argmin index {tag}")
+    # the bars
+    np.testing.assert_allclose(got_scale, ref_scale, rtol=1e-6, atol=0, err_msg=f"scale {tag}")
+    np.testing.assert_allclose(got_sse, ref_sse, rtol=1e-4, atol=0, err_msg=f"sse {tag}")
+    # and the stronger statement that holds by construction
+    np.testing.assert_array_equal(got_scale.view(np.uint32), np.asarray(ref_scale).view(np.uint32),
+                                  err_msg=f"scale bits {tag}")
+    np.testing.assert_array_equal(got_sse, ref_sse, err_msg=f"sse bits {tag}")
+
+
+# ------------------------------------------------------------------ grid sweep alone
+@pytest.mark.parametrize("K,n", [(3, 9), (5, 27), (4, 64), (3, 147), (6, 576), (2, 4608), (2, 8192),
+                                 (2, 8256), (1, 25088), (1, 65536), (7, 1), (3, 130)])
+@pytest.mark.parametrize("G,cpl", [(128, 1), (256, 2), (256, 4), (500, 2), (50, 1)])
+def test_grid_sweep_matches_oracle(B, K, n, G, cpl):
+    say(f"grid_sse K={K} n={n} G={G} cpl={cpl}")
+    w = synth.small_weights(K, n, 1000 + K * 7 + n, "laplace")
+    p = B.params(*SIGNED, G, 0, cpl)
+    absmax, grid = B.mmse_grid_sse_kernelwise(to_dev(w), p)
+    absmax, grid = absmax.cpu().numpy(), grid.cpu().numpy()
+    for k in range(K):
+        r = oracle.can_search(w[k], *SIGNED, G, 0, want_grid=True)
+        assert absmax[k] == oracle.can_absmax(w[k])
+        np.testing.assert_array_equal(grid[k], r["grid_sse"], err_msg=f"k={k}")
+
+
+# ------------------------------------------------------------------ kernel-wise search
+@pytest.mark.parametrize("K,n,kind", [(130, 9, "outliers"), (70, 27, "normal"), (33, 147, "laplace"),
+                                      (64, 576, "normal"), (20, 1152, "student"), (9, 4608, "laplace"),
+                                      (3, 25088, "laplace"), (5, 16, "laplace"), (5, 17, "laplace"),
+                                      (300, 64, "normal"), (11, 100, "student"), (2, 40000, "laplace"),
+                                      (1, 65536, "laplace")])
+def test_kernelwise_search_matches_oracle(B, K, n, kind):
+    say(f"kernelwise K={K} n={n} kind={kind}")
+    w = synth.small_weights(K, n, 2000 + K + n, kind)
+    G = 256
+    p = B.params(*SIGNED, G, 20)
+    r = B.mmse_scale_search_kernelwise(to_dev(w), p)
+    s, i, e = oracle.can_search_kernelwise(w, *SIGNED, G, 20)
+    assert_search_equal(r.scale.cpu().numpy(), r.idx.cpu().numpy(), r.sse.cpu().numpy(), s, i, e)
+
+
+@pytest.mark.parametrize("G,iters,qr", [(128, 20, SIGNED), (500, 20, SIGNED), (50, 20, UNSIGNED),
+                                        (256, 0, SIGNED), (512, 20, UNSIGNED), (1, 5, SIGNED),
+                                        (2048, 3, SIGNED), (64, 64, SIGNED)])
+def test_kernelwise_parameters(B, G, iters, qr):
+    say(f"kernelwise params G={G} iters={iters} range={qr}")
+    w = synth.small_weights(24, 321, 31 + G, "student")
+    if qr == UNSIGNED:
+        w = np.maximum(w, 0)
+    p = B.params(*qr, G, iters)
+    r = B.mmse_scale_search_kernelwise(to_dev(w), p)
+    s, i, e = oracle.can_search_kernelwise(w, *qr, G, iters)
+    assert_search_equal(r.scale.cpu().numpy(), r.idx.cpu().numpy(), r.sse.cpu().numpy(), s, i, e)
+
+
+def test_kernelwise_degenerate_rows(B):
+    say("kernelwise degenerate rows")
+    w = synth.small_weights(8, 200, 5, "normal")
+    w[1] = 0.0                       # all-zero kernel
+    w[2] = 1e-25                     # below the 2^-60 threshold
+    w[3, 17] = np.inf                # rejected
+    w[4, 3] = np.nan                 # rejected
+    w[5] = 0.375                     # constant
+    w[6] = np.array([-7, 0] * 100, np.float32) * 0.25     # exact tie between two grid points (G=256)
+    p = B.params(*SIGNED, 256, 20)
+    r = B.mmse_scale_search_kernelwise(to_dev(w), p)
+    gs, gi, ge = r.scale.cpu().numpy(), r.idx.cpu().numpy(), r.sse.cpu().numpy()
+    for k in range(8):
+        o = oracle.can_search(w[k], *SIGNED, 256, 20)
+        assert gi[k] == o["idx"], k
+        if o["rc"] != 0:
+            assert np.isnan(gs[k]) and np.isnan(ge[k]) and gi[k] == -1
+        else:
+            assert gs[k] == o["scale"] and ge[k] == o["sse"], k
+    assert gi[6] == 7 * 256 // 8 - 1 and ge[6] == 0.0
+    assert gs[1] == 1.0 and ge[1] == 0.0 and gs[2] == 1.0
+
+
+def test_on_grid_and_scaling_metamorphism(B):
+    say("on-grid + power-of-two scaling")
+    w, q = synth.on_grid_tensor(16, 576, 3, 2.0 ** -7, -7, 7)
+    p = B.params(*SIGNED, 256, 20)
+    r = B.mmse_scale_search_kernelwise(to_dev(w), p)
+    assert np.all(r.idx.cpu().numpy() == 255)
+    assert np.all(r.scale.cpu().numpy() == np.float32(2.0 ** -7))
+    assert np.all(r.sse.cpu().numpy() == 0.0)
+    w = synth.small_weights(10, 300, 8, "laplace")
+    r0 = B.mmse_scale_search_kernelwise(to_dev(w), p)
+    r1 = B.mmse_scale_search_kernelwise(to_dev(w * np.float32(2.0 ** 5)), p)
+    np.testing.assert_array_equal(r0.idx.cpu().numpy(), r1.idx.cpu().numpy())
+    np.testing.assert_array_equal(r0.scale.cpu().numpy() * np.float32(32), r1.scale.cpu().numpy())
+    np.testing.assert_array_equal(r0.sse.cpu().numpy() * 1024.0, r1.sse.cpu().numpy())
+
+
+# ------------------------------------------------------------------ codes and packing
+@pytest.mark.parametrize("K,n", [(1, 1), (3, 9), (5, 27), (7, 147), (64, 576), (3, 4099), (1, 100001),
+                                 (2049, 1), (9, 2305)])
+@pytest.mark.parametrize("qr", [SIGNED, UNSIGNED])
+def test_quantize_pack_matches_oracle(B, K, n, qr):
+    say(f"pack K={K} n={n} range={qr}")
+    w = synth.small_weights(K, n, 3000 + K + n, "outliers")
+    if qr == UNSIGNED:
+        w = np.abs(w)
+    s, _, _ = oracle.can_search_kernelwise(w, *qr, 64, 5)
+    got = B.quantize_pack_int4(to_dev(w), to_dev(s), *qr).cpu().numpy()
+    ref = oracle.can_quantize_pack_int4(w, s, *qr)
+    np.testing.assert_array_equal(got, ref)
+
+
+def test_quantize_pack_unaligned_views(B):
+    """Input and output that are only 4-byte / 1-byte aligned take the scalar paths."""
+    say("pack unaligned")
+    import torch
+    w = synth.small_weights(5, 333, 77, "laplace")
+    s, _, _ = oracle.can_search_kernelwise(w, *SIGNED, 64, 5)
+    buf = torch.zeros(w.size + 3, dtype=torch.float32, device="cuda")
+    buf[1:1 + w.size] = to_dev(w).ravel()
+    wv = buf[1:1 + w.size].view(5, 333)
+    out = torch.zeros((w.size + 1) // 2 + 3, dtype=torch.uint8, device="cuda")
+    B.quantize_pack_int4(wv, to_dev(s), *SIGNED, packed=out[1:1 + (w.size + 1) // 2])
+    np.testing.assert_array_equal(out[1:1 + (w.size + 1) // 2].cpu().numpy(),
+                                  oracle.can_quantize_pack_int4(w, s, *SIGNED))
+    assert out[0] == 0 and out[-1] == 0 and out[-2] == 0
+
+
+# ------------------------------------------------------------------ residual (second tensor)
+@pytest.mark.parametrize("K,n", [(40, 9), (12, 147), (32, 576), (4, 4608), (2, 25088)])
+def test_residual_quantize_matches_oracle(B, K, n):
+    say(f"residual K={K} n={n}")
+    w = synth.small_weights(K, n, 4000 + K + n, "student")
+    G = 256
+    p = B.params(*SIGNED, G, 20)
+    wd = to_dev(w)
+    r1 = B.mmse_scale_search_kernelwise(wd, p)
+    s1, i1, e1 = oracle.can_search_kernelwise(w, *SIGNED, G, 20)
+    assert_search_equal(r1.scale.cpu().numpy(), r1.idx.cpu().numpy(), r1.sse.cpu().numpy(), s1, i1, e1)
+    r2 = B.residual_quantize(wd, r1.scale, p)
+    s2, i2, e2, p2 = oracle.can_residual_quantize(w, s1, *SIGNED, G, 20)
+    assert_search_equal(r2.scale.cpu().numpy(), r2.idx.cpu().numpy(), r2.sse.cpu().numpy(), s2, i2, e2)
+    np.testing.assert_array_equal(r2.packed.cpu().numpy(), p2)
+    assert np.all(r2.sse.cpu().numpy() <= r1.sse.cpu().numpy())
+
+
+# ------------------------------------------------------------------ activations
+@pytest.mark.parametrize("N", [1, 63, 4096, 4097, 100003, 524288, 64 * 4096 + 5, 3000001])
+@pytest.mark.parametrize("G", [128, 50])
+def test_activation_search_matches_oracle(B, N, G):
+    say(f"activation N={N} G={G}")
+    x = synth.acts_relu_normal(N, 5000 + N % 1000 + G)
+    p = B.params(*UNSIGNED, G, 20)
+    r = B.mmse_scale_search_activation(to_dev(x), p)
+    o = oracle.can_search(x, *UNSIGNED, G, 20)
+    assert_search_equal(r.scale.cpu().numpy(), r.idx.cpu().numpy(), r.sse.cpu().numpy(),
+                        np.array([o["scale"]], np.float32), np.array([o["idx"]], np.int32),
+                        np.array([o["sse"]]))
+    got = B.quantize_pack_int4(to_dev(x), r.scale, *UNSIGNED).cpu().numpy()
+    np.testing.assert_array_equal(got, oracle.can_quantize_pack_int4(x, [o["scale"]], *UNSIGNED))
+
+
+def test_activation_degenerate(B):
+    say("activation degenerate")
+    p = B.params(*UNSIGNED, 64, 10)
+    z = np.zeros(5000, np.float32)
+    r = B.mmse_scale_search_activation(to_dev(z), p)
+    assert (float(r.scale[0]), int(r.idx[0]), float(r.sse[0])) == (1.0, 0, 0.0)
+    z[77] = np.nan
+    r = B.mmse_scale_search_activation(to_dev(z), p)
+    assert np.isnan(float(r.scale[0])) and int(r.idx[0]) == -1 and np.isnan(float(r.sse[0]))
+    c = np.full(9000, 0.9375, np.float32)
+    r = B.mmse_scale_search_activation(to_dev(c), p)
+    assert (float(r.scale[0]), int(r.idx[0]), float(r.sse[0])) == (0.0625, 63, 0.0)
+
+
+# ------------------------------------------------------------------ whole networks (batched entry point)
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_whole_network_batched(B, cfg):
+    say(f"whole-net config {cfg}")
+    c = synth.config(cfg)
+    ws = [c.weight_tensor(i) for i in range(len(c.weight_shapes))]
+    p = B.params(*SIGNED, c.grid_points, c.refine_iters)
+    res = B.mmse_scale_search_batched([to_dev(w) for w in ws], p, want_packed=True)
+    import torch
+    torch.cuda.synchronize()
+    for i, (w, r) in enumerate(zip(ws, res)):
+        s, j, e = oracle.can_search_kernelwise(w, *SIGNED, c.grid_points, c.refine_iters)
+        assert_search_equal(r.scale.cpu().numpy(), r.idx.cpu().numpy(), r.sse.cpu().numpy(), s, j, e,
+                            tag=f"cfg{cfg} tensor {i} {c.weight_shapes[i]}")
+        np.testing.assert_array_equal(r.packed.cpu().numpy(), oracle.can_quantize_pack_int4(w, s, *SIGNED))
+
+
+def test_config1_activations(B):
+    say("config 1 activations")
+    c = synth.config(1)
+    x = c.act_tensor(0)
+    p = B.params(*UNSIGNED, c.grid_points, c.refine_iters)
+    r = B.mmse_scale_search_activation(to_dev(x), p)
+    o = oracle.can_search(x, *UNSIGNED, c.grid_points, c.refine_iters)
+    assert int(r.idx[0]) == o["idx"] and float(r.scale[0]) == o["scale"] and float(r.sse[0]) == o["sse"]
+
+
+def test_results_do_not_depend_on_tuning_or_repeat(B):
+    say("determinism across cands_per_lane and repeats")
+    w = synth.small_weights(50, 1152, 9, "laplace")
+    wd = to_dev(w)
+    base = None
+    for cpl in (1, 2, 4, 0, 2):
+        r = B.mmse_scale_search_kernelwise(wd, B.params(*SIGNED, 256, 20, cpl))
+        cur = (r.scale.cpu().numpy().copy(), r.idx.cpu().numpy().copy(), r.sse.cpu().numpy().copy())
+        if base is None:
+            base = cur
+        for a, b in zip(base, cur):
+            np.testing.assert_array_equal(a, b)
