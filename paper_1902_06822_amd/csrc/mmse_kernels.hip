@@ -163,6 +163,47 @@ __device__ __forceinline__ void tree_fold(const double (&st)[C][L], unsigned m, 
     }
 }
 
+// Squared errors of NE elements against C candidates, accumulated into s[C] in element
+// order.  The five operations of an evaluation form a dependent chain, so they are issued
+// stage by stage over all NE*C evaluations: consecutive instructions are independent and
+// the VALU pipeline latency is covered inside one wave.  (Order of the accumulation, the
+// only thing that affects the result, is unchanged: element by element per candidate.)
+// Scheduling fences keep the compiler from re-serialising the stages; LDS/VMEM/SALU
+// instructions may still move across them.
+#define MMSE_STAGE_FENCE() __builtin_amdgcn_sched_barrier(0x94)
+template <int NE, int C>
+__device__ __forceinline__ void eval_stage(const float (&x)[NE], const float (&alpha)[C], const float (&inv)[C],
+                                           float lo, float hi, float (&s)[C])
+{
+    float t[NE][C];
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = x[i] * inv[u];
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = __builtin_rintf(t[i][u]);
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = __builtin_amdgcn_fmed3f(t[i][u], lo, hi);
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = __builtin_fmaf(-alpha[u], t[i][u], x[i]);
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i) {
+#pragma unroll
+        for (int u = 0; u < C; ++u) s[u] = __builtin_fmaf(t[i][u], t[i][u], s[u]);
+        MMSE_STAGE_FENCE();
+    }
+}
+
 // Sweep `nchunks` chunks that sit in LDS at `slice` for the C candidates of this lane.
 template <int C, int L>
 __device__ __forceinline__ void sweep_slice(const float* slice, int nchunks, unsigned& ci,
@@ -170,21 +211,28 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nchunks, uns
                                             float lo, float hi, double (&st)[C][L])
 {
     const float4* s4 = reinterpret_cast<const float4*>(slice);
+    constexpr int NE = (C >= 4) ? 4 : 8;            // elements per stage group
     for (int c = 0; c < nchunks; ++c, ++ci) {
         float s[C];
 #pragma unroll
         for (int u = 0; u < C; ++u) s[u] = 0.0f;
+        // elements come from LDS one group ahead of their use (same address in every lane: broadcast)
+        float4 nxt[NE / 4];
 #pragma unroll
-        for (int e = 0; e < kChunk / 4; ++e) {
-            const float4 v = s4[c * (kChunk / 4) + e];     // same address in every lane: LDS broadcast
+        for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + q];
 #pragma unroll
-            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.x, alpha[u], inv[u], lo, hi, s[u]);
+        for (int e = 0; e < kChunk / NE; ++e) {
+            float x[NE];
 #pragma unroll
-            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.y, alpha[u], inv[u], lo, hi, s[u]);
+            for (int q = 0; q < NE / 4; ++q) {
+                x[4 * q + 0] = nxt[q].x; x[4 * q + 1] = nxt[q].y; x[4 * q + 2] = nxt[q].z; x[4 * q + 3] = nxt[q].w;
+            }
+            if (e + 1 < kChunk / NE) {
 #pragma unroll
-            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.z, alpha[u], inv[u], lo, hi, s[u]);
-#pragma unroll
-            for (int u = 0; u < C; ++u) s[u] = sq_err_acc(v.w, alpha[u], inv[u], lo, hi, s[u]);
+                for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + (e + 1) * (NE / 4) + q];
+            }
+            __builtin_amdgcn_sched_barrier(0);       // the prefetch is issued before this group's arithmetic
+            eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
         }
         double t[C];
 #pragma unroll
@@ -417,10 +465,14 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B)
 
     auto eval = [&](float alpha) -> double {
         const float inv = 1.0f / alpha;
-        float s = 0.0f;
+        float s[1] = {0.0f};
+        const float al[1] = {alpha}, iv[1] = {inv};
 #pragma unroll
-        for (int i = 0; i < CL; ++i) s = sq_err_acc(x[i], alpha, inv, lo, hi, s);
-        return tree_combine((double)s, c, m, l0, active, buf, par);
+        for (int i = 0; i < CL; i += 8) {
+            const float xs[8] = {x[i], x[i + 1], x[i + 2], x[i + 3], x[i + 4], x[i + 5], x[i + 6], x[i + 7]};
+            eval_stage<8, 1>(xs, al, iv, lo, hi, s);
+        }
+        return tree_combine((double)s[0], c, m, l0, active, buf, par);
     };
 
     const float aj = active ? grid_alpha(a, qmaxf, Gf, j) : 1.0f;
@@ -787,7 +839,7 @@ int pick_cands(const mmse_params_t* p)
 {
     if (p->cands_per_lane) return p->cands_per_lane;
     const int G = p->grid_points;
-    if (G <= 128) return 1;
+    if (G <= 512) return 1;     // one candidate per lane: most waves per SIMD, which the dual-issue VALU needs
     if (G <= 1024) return 2;
     return 4;
 }
