@@ -36,6 +36,81 @@ OPS_PER_EVAL = 5          # v_mul, v_rndne, v_med3, v_fma, v_fma(c)
 FLOPS_PER_EVAL = 7        # 1 + 1 + 1 + 2 + 2
 
 
+def bench_activation(args, cfg, torch, B) -> int:
+    """Per-layer search (Eq. 15) + packed codes for the largest activation tensor of the configuration."""
+    if not cfg.act_shapes:
+        print(f"bench.py: configuration {cfg.cfg} has no activations", file=sys.stderr)
+        return 2
+    G = args.grid_points if args.grid_points > 0 else cfg.grid_points
+    iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
+    li = max(range(len(cfg.act_shapes)), key=lambda i: cfg.act_shapes[i].per_image)
+    x = cfg.act_tensor(li)
+    N = x.size
+    xd = torch.from_numpy(x).cuda()
+    p = B.params(0, 15, G, iters, args.cands_per_lane)
+    ws = B.alloc_workspace(B.mmse_workspace_bytes_activation(N, p))
+    out = B.SearchResult(torch.empty(1, dtype=torch.float32, device="cuda"),
+                         torch.empty(1, dtype=torch.int32, device="cuda"),
+                         torch.empty(1, dtype=torch.float64, device="cuda"))
+    packed = torch.empty((N + 1) // 2, dtype=torch.uint8, device="cuda")
+
+    def step():
+        B.mmse_scale_search_activation(xd, p, ws, out)
+        B.quantize_pack_int4(xd, out.scale, 0, 15, packed)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    evals = N * (G + 2 + iters)
+
+    # dominant kernel alone: grid sweep (refine_iters = 0 leaves abs-max, sweep, reduction, argmin)
+    p0 = B.params(0, 15, G, 0, args.cands_per_lane)
+    B.mmse_scale_search_activation(xd, p0, ws, out)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(args.steps):
+        B.mmse_scale_search_activation(xd, p0, ws, out)
+    ev1.record()
+    torch.cuda.synchronize()
+    sweep_ms = ev0.elapsed_time(ev1) / args.steps
+    peak_tflops = LANE_OPS_PER_S * FLOPS_PER_EVAL / OPS_PER_EVAL / 1e12
+    ach = N * G * FLOPS_PER_EVAL / (sweep_ms * 1e-3) / 1e12
+    roofline = {"bound": "alu", "kernel": "k_act_sweep (+abs-max, block reduction, argmin in the timed region)",
+                "achieved": round(ach, 3), "peak": round(peak_tflops, 3), "unit": "TFLOP/s",
+                "frac": round(ach / peak_tflops, 4), "traffic": None, "avg_launch_ms": round(sweep_ms, 5),
+                "evals_per_s": N * G / (sweep_ms * 1e-3)}
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        o = oracle.can_search(x, 0, 15, G, iters)
+        ref_packed = oracle.can_quantize_pack_int4(x, [o["scale"]], 0, 15)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": evals / dt, "unit": "evals/s", "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"the full tensor once ({N} elements): search + codes", "seconds": round(dt, 3)}
+        parity = (int(out.idx[0]) == o["idx"] and float(out.scale[0]) == float(o["scale"])
+                  and abs(float(out.sse[0]) - o["sse"]) <= 1e-4 * o["sse"]
+                  and np.array_equal(packed.cpu().numpy(), ref_packed))
+    print(json.dumps({
+        "metric": METRIC, "value": evals / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] largest activation tensor "
+                               f"({cfg.act_shapes[li].name}, batch {cfg.act_batch})",
+                   "elements": N, "grid_points": G, "refine_iters": iters, "range": "unsigned INT4 (0..15)",
+                   "outputs": "scale, argmin index, sse, packed INT4 codes", "evals_per_step": evals},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +119,14 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="BASELINE.json configuration (weights part)")
     ap.add_argument("--cands-per-lane", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--part", choices=("weights", "activation"), default="weights",
+                    help="weights: the whole-net kernel-wise path (default); activation: the largest "
+                         "calibration tensor of the configuration through the per-layer path")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run plain device copies of this many MiB (for scaling FETCH_SIZE/WRITE_SIZE "
+                         "counters under rocprofv3 --pmc); not part of any timed region")
+    ap.add_argument("--grid-points", type=int, default=0, help="override G of the configuration")
+    ap.add_argument("--refine-iters", type=int, default=-1, help="override the refinement iterations")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -59,8 +142,19 @@ def main() -> int:
     B.load_library()
     torch.cuda.set_device(0)
 
+    if args.copy_calibration_mib > 0:
+        src = torch.ones(args.copy_calibration_mib * (1 << 20) // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     cfg = synth.config(args.config)
-    G, iters = cfg.grid_points, cfg.refine_iters
+    if args.part == "activation":
+        return bench_activation(args, cfg, torch, B)
+    G = args.grid_points if args.grid_points > 0 else cfg.grid_points
+    iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
     host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]
     dev_w = [torch.from_numpy(w).cuda() for w in host_w]
     elements = sum(w.size for w in host_w)

@@ -386,11 +386,11 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 // All lanes of the workgroup call it together.  `par` alternates the buffer so that
 // a call never overwrites what a slower lane is still reading from the previous call.
 __device__ __forceinline__ double tree_combine(double v, int c, int m, int l0, bool active,
-                                               double (*buf)[1024], int& par)
+                                               double* buf, int stride, int& par)
 {
     if (m == 1) return v;                     // m is uniform over the workgroup
     int pb = par;
-    if (active) buf[pb][l0 + c] = v;
+    if (active) buf[pb * stride + l0 + c] = v;
     __syncthreads();
     int cnt = m;
     while (cnt > 1) {
@@ -398,21 +398,27 @@ __device__ __forceinline__ double tree_combine(double v, int c, int m, int l0, b
         if (active && c < ncnt) {
             double e[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) e[i] = (8 * c + i < cnt) ? buf[pb][l0 + 8 * c + i] : 0.0;
-            buf[pb ^ 1][l0 + c] = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+            for (int i = 0; i < 8; ++i) e[i] = (8 * c + i < cnt) ? buf[pb * stride + l0 + 8 * c + i] : 0.0;
+            buf[(pb ^ 1) * stride + l0 + c] = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
         }
         __syncthreads();
         pb ^= 1;
         cnt = ncnt;
     }
     par = pb ^ 1;
-    return active ? buf[pb][l0] : 0.0;
+    return active ? buf[pb * stride + l0] : 0.0;
 }
 
+constexpr int kTileStride = 68;   // floats between chunks in the transpose tile (64 + 4: keeps 16-byte alignment)
+
 template <int CL>   // element slots per lane: 64 (general) or 16 (kernels of <= 16 elements)
-__global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B)
+__global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int tile_chunks)
 {
-    __shared__ double buf[2][1024];
+    // dynamic LDS: [combine buffer: 2 x blockDim doubles][per-wave transpose tiles]
+    extern __shared__ double smem_d[];
+    double* buf = smem_d;
+    float* tiles = reinterpret_cast<float*>(smem_d + 2 * blockDim.x);
+
     const int tid = threadIdx.x;
     const int t = find_tensor(B, blockIdx.x);
     const TensorArgs& A = B.t[t];
@@ -423,7 +429,8 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B)
     const int ch = tid / m, c = tid - ch * m;
     const int k = g * cpw + ch;
     const float lo = B.lo, hi = B.hi;
-    bool active = (ch < cpw) && (k < A.K);
+    const bool in_range = (ch < cpw) && (k < A.K);
+    bool active = in_range;
 
     float a = 0.0f;
     int j = 0;
@@ -433,10 +440,49 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B)
 
     // this lane's chunk, kept in registers for all probes (zeros beyond the end are exact no-ops)
     float x[CL];
-    {
-        const bool resid = A.scale1 != nullptr;
-        float s1 = 1.0f, inv1 = 1.0f;
-        if (active && resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+    const bool resid = A.scale1 != nullptr;
+    float s1 = 1.0f, inv1 = 1.0f;
+    if (active && resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+    const bool coalesced = (CL == kChunk) && (n % kChunk == 0) &&
+                           ((reinterpret_cast<uintptr_t>(A.w) & 15u) == 0) && tile_chunks > 0;
+    if (coalesced) {
+        // The workgroup's lanes map to consecutive 64-element chunks of memory.  Each wave reads
+        // its own 64 chunks with fully coalesced 16-byte loads, tile_chunks chunks at a time,
+        // and hands every lane its chunk through a wave-private LDS tile.
+        const int lane = tid & 63, wave = tid >> 6;
+        const int left = A.K - g * cpw;
+        const int nvalid = (left < cpw ? left : cpw) * m;              // chunks this workgroup owns
+        const float4* __restrict__ src4 =
+            reinterpret_cast<const float4*>(A.w + (size_t)g * cpw * n) + (size_t)wave * 64 * (kChunk / 4);
+        float* tile = tiles + (size_t)wave * tile_chunks * kTileStride;
+        const int per_lane = tile_chunks / 4;                          // float4 loads per lane and pass
+#pragma unroll
+        for (int i = 0; i < CL; ++i) x[i] = 0.0f;
+        for (int p0 = 0; p0 < 64; p0 += tile_chunks) {
+            for (int r = 0; r < per_lane; ++r) {
+                const int f = r * 64 + lane;                           // float4 number inside this pass
+                const int cj = f >> 4;                                 // chunk inside this pass
+                if (wave * 64 + p0 + cj < nvalid) {
+                    const float4 v = src4[(size_t)p0 * (kChunk / 4) + f];
+                    *reinterpret_cast<float4*>(tile + cj * kTileStride + (f & 15) * 4) = v;
+                }
+            }
+            __syncthreads();
+            if (lane >= p0 && lane < p0 + tile_chunks && in_range) {
+                const float4* t4 = reinterpret_cast<const float4*>(tile + (lane - p0) * kTileStride);
+#pragma unroll
+                for (int i = 0; i < CL / 4; ++i) {
+                    const float4 v = t4[i];
+                    x[4 * i + 0] = v.x; x[4 * i + 1] = v.y; x[4 * i + 2] = v.z; x[4 * i + 3] = v.w;
+                }
+            }
+            __syncthreads();
+        }
+        if (!active) {
+#pragma unroll
+            for (int i = 0; i < CL; ++i) x[i] = 0.0f;
+        }
+    } else {
         const int e0 = c * kChunk;
         const int len = active ? ((n - e0) < CL ? (n - e0) : CL) : 0;
         const float* __restrict__ src = A.w + ((size_t)(active ? k : 0) * n + (active ? e0 : 0));
@@ -452,10 +498,10 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B)
 #pragma unroll
             for (int i = 0; i < CL; ++i) x[i] = (i < len) ? src[i] : 0.0f;
         }
-        if (resid) {
+    }
+    if (resid) {
 #pragma unroll
-            for (int i = 0; i < CL; ++i) x[i] = residual_of(x[i], true, s1, inv1, lo, hi);
-        }
+        for (int i = 0; i < CL; ++i) x[i] = residual_of(x[i], true, s1, inv1, lo, hi);
     }
 
     const int G = B.G;
@@ -472,7 +518,7 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B)
             const float xs[8] = {x[i], x[i + 1], x[i + 2], x[i + 3], x[i + 4], x[i + 5], x[i + 6], x[i + 7]};
             eval_stage<8, 1>(xs, al, iv, lo, hi, s);
         }
-        return tree_combine((double)s[0], c, m, l0, active, buf, par);
+        return tree_combine((double)s[0], c, m, l0, active, buf, (int)blockDim.x, par);
     };
 
     const float aj = active ? grid_alpha(a, qmaxf, Gf, j) : 1.0f;
@@ -930,8 +976,12 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
                     if (nb == 0) return MMSE_OK;
                     B.start[nb] = wg;
                     B.count = nb;
-                    if (cls == 0) hipLaunchKernelGGL(k_refine_kernelwise<16>, dim3(wg), dim3(threads), 0, s, B);
-                    else hipLaunchKernelGGL(k_refine_kernelwise<kChunk>, dim3(wg), dim3(threads), 0, s, B);
+                    // LDS: combine buffer (2 doubles per thread) + one transpose tile per wave
+                    const int tile_chunks = cls == 0 ? 0 : 32 * 256 / threads;
+                    const size_t lds = (size_t)threads * 2 * sizeof(double) +
+                                       (size_t)(threads / 64) * tile_chunks * kTileStride * sizeof(float);
+                    if (cls == 0) hipLaunchKernelGGL(k_refine_kernelwise<16>, dim3(wg), dim3(threads), lds, s, B, tile_chunks);
+                    else hipLaunchKernelGGL(k_refine_kernelwise<kChunk>, dim3(wg), dim3(threads), lds, s, B, tile_chunks);
                     nb = 0; wg = 0;
                     return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
                 };
