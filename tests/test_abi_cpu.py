@@ -1,0 +1,137 @@
+"""CPU-side checks of the C ABI: the library loads, exports what include/mmse.h declares,
+and rejects bad arguments before touching the GPU (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1902_06822_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1902_06822_amd import build
+        build.build()
+    binding.load_library()
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mmse.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*\s*|int\s+)(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_symbols_are_exported(B):
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
+    lib = B.load_library()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_struct_layouts_match_header(B):
+    assert C.sizeof(B.MmseParams) == 20
+    assert C.sizeof(B.MmseTensorDesc) == 64
+    assert B.MmseTensorDesc.K.offset == 8 and B.MmseTensorDesc.packed_dev.offset == 56
+
+
+def test_status_strings(B):
+    assert B.status_string(0) == "ok"
+    for rc in range(-6, 0):
+        assert B.status_string(rc) not in ("ok", "unknown status")
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_workspace_queries(B):
+    p = B.params(-8, 7, 256, 20)
+    assert B.mmse_workspace_bytes_kernelwise(5800, 576, p) == 23296          # 5800 floats, rounded to 256
+    n1 = B.mmse_workspace_bytes_activation(4096, p)
+    n2 = B.mmse_workspace_bytes_activation(51380224, B.params(0, 15, 512, 20))
+    assert 256 < n1 < 16384 and n2 > 12544 * 512 * 8
+    with pytest.raises(RuntimeError):
+        B.mmse_workspace_bytes_kernelwise(0, 5, p)
+    with pytest.raises(RuntimeError):
+        B.mmse_workspace_bytes_activation(-1, p)
+
+
+@pytest.mark.parametrize("bad", [dict(qmin=1), dict(qmax=0), dict(qmin=-9, qmax=7), dict(grid_points=0),
+                                 dict(grid_points=2049), dict(refine_iters=-1), dict(refine_iters=65),
+                                 dict(cands_per_lane=3), dict(grid_points=1024, cands_per_lane=1)])
+def test_bad_parameters_are_rejected(B, bad):
+    kw = dict(qmin=-8, qmax=7, grid_points=256, refine_iters=20, cands_per_lane=0)
+    kw.update(bad)
+    p = B.params(**kw)
+    out = C.c_size_t(0)
+    assert B.load_library().mmse_workspace_bytes_kernelwise(8, 8, C.byref(p), C.byref(out)) == -3
+
+
+def test_entry_points_validate_before_enqueue(B):
+    """Fake (never dereferenced) addresses: every call must fail in validation, on the host."""
+    lib = B.load_library()
+    p = B.params(-8, 7, 256, 20)
+    a = 0x10000            # 64 KiB: aligned to everything, never touched
+    # NULL pointers
+    assert lib.mmse_scale_search_kernelwise(None, 4, 4, C.byref(p), a, a, a, a, 4096, None) == -1
+    assert lib.mmse_scale_search_kernelwise(a, 4, 4, C.byref(p), None, a, a, a, 4096, None) == -1
+    assert lib.mmse_scale_search_kernelwise(a, 4, 4, None, a, a, a, a, 4096, None) == -1
+    assert lib.mmse_scale_search_activation(None, 4, C.byref(p), a, a, a, a, 1 << 20, None) == -1
+    assert lib.quantize_pack_int4(a, 4, 4, None, -8, 7, a, None) == -1
+    assert lib.residual_quantize(a, 4, 4, None, C.byref(p), a, a, a, a, a, 4096, None) == -1
+    assert lib.mmse_scale_search_batched(None, 1, C.byref(p), a, 4096, None) == -1
+    assert lib.mmse_grid_sse_kernelwise(a, 4, 4, C.byref(p), None, a, None) == -1
+    # sizes
+    assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
+    assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2
+    assert lib.mmse_scale_search_kernelwise(a, 1 << 20, 4096, C.byref(p), a, a, a, a, 1 << 30, None) == -2
+    assert lib.mmse_scale_search_activation(a, 0, C.byref(p), a, a, a, a, 1 << 20, None) == -2
+    assert lib.mmse_scale_search_activation(a, 1 << 31, C.byref(p), a, a, a, a, 1 << 20, None) == -2
+    assert lib.quantize_pack_int4(a, 4, -1, a, -8, 7, a, None) == -2
+    # parameters
+    assert lib.quantize_pack_int4(a, 4, 4, a, 1, 7, a, None) == -3
+    # workspace: missing, misaligned, too small
+    assert lib.mmse_scale_search_kernelwise(a, 4, 4, C.byref(p), a, a, a, None, 4096, None) == -4
+    assert lib.mmse_scale_search_kernelwise(a, 4, 4, C.byref(p), a, a, a, a + 64, 4096, None) == -4
+    assert lib.mmse_scale_search_kernelwise(a, 400, 4, C.byref(p), a, a, a, a, 1024, None) == -4
+    assert lib.mmse_scale_search_activation(a, 1 << 20, C.byref(p), a, a, a, a, 4096, None) == -4
+    # alignment of typed outputs
+    assert lib.mmse_scale_search_kernelwise(a + 2, 4, 4, C.byref(p), a, a, a, a, 4096, None) == -6
+    assert lib.mmse_scale_search_kernelwise(a, 4, 4, C.byref(p), a, a, a + 4, a, 4096, None) == -6
+    assert lib.mmse_scale_search_activation(a, 64, C.byref(p), a, a + 2, a, a, 1 << 20, None) == -6
+
+
+def test_binding_refuses_host_tensors(B):
+    import torch
+    with pytest.raises(ValueError):
+        B.mmse_scale_search_kernelwise(torch.zeros(4, 4), B.params(-8, 7, 16, 0))
+
+
+def test_missing_library_is_an_error(B, monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """Only tests, smoke() and bench.py's cpu_baseline leg may use oracle/."""
+    pkg = os.path.join(ROOT, "paper_1902_06822_amd")
+    pat = re.compile(r"^\s*(import\s+oracle|from\s+oracle)|libmmse_oracle|mmse_oracle\.c|oracle/", re.M)
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not pat.search(text), f
+    assert not pat.search(open(os.path.join(ROOT, "include", "mmse.h")).read())
