@@ -385,12 +385,12 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 // per barrier.  v: this lane's chunk sum; c: chunk number; l0: first lane of the kernel.
 // All lanes of the workgroup call it together.  `par` alternates the buffer so that
 // a call never overwrites what a slower lane is still reading from the previous call.
-__device__ __forceinline__ double tree_combine(double v, int c, int m, int l0, bool active,
-                                               double* buf, int stride, int& par)
+__device__ __forceinline__ double tree_combine(double v, int c, int m, bool active,
+                                               double*& cur, double*& nxt)
 {
+    // cur / nxt: this kernel's slice of the two halves of the combine buffer (lane c at [c]).
     if (m == 1) return v;                     // m is uniform over the workgroup
-    int pb = par;
-    if (active) buf[pb * stride + l0 + c] = v;
+    if (active) cur[c] = v;
     __syncthreads();
     int cnt = m;
     while (cnt > 1) {
@@ -398,15 +398,17 @@ __device__ __forceinline__ double tree_combine(double v, int c, int m, int l0, b
         if (active && c < ncnt) {
             double e[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) e[i] = (8 * c + i < cnt) ? buf[pb * stride + l0 + 8 * c + i] : 0.0;
-            buf[(pb ^ 1) * stride + l0 + c] = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+            for (int i = 0; i < 8; ++i) e[i] = (8 * c + i < cnt) ? cur[8 * c + i] : 0.0;
+            nxt[c] = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
         }
         __syncthreads();
-        pb ^= 1;
+        double* t = cur; cur = nxt; nxt = t;
         cnt = ncnt;
     }
-    par = pb ^ 1;
-    return active ? buf[pb * stride + l0] : 0.0;
+    const double r = active ? cur[0] : 0.0;
+    // the next call starts in the other half, so it cannot overwrite what a slower lane still reads
+    double* t = cur; cur = nxt; nxt = t;
+    return r;
 }
 
 constexpr int kTileStride = 68;   // floats between chunks in the transpose tile (64 + 4: keeps 16-byte alignment)
@@ -506,8 +508,8 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
 
     const int G = B.G;
     const float qmaxf = (float)B.qmax, Gf = (float)G;
-    const int l0 = tid - c;
-    int par = 0;
+    double* cur = buf + (tid - c);
+    double* nxt = buf + blockDim.x + (tid - c);
 
     auto eval = [&](float alpha) -> double {
         const float inv = 1.0f / alpha;
@@ -518,7 +520,7 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
             const float xs[8] = {x[i], x[i + 1], x[i + 2], x[i + 3], x[i + 4], x[i + 5], x[i + 6], x[i + 7]};
             eval_stage<8, 1>(xs, al, iv, lo, hi, s);
         }
-        return tree_combine((double)s[0], c, m, l0, active, buf, (int)blockDim.x, par);
+        return tree_combine((double)s[0], c, m, active, cur, nxt);
     };
 
     const float aj = active ? grid_alpha(a, qmaxf, Gf, j) : 1.0f;
@@ -627,24 +629,115 @@ __global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
 //   part0[nb][G] doubles                  per-block tree sums of the grid sweep
 //   part1[ceil(nb/64)][G], part2, ...     upper tree levels, 64 blocks at a time
 //   probe0[nb], probe1[...], ...          same hierarchy for one refinement probe
+constexpr int kMaxProbes = 8;          // scales evaluated in one pass over an activation tensor
+
 struct ActState {
     unsigned absmax_bits;
     int status;              // 0 normal, 1 all-zero (scale 1), 2 rejected
-    int j;
-    int it;
+    int j;                   // grid argmin
+    int it;                  // golden-section iterations decided so far
+    int done;                // refinement finished
+    int have_c, have_d;      // f(pc), f(pd) known
+    int nprobe;              // scales to evaluate in the next pass
     float absmax;
-    float lo_a, hi_a, pc, pd, probe, best_a;
-    int left;
+    float lo_a, hi_a, pc, pd, best_a;
+    float probes[kMaxProbes];
     double ec, ed, best;
 };
 
 __global__ void k_act_init(ActState* S)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
-        S->absmax_bits = 0; S->status = 0; S->j = 0; S->it = 0; S->absmax = 0.0f;
-        S->lo_a = S->hi_a = S->pc = S->pd = S->probe = S->best_a = 1.0f;
-        S->left = 0; S->ec = S->ed = S->best = 0.0;
+        S->absmax_bits = 0; S->status = 0; S->j = 0; S->it = 0; S->done = 1;
+        S->have_c = S->have_d = 0; S->nprobe = 0; S->absmax = 0.0f;
+        S->lo_a = S->hi_a = S->pc = S->pd = S->best_a = 1.0f;
+        for (int i = 0; i < kMaxProbes; ++i) S->probes[i] = 1.0f;
+        S->ec = S->ed = S->best = 0.0;
     }
+}
+
+// ---- golden-section bookkeeping (one thread) ---------------------------------------
+// The search is sequential: each iteration needs f at one new scale.  One pass over a big
+// tensor costs a full read of it, so a pass evaluates the scale(s) the search is waiting
+// for *and* every scale the next two iterations could ask for (both outcomes of each
+// comparison: 1 + 2 + 4, or 2 + 2 + 4 at the start).  act_advance then replays the plain
+// sequential algorithm, looking values up by scale; it stops when a value is missing.
+// The probes are produced by the same fp32 expressions on both paths, so a lookup is an
+// exact match.  Nothing about the result depends on how much was evaluated ahead.
+template <int DEPTH>
+__device__ void act_enumerate(float lo_a, float hi_a, float pc, float pd, int depth, float* list, int& n)
+{
+    if constexpr (DEPTH > 0) {
+        if (depth == 0) return;
+        {   // f(pc) <= f(pd): keep [lo, pd]
+            const float nh = pd, npd = pc;
+            const float npc = __builtin_fmaf(-kPhi, nh - lo_a, nh);
+            if (n < kMaxProbes) list[n++] = npc;
+            act_enumerate<DEPTH - 1>(lo_a, nh, npc, npd, depth - 1, list, n);
+        }
+        {   // otherwise: keep [pc, hi]
+            const float nl = pc, npc = pd;
+            const float npd = __builtin_fmaf(kPhi, hi_a - nl, nl);
+            if (n < kMaxProbes) list[n++] = npd;
+            act_enumerate<DEPTH - 1>(nl, hi_a, npc, npd, depth - 1, list, n);
+        }
+    }
+}
+
+__device__ void act_plan(ActState* S, int iters)
+{
+    int n = 0;
+    float list[kMaxProbes];
+    if (!S->done) {
+        if (!S->have_c) list[n++] = S->pc;
+        if (!S->have_d) list[n++] = S->pd;
+        int depth = iters - S->it;
+        if (depth > 2) depth = 2;
+        act_enumerate<2>(S->lo_a, S->hi_a, S->pc, S->pd, depth, list, n);
+    }
+    S->nprobe = n;
+    for (int i = 0; i < kMaxProbes; ++i) S->probes[i] = i < n ? list[i] : 1.0f;
+}
+
+__device__ bool act_lookup(const float* probes, const double* vals, int n, float a, double& out)
+{
+    for (int i = 0; i < n; ++i)
+        if (probes[i] == a) { out = vals[i]; return true; }
+    return false;
+}
+
+__device__ void act_advance(ActState* S, const double* vals, int iters)
+{
+    float lo_a = S->lo_a, hi_a = S->hi_a, pc = S->pc, pd = S->pd, best_a = S->best_a;
+    double ec = S->ec, ed = S->ed, best = S->best;
+    int have_c = S->have_c, have_d = S->have_d, it = S->it, done = S->done;
+    const int n = S->nprobe;
+    while (!done) {
+        if (!have_c) {
+            if (!act_lookup(S->probes, vals, n, pc, ec)) break;
+            have_c = 1;
+            if (ec < best) { best = ec; best_a = pc; }
+        }
+        if (!have_d) {
+            if (!act_lookup(S->probes, vals, n, pd, ed)) break;
+            have_d = 1;
+            if (ed < best) { best = ed; best_a = pd; }
+        }
+        if (it == iters) { done = 1; break; }
+        if (ec <= ed) {
+            hi_a = pd; pd = pc; ed = ec;
+            pc = __builtin_fmaf(-kPhi, hi_a - lo_a, hi_a);
+            have_c = 0;
+        } else {
+            lo_a = pc; pc = pd; ec = ed;
+            pd = __builtin_fmaf(kPhi, hi_a - lo_a, lo_a);
+            have_d = 0;
+        }
+        ++it;
+    }
+    S->lo_a = lo_a; S->hi_a = hi_a; S->pc = pc; S->pd = pd; S->best_a = best_a;
+    S->ec = ec; S->ed = ed; S->best = best;
+    S->have_c = have_c; S->have_d = have_d; S->it = it; S->done = done;
 }
 
 __global__ void __launch_bounds__(256) k_act_absmax(const float* __restrict__ x, long long N, ActState* S)
@@ -777,6 +870,7 @@ __global__ void __launch_bounds__(1024) k_act_argmin(const double* __restrict__ 
         const float aj = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, bJ);
         S->absmax = a; S->j = bJ; S->status = tiny ? 1 : 0; S->it = 0;
         S->best = bE; S->best_a = aj;
+        S->done = 1; S->have_c = S->have_d = 0;
         *idx = bJ; *scale = aj; *sse = bE;
         if (!tiny && iters > 0) {
             const float lo_a = bJ == 0 ? 0.0f : grid_alpha(a, qmaxf, Gf, bJ - 1);
@@ -785,83 +879,100 @@ __global__ void __launch_bounds__(1024) k_act_argmin(const double* __restrict__ 
             S->lo_a = lo_a; S->hi_a = hi_a;
             S->pc = __builtin_fmaf(-kPhi, w, hi_a);
             S->pd = __builtin_fmaf(kPhi, w, lo_a);
-            S->probe = S->pc;
+            S->done = 0;
         }
+        act_plan(S, iters);
     }
 }
 
-// One refinement probe: lane = chunk, wave = block (64 chunks): fp32 chunk sums, then the
-// first six tree levels inside the wave.
+// One refinement pass: f at up to kMaxProbes scales for every block of 64 chunks.
+// lane = chunk, wave = block.  The wave reads its 16 KB with coalesced 16-byte loads and
+// turns them into one chunk per lane through a wave-private LDS tile (32 chunks at a time);
+// fp32 chunk sums per scale, then the first six tree levels by wave shuffles.
 __global__ void __launch_bounds__(256) k_act_probe(const float* __restrict__ x, long long N, float lo, float hi,
                                                    const ActState* S, double* probe0)
 {
-    if (S->status != 0) return;
-    const float alpha = S->probe;
-    const float inv = 1.0f / alpha;
-    const long long chunk = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long e0 = chunk * kChunk;
-    float s = 0.0f;
-    if (e0 < N) {
-        const float* __restrict__ src = x + e0;
-        const int len = (N - e0) < kChunk ? (int)(N - e0) : kChunk;
-        if (len == kChunk && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
-            const float4* s4 = reinterpret_cast<const float4*>(src);
+    __shared__ float4 tile4[4][32 * kTileStride / 4];
+    if (S->status != 0 || S->done) return;
+    const int np = S->nprobe;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long blk = (long long)blockIdx.x * 4 + wave;
+    const long long base = blk * kBlockElems;                 // first element of this wave's block
+    float* tile = reinterpret_cast<float*>(tile4[wave]);
+
+    float xr[kChunk];
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) xr[i] = 0.0f;
+    const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+    for (int p0 = 0; p0 < 64; p0 += 32) {
+        // 32 chunks = 2048 floats = 512 float4: 8 per lane
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int f = r * 64 + lane;
+            const long long e = base + (long long)p0 * kChunk + 4LL * f;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (aligned && e + 4 <= N) {
+                v = *reinterpret_cast<const float4*>(x + e);
+            } else if (e < N) {
+                v.x = x[e];
+                if (e + 1 < N) v.y = x[e + 1];
+                if (e + 2 < N) v.z = x[e + 2];
+                if (e + 3 < N) v.w = x[e + 3];
+            }
+            *reinterpret_cast<float4*>(tile + (f >> 4) * kTileStride + (f & 15) * 4) = v;
+        }
+        __syncthreads();
+        if (lane >= p0 && lane < p0 + 32) {
+            const float4* t4 = reinterpret_cast<const float4*>(tile + (lane - p0) * kTileStride);
 #pragma unroll
             for (int i = 0; i < kChunk / 4; ++i) {
-                const float4 v = s4[i];
-                s = sq_err_acc(v.x, alpha, inv, lo, hi, s);
-                s = sq_err_acc(v.y, alpha, inv, lo, hi, s);
-                s = sq_err_acc(v.z, alpha, inv, lo, hi, s);
-                s = sq_err_acc(v.w, alpha, inv, lo, hi, s);
+                const float4 v = t4[i];
+                xr[4 * i + 0] = v.x; xr[4 * i + 1] = v.y; xr[4 * i + 2] = v.z; xr[4 * i + 3] = v.w;
             }
-        } else {
-            for (int i = 0; i < len; ++i) s = sq_err_acc(src[i], alpha, inv, lo, hi, s);
         }
+        __syncthreads();
     }
-    double v = (double)s;
+
+    for (int pi = 0; pi < np; ++pi) {
+        const float alpha = S->probes[pi];
+        float s[1] = {0.0f};
+        const float al[1] = {alpha}, iv[1] = {1.0f / alpha};
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) v = v + __shfl_xor(v, off, 64);   // pairwise tree, same in all lanes
-    if ((threadIdx.x & 63) == 0) {
-        const long long blk = chunk >> 6;
-        if (blk * (long long)kBlockElems < N) probe0[blk] = v;
+        for (int i = 0; i < kChunk; i += 8) {
+            const float xs[8] = {xr[i], xr[i + 1], xr[i + 2], xr[i + 3], xr[i + 4], xr[i + 5], xr[i + 6], xr[i + 7]};
+            eval_stage<8, 1>(xs, al, iv, lo, hi, s);
+        }
+        double v = (double)s[0];
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) v = v + __shfl_xor(v, off, 64);   // pairwise tree, same in all lanes
+        if (lane == 0 && base < N) probe0[blk * kMaxProbes + pi] = v;
     }
 }
 
-// Golden-section bookkeeping after the probe value is known (single thread).
-__global__ void k_act_update(const double* __restrict__ tot, int iters, ActState* S, float* scale, double* sse)
+// Last tree level(s) over <= 64 rows of per-scale sums, then the golden-section bookkeeping.
+__global__ void __launch_bounds__(64) k_act_finish(const double* __restrict__ part, int rows, int iters,
+                                                   ActState* S, float* scale, double* sse)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0 || S->status != 0) return;
-    const double e = tot[0];
-    const float probe = S->probe;
-    int it = S->it;                           // 0: probe was c0, 1: probe was d0, >= 2: iteration it-2
-    float lo_a = S->lo_a, hi_a = S->hi_a, pc = S->pc, pd = S->pd;
-    double ec = S->ec, ed = S->ed, best = S->best;
-    float best_a = S->best_a;
-    if (it == 0) { ec = e; }
-    else if (it == 1) { ed = e; }
-    else if (S->left) { ec = e; }
-    else { ed = e; }
-    if (e < best) { best = e; best_a = probe; }
-    float next = pd;                          // after c0 comes d0
-    int left = 0;
-    if (it >= 1 && it - 1 < iters) {          // choose the next probe of iteration it-1
-        left = ec <= ed;
-        if (left) {
-            hi_a = pd; pd = pc; ed = ec;
-            const float w = hi_a - lo_a;
-            pc = __builtin_fmaf(-kPhi, w, hi_a);
-            next = pc;
-        } else {
-            lo_a = pc; pc = pd; ec = ed;
-            const float w = hi_a - lo_a;
-            pd = __builtin_fmaf(kPhi, w, lo_a);
-            next = pd;
-        }
+    __shared__ double vals[kMaxProbes];
+    if (S->status != 0 || S->done) return;
+    const int t = threadIdx.x;
+    if (t < kMaxProbes) {
+        double v[64];
+#pragma unroll
+        for (int i = 0; i < 64; ++i) v[i] = (i < rows && t < S->nprobe) ? part[(size_t)i * kMaxProbes + t] : 0.0;
+#pragma unroll
+        for (int w = 1; w < 64; w <<= 1)
+#pragma unroll
+            for (int i = 0; i < 64; i += 2 * w) v[i] = v[i] + v[i + w];
+        vals[t] = v[0];
     }
-    S->lo_a = lo_a; S->hi_a = hi_a; S->pc = pc; S->pd = pd; S->ec = ec; S->ed = ed;
-    S->best = best; S->best_a = best_a; S->left = left; S->probe = next; S->it = it + 1;
-    *scale = best_a;
-    *sse = best;
+    __syncthreads();
+    if (t == 0) {
+        act_advance(S, vals, iters);
+        act_plan(S, iters);
+        *scale = S->best_a;
+        *sse = S->best;
+    }
 }
 
 // ---------------------------------------------------------------------------------
@@ -1033,10 +1144,11 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
 
 struct ActPlan {
     int nb;                 // blocks of 4096 elements
-    int levels;             // number of reduce64 stages until one row is left
+    int levels;             // reduce64 stages of the grid sums until one row is left
     int rows[8];            // rows[0] = nb, rows[i+1] = ceil(rows[i]/64)
-    size_t off_part[8];     // byte offsets of the grid-sum levels
-    size_t off_probe[8];    // byte offsets of the probe levels
+    int plevels;            // reduce64 stages of the probe sums until <= 64 rows are left
+    size_t off_part[8];     // byte offsets of the grid-sum levels ([rows][G] doubles)
+    size_t off_probe[8];    // byte offsets of the probe levels ([rows][kMaxProbes] doubles)
     size_t bytes;
 };
 
@@ -1047,11 +1159,20 @@ ActPlan plan_activation(long long N, int G)
     P.rows[0] = P.nb;
     P.levels = 0;
     while (P.rows[P.levels] > 1) { P.rows[P.levels + 1] = (P.rows[P.levels] + 63) / 64; ++P.levels; }
+    P.plevels = 0;
+    while (P.rows[P.plevels] > 64) ++P.plevels;
     size_t off = round256(sizeof(ActState));
     for (int l = 0; l <= P.levels; ++l) { P.off_part[l] = off; off += round256((size_t)P.rows[l] * G * sizeof(double)); }
-    for (int l = 0; l <= P.levels; ++l) { P.off_probe[l] = off; off += round256((size_t)P.rows[l] * sizeof(double)); }
+    for (int l = 0; l <= P.plevels; ++l) { P.off_probe[l] = off; off += round256((size_t)P.rows[l] * kMaxProbes * sizeof(double)); }
     P.bytes = off;
     return P;
+}
+
+// passes over the tensor that the refinement needs: the first settles 4 evaluations, each later one 3
+int refine_passes(int iters)
+{
+    if (iters <= 0) return 0;
+    return 1 + (iters > 2 ? (iters - 2 + 2) / 3 : 0);
 }
 
 }  // namespace
@@ -1232,24 +1353,20 @@ int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_param
                            S, scale_dev, idx_dev, sse_dev);
         MMSE_CHECK_LAUNCH();
     }
-    if (p->refine_iters > 0) {
-        const long long nchunks = (N + kChunk - 1) / kChunk;
-        const int pgrid = (int)((nchunks + 255) / 256);
-        for (int e = 0; e < 2 + p->refine_iters; ++e) {
-            hipLaunchKernelGGL(k_act_probe, dim3(pgrid), dim3(256), 0, s, x_dev, (long long)N, lo, hi, S,
-                               reinterpret_cast<double*>(ws + P.off_probe[0]));
-            MMSE_CHECK_LAUNCH();
-            for (int l = 0; l < P.levels; ++l) {
-                hipLaunchKernelGGL(k_act_reduce64, dim3(1, P.rows[l + 1]), dim3(64), 0, s,
-                                   reinterpret_cast<const double*>(ws + P.off_probe[l]), P.rows[l], 1,
-                                   reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
-                MMSE_CHECK_LAUNCH();
-            }
-            hipLaunchKernelGGL(k_act_update, dim3(1), dim3(64), 0, s,
-                               reinterpret_cast<const double*>(ws + P.off_probe[P.levels]), p->refine_iters,
-                               S, scale_dev, sse_dev);
+    for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
+        hipLaunchKernelGGL(k_act_probe, dim3((P.nb + 3) / 4), dim3(256), 0, s, x_dev, (long long)N, lo, hi, S,
+                           reinterpret_cast<double*>(ws + P.off_probe[0]));
+        MMSE_CHECK_LAUNCH();
+        for (int l = 0; l < P.plevels; ++l) {
+            hipLaunchKernelGGL(k_act_reduce64, dim3(1, P.rows[l + 1]), dim3(64), 0, s,
+                               reinterpret_cast<const double*>(ws + P.off_probe[l]), P.rows[l], kMaxProbes,
+                               reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
             MMSE_CHECK_LAUNCH();
         }
+        hipLaunchKernelGGL(k_act_finish, dim3(1), dim3(64), 0, s,
+                           reinterpret_cast<const double*>(ws + P.off_probe[P.plevels]), P.rows[P.plevels],
+                           p->refine_iters, S, scale_dev, sse_dev);
+        MMSE_CHECK_LAUNCH();
     }
 #undef MMSE_CHECK_LAUNCH
     return MMSE_OK;
