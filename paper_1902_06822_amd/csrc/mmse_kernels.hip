@@ -204,35 +204,52 @@ __device__ __forceinline__ void eval_stage(const float (&x)[NE], const float (&a
     }
 }
 
-// Sweep `nchunks` chunks that sit in LDS at `slice` for the C candidates of this lane.
+// Sweep the `nelem` elements (a multiple of 8; zero padded) that sit in LDS at `slice` for the C
+// candidates of this lane: whole 64-element chunks, then a last shorter chunk that only walks the
+// 8-element groups it has (padding zeros would be exact no-ops, so skipping them changes nothing).
 template <int C, int L>
-__device__ __forceinline__ void sweep_slice(const float* slice, int nchunks, unsigned& ci,
+__device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsigned& ci,
                                             const float (&alpha)[C], const float (&inv)[C],
                                             float lo, float hi, double (&st)[C][L])
 {
     const float4* s4 = reinterpret_cast<const float4*>(slice);
     constexpr int NE = (C >= 4) ? 4 : 8;            // elements per stage group
-    for (int c = 0; c < nchunks; ++c, ++ci) {
+    const int nfull = nelem / kChunk;
+    const int tail = nelem - nfull * kChunk;        // 0, 8, ..., 56 elements of a last partial chunk
+    const int ntotal = nfull + (tail > 0 ? 1 : 0);
+    for (int c = 0; c < ntotal; ++c, ++ci) {
         float s[C];
 #pragma unroll
         for (int u = 0; u < C; ++u) s[u] = 0.0f;
-        // elements come from LDS one group ahead of their use (same address in every lane: broadcast)
-        float4 nxt[NE / 4];
+        if (c < nfull) {
+            // elements come from LDS one group ahead of their use (same address in every lane: broadcast)
+            float4 nxt[NE / 4];
 #pragma unroll
-        for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + q];
+            for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + q];
 #pragma unroll
-        for (int e = 0; e < kChunk / NE; ++e) {
-            float x[NE];
+            for (int e = 0; e < kChunk / NE; ++e) {
+                float x[NE];
 #pragma unroll
-            for (int q = 0; q < NE / 4; ++q) {
-                x[4 * q + 0] = nxt[q].x; x[4 * q + 1] = nxt[q].y; x[4 * q + 2] = nxt[q].z; x[4 * q + 3] = nxt[q].w;
+                for (int q = 0; q < NE / 4; ++q) {
+                    x[4 * q + 0] = nxt[q].x; x[4 * q + 1] = nxt[q].y; x[4 * q + 2] = nxt[q].z; x[4 * q + 3] = nxt[q].w;
+                }
+                if (e + 1 < kChunk / NE) {
+#pragma unroll
+                    for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + (e + 1) * (NE / 4) + q];
+                }
+                __builtin_amdgcn_sched_barrier(0);       // the prefetch is issued before this group's arithmetic
+                eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
             }
-            if (e + 1 < kChunk / NE) {
+        } else {
+            for (int e = 0; e < tail / NE; ++e) {
+                float x[NE];
 #pragma unroll
-                for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + (e + 1) * (NE / 4) + q];
+                for (int q = 0; q < NE / 4; ++q) {
+                    const float4 v = s4[c * (kChunk / 4) + e * (NE / 4) + q];
+                    x[4 * q + 0] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+                }
+                eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
             }
-            __builtin_amdgcn_sched_barrier(0);       // the prefetch is issued before this group's arithmetic
-            eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
         }
         double t[C];
 #pragma unroll
@@ -333,7 +350,7 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
         for (int l = 0; l < kLevelsKW; ++l) st[u][l] = 0.0;
     unsigned ci = 0;
     if (single) {
-        sweep_slice<C, kLevelsKW>(slice, npad / kChunk, ci, alpha, inv, lo, hi, st);
+        sweep_slice<C, kLevelsKW>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st);
     } else {
         for (int t0 = 0; t0 < npad; t0 += kTile) {
             const int tlen = (npad - t0) < kTile ? (npad - t0) : kTile;
@@ -343,7 +360,8 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
                 slice[i] = residual_of(gi < n ? src[gi] : 0.0f, resid, s1, inv1, lo, hi);
             }
             __syncthreads();
-            sweep_slice<C, kLevelsKW>(slice, tlen / kChunk, ci, alpha, inv, lo, hi, st);
+            const int valid = ((n + 7) & ~7) - t0;       // the last tile may end in a partial chunk
+            sweep_slice<C, kLevelsKW>(slice, valid < tlen ? valid : tlen, ci, alpha, inv, lo, hi, st);
         }
     }
     double E[C];
@@ -560,6 +578,37 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
     if (active && c == 0) {
         A.scale[k] = best_a;
         A.sse[k] = best;
+    }
+
+    // Fused INT4 codes (the host passes `packed` here only when n is even, so that every chunk
+    // starts and ends on a byte boundary): the chunk is still in registers, the scale is final.
+    if (A.packed != nullptr && in_range) {
+        const float inv = 1.0f / (active ? best_a : 1.0f);      // all-zero / rejected kernels: x is 0 here, codes 0
+        const int e0 = c * kChunk;
+        const int len = (n - e0) < CL ? (n - e0) : CL;
+        unsigned words[CL / 8];
+#pragma unroll
+        for (int w = 0; w < CL / 8; ++w) {
+            unsigned word = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                word |= ((unsigned)(int)code_of(x[8 * w + i], inv, lo, hi) & 0xFu) << (4 * i);
+            words[w] = word;
+        }
+        uint8_t* dst = A.packed + (((size_t)k * n + e0) >> 1);
+        if (len == CL && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+            if constexpr (CL == kChunk) {
+                reinterpret_cast<uint4*>(dst)[0] = make_uint4(words[0], words[1], words[2], words[3]);
+                reinterpret_cast<uint4*>(dst)[1] = make_uint4(words[4], words[5], words[6], words[7]);
+            } else {
+                reinterpret_cast<uint2*>(dst)[0] = make_uint2(words[0], words[1]);
+            }
+        } else {
+            const int nbytes = len >> 1;
+#pragma unroll
+            for (int b = 0; b < CL / 2; ++b)
+                if (b < nbytes) dst[b] = (uint8_t)(words[b >> 2] >> (8 * (b & 3)));
+        }
     }
 }
 
@@ -804,7 +853,7 @@ __global__ void __launch_bounds__(512) k_act_sweep(const float* __restrict__ x, 
 #pragma unroll
         for (int l = 0; l < kLevelsBlk; ++l) st[u][l] = 0.0;
     unsigned ci = 0;
-    sweep_slice<C, kLevelsBlk>(slice, npad / kChunk, ci, alpha, inv, lo, hi, st);
+    sweep_slice<C, kLevelsBlk>(slice, (len + 7) & ~7, ci, alpha, inv, lo, hi, st);
     double E[C];
     tree_fold<C, kLevelsBlk>(st, ci, E);
 #pragma unroll
@@ -1104,6 +1153,7 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
                     const int lanes = cls == 0 ? 1 : m;
                     const int cpw = threads / lanes;
                     B.t[nb] = a;
+                    if (a.n & 1) B.t[nb].packed = nullptr;     // odd n: bytes straddle kernels, k_pack_int4 does those
                     B.start[nb] = wg;
                     wg += (a.K + cpw - 1) / cpw;
                     if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
@@ -1129,6 +1179,7 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
         for (int i = 0; i < count; ++i) {
             const TensorArgs& a = items[i].a;
             if (!a.packed) continue;
+            if (do_search && p->refine_iters > 0 && (a.n & 1) == 0) continue;   // coded by the refinement kernel
             const long long total = (long long)a.K * a.n;
             const long long per_wg = (long long)kPackThreads * kPackPerThread;
             B.t[nb] = a;
