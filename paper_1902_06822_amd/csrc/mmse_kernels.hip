@@ -38,7 +38,8 @@ namespace {
 constexpr int kChunk = 64;             // elements per sequential fp32 chunk
 constexpr int kMaxBatch = 32;          // tensors per launch (descriptor table lives in kernarg)
 constexpr int kTile = 8192;            // floats of one kernel staged in LDS at a time
-constexpr int kLevelsKW = 11;          // binary-counter levels for <= 1024 chunks
+constexpr int kLevelsKW = 11;          // binary-counter levels for <= 1024 chunks (65536 elements)
+constexpr int kLevelsKWSmall = 8;      // ... for <= 128 chunks (8192 elements: one LDS tile)
 constexpr int kBlockChunks = 64;       // activation block = 64 chunks = 4096 elements
 constexpr int kBlockElems = kBlockChunks * kChunk;
 constexpr int kLevelsBlk = 7;          // levels for 64 chunks
@@ -268,7 +269,7 @@ __device__ __forceinline__ int find_tensor(const Batch& B, int bid)
 // ---------------------------------------------------------------------------------
 // k_sweep_kernelwise: abs-max + grid sweep + argmin, one workgroup per weight kernel
 // ---------------------------------------------------------------------------------
-template <int C>
+template <int C, int LV>   // LV: binary-counter levels, enough for the longest kernel of the launch
 __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 {
     extern __shared__ float4 smem4[];
@@ -343,14 +344,14 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
     }
 
     // ---- pass 2: sweep
-    double st[C][kLevelsKW];
+    double st[C][LV];
 #pragma unroll
     for (int u = 0; u < C; ++u)
 #pragma unroll
-        for (int l = 0; l < kLevelsKW; ++l) st[u][l] = 0.0;
+        for (int l = 0; l < LV; ++l) st[u][l] = 0.0;
     unsigned ci = 0;
     if (single) {
-        sweep_slice<C, kLevelsKW>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st);
+        sweep_slice<C, LV>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st);
     } else {
         for (int t0 = 0; t0 < npad; t0 += kTile) {
             const int tlen = (npad - t0) < kTile ? (npad - t0) : kTile;
@@ -361,11 +362,11 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
             }
             __syncthreads();
             const int valid = ((n + 7) & ~7) - t0;       // the last tile may end in a partial chunk
-            sweep_slice<C, kLevelsKW>(slice, valid < tlen ? valid : tlen, ci, alpha, inv, lo, hi, st);
+            sweep_slice<C, LV>(slice, valid < tlen ? valid : tlen, ci, alpha, inv, lo, hi, st);
         }
     }
     double E[C];
-    tree_fold<C, kLevelsKW>(st, ci, E);
+    tree_fold<C, LV>(st, ci, E);
 
     if (A.grid_sse) {
 #pragma unroll
@@ -1078,7 +1079,10 @@ int launch_sweep(const Batch& B, int nwg, int G, int max_npad, hipStream_t s)
 {
     const int waves = (G + 64 * C - 1) / (64 * C);
     const size_t lds = (size_t)(max_npad < kTile ? max_npad : kTile) * sizeof(float);
-    hipLaunchKernelGGL(k_sweep_kernelwise<C>, dim3(nwg), dim3(64 * waves), lds, s, B);
+    if (max_npad <= kTile)
+        hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall>), dim3(nwg), dim3(64 * waves), lds, s, B);
+    else
+        hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW>), dim3(nwg), dim3(64 * waves), lds, s, B);
     return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
 }
 
