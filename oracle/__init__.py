@@ -18,7 +18,8 @@ from typing import Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmmse_oracle.so")
+# MMSE_ORACLE_LIB lets the mutation tests point the same Python wrapper at a deliberately broken build
+_LIB_PATH = os.environ.get("MMSE_ORACLE_LIB") or os.path.join(_HERE, "libmmse_oracle.so")
 _lib = None
 
 

@@ -15,12 +15,12 @@ CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-mfma", "-msse4.1", "-fopenmp
           "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 
-def build(verbose: bool = False) -> str:
-    cmd = ["gcc", *CFLAGS, SRC, "-o", OUT, "-lm"]
+def build(verbose: bool = False, src: str = SRC, out: str = OUT) -> str:
+    cmd = ["gcc", *CFLAGS, src, "-o", out, "-lm"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return OUT
+    return out
 
 
 if __name__ == "__main__":

@@ -135,3 +135,31 @@ def test_product_path_does_not_touch_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not pat.search(text), f
     assert not pat.search(open(os.path.join(ROOT, "include", "mmse.h")).read())
+
+
+def test_hot_kernels_spill_nothing():
+    """Register arrays of the hot kernels (tree partials, staged temporaries, chunk data) must stay in
+    VGPRs: the compiler's resource report may show no scratch for them."""
+    import shutil
+    import subprocess
+    from paper_1902_06822_amd import build
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    r = subprocess.run([hipcc, *flags, "--cuda-device-only", "-c", *build.SRC, "-o", os.devnull,
+                        "-Rpass-analysis=kernel-resource-usage"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    name, seen = None, {}
+    for line in r.stderr.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name:
+            seen[name] = int(m.group(1))
+    hot = [k for k in seen if any(t in k for t in ("k_sweep_kernelwise", "k_refine_kernelwise", "k_pack_int4",
+                                                    "k_act_sweep", "k_act_probe", "k_act_absmax", "k_act_reduce64"))]
+    assert len(hot) >= 10, seen
+    for k in hot:
+        assert seen[k] == 0, (k, seen[k])

@@ -292,6 +292,36 @@ def test_refinement_structure(seed):
     assert p[1] == pytest.approx(lo + phi * w, rel=1e-6)
 
 
+def test_refinement_converges_to_the_vertex_where_f_is_a_parabola():
+    """With a fine grid and few elements the codes do not change across the bracket, so
+    f(alpha) = sum (x - alpha*q)^2 is an exact parabola there with vertex sum(xq)/sum(q^2):
+    a golden-section search must close in on it (this pins which half is kept)."""
+    G, iters, used = 2048, 30, 0
+    for seed in range(40):
+        rng = np.random.default_rng(1000 + seed)
+        x = rng.normal(0, 1, 6).astype(np.float32)
+        r = oracle.can_search(x, *SIGNED, G, iters, want_probes=True)
+        grid = oracle.can_grid(np.abs(x).max(), 7, G)
+        j = r["idx"]
+        if j == 0 or j == G - 1:
+            continue
+        lo, hi = grid[j - 1], grid[j + 1]
+        q_lo = oracle.can_codes(x, [lo], *SIGNED).ravel()
+        q_hi = oracle.can_codes(x, [hi], *SIGNED).ravel()
+        if not np.array_equal(q_lo, q_hi):
+            continue                                    # a code flips inside the bracket: not a parabola
+        q = q_lo.astype(np.float64)
+        vertex = float(np.dot(x.astype(np.float64), q) / np.dot(q, q))
+        target = min(max(vertex, float(lo)), float(hi))
+        w0 = float(hi) - float(lo)
+        # near the vertex f is flat to within fp32 rounding of the sums, so the search cannot resolve
+        # alpha much better than sqrt(eps); a search that kept the wrong half ends >= 0.38*w0 away
+        assert abs(float(r["probes"][-1]) - target) <= 0.05 * w0
+        assert abs(float(r["scale"]) - target) <= 0.05 * w0
+        used += 1
+    assert used >= 10
+
+
 def test_refine_iters_zero_returns_grid_point():
     x = synth.small_weights(1, 300, 2, "student")[0]
     r = oracle.can_search(x, *SIGNED, 77, 0)
