@@ -114,8 +114,9 @@ def bench_activation(args, cfg, torch, B) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps; the GPU needs some tens of milliseconds of work to reach its steady clock")
     ap.add_argument("--config", type=int, default=2, help="BASELINE.json configuration (weights part)")
     ap.add_argument("--cands-per-lane", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -200,7 +201,11 @@ def main() -> int:
         "peak": round(peak_tflops, 3),
         "unit": "TFLOP/s",
         "frac": round(achieved_tflops / peak_tflops, 4),
-        "traffic": None,
+        # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
+        # (profiles/weights_cfg2_resnet18.md; counters scaled by a 1 GiB copy in the same run); only
+        # measured for the default configuration
+        "traffic": 47.6e6 if (args.config == 2 and args.grid_points == 0) else None,
+        "algorithmic_bytes": 4 * elements,
         "avg_launch_ms": round(sweep_ms / nlaunch, 5),
         "launches_per_step": nlaunch,
         "evals_per_s": sweep_evals / (sweep_ms * 1e-3),
