@@ -49,6 +49,8 @@ def _load():
         "can_quantize_pack_int4": (None, [f32p, i64, i64, f32p, i32, i32, u8p]),
         "can_residual": (None, [f32p, i64, i64, f32p, i32, i32, f32p]),
         "can_residual_quantize": (None, [f32p, i64, i64, f32p, i32, i32, i32, i32, f32p, i32p, f64p, u8p]),
+        "can_dual_alternating_kernelwise": (None, [f32p, i64, i64, i32, i32, i32, i32, f64, i32,
+                                                   f32p, f32p, u8p, u8p, f64p, i32p]),
         "oracle_num_threads": (i32, []),
     }
     for name, (res, args) in sig.items():
@@ -208,3 +210,17 @@ def can_residual_quantize(w, scale1, qmin: int, qmax: int, G: int, iters: int):
                                   _p(scale2, C.c_float), _p(idx2, C.c_int32), _p(sse2, C.c_double),
                                   _p(packed2, C.c_uint8))
     return scale2, idx2, sse2, packed2
+
+
+def can_dual_alternating(w, qmin: int, qmax: int, G: int, iters: int, eps: float, max_sweeps: int):
+    """Algorithm 1 iterated for two tensors, per kernel.  Returns dict(scale1, scale2, packed1, packed2, sse, sweeps)."""
+    w = _f32(w)
+    K, n = w.shape
+    out = {"scale1": np.zeros(K, np.float32), "scale2": np.zeros(K, np.float32),
+           "packed1": np.zeros((K * n + 1) // 2, np.uint8), "packed2": np.zeros((K * n + 1) // 2, np.uint8),
+           "sse": np.zeros(K, np.float64), "sweeps": np.zeros(K, np.int32)}
+    _load().can_dual_alternating_kernelwise(
+        _p(w, C.c_float), K, n, qmin, qmax, G, iters, float(eps), int(max_sweeps),
+        _p(out["scale1"], C.c_float), _p(out["scale2"], C.c_float), _p(out["packed1"], C.c_uint8),
+        _p(out["packed2"], C.c_uint8), _p(out["sse"], C.c_double), _p(out["sweeps"], C.c_int32))
+    return out

@@ -360,6 +360,103 @@ void can_residual_quantize(const float *w, int64_t K, int64_t n, const float *sc
     free(resid);
 }
 
+/* ------------------------------------------------------------------ */
+/* Algorithm 1 iterated (Section 3.5), n = 2 tensors of equal precision */
+/* ------------------------------------------------------------------ */
+
+/* T - alpha*Q for stored integer codes, one fused multiply-add per element. */
+static void can_subtract_codes(const float *t, const int32_t *q, float alpha, int64_t n, float *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = fmaf(-alpha, (float)q[i], t[i]);
+}
+
+/* phi of Algorithm 1: the MMSE mapping of Section 3.4 (search + codes). */
+static int can_phi(const float *x, int64_t n, int qmin, int qmax, int G, int iters,
+                   float *alpha, int32_t *q, double *sse)
+{
+    int32_t idx;
+    int rc = can_search(x, n, qmin, qmax, G, iters, alpha, &idx, sse, NULL, NULL);
+    if (rc == 0) can_codes(x, 1, n, alpha, qmin, qmax, q);
+    else for (int64_t i = 0; i < n; ++i) q[i] = 0;
+    return rc;
+}
+
+/* Alternating optimisation for one kernel T.  Sweep: (a1,Q1) = phi(T - a2*Q2), then
+ * (a2,Q2) = phi(T - a1*Q1); E = the error the second phi reports, i.e. ||T - a1*Q1 - a2*Q2||^2.
+ * The first sweep starts from Q2 = 0 (so it is the plain fit followed by the residual fit).
+ * The paper leaves "convergence rate > epsilon" undefined; the reading here: after a sweep
+ * s >= 1 with error E_s, stop when E_{s-1} - E_s <= eps * E_{s-1}; a sweep that does not lower
+ * the error is discarded (phi is a grid heuristic, so it is not guaranteed to).  At most
+ * max_sweeps sweeps; E = 0 stops at once.  sweeps_done counts the sweeps whose result is kept.
+ * Returns 0, or -1 when phi rejected the input (then scales and sse are NaN, codes 0). */
+int can_dual_alternating(const float *t, int64_t n, int qmin, int qmax, int G, int iters,
+                         double eps, int max_sweeps,
+                         float *a1_out, float *a2_out, int32_t *q1, int32_t *q2,
+                         double *sse_out, int32_t *sweeps_done)
+{
+    size_t nn = (size_t)(n > 0 ? n : 1);
+    float *r = (float *)calloc(nn, sizeof(float));
+    int32_t *tq1 = (int32_t *)malloc(sizeof(int32_t) * nn);
+    int32_t *tq2 = (int32_t *)malloc(sizeof(int32_t) * nn);
+    float a1 = 1.0f, a2 = 1.0f;
+    double e = 0.0, e1;
+    int rc;
+    for (int64_t i = 0; i < n; ++i) { q1[i] = 0; q2[i] = 0; }
+    *sweeps_done = 0;
+    /* sweep 0 */
+    can_subtract_codes(t, q2, a2, n, r);
+    rc = can_phi(r, n, qmin, qmax, G, iters, &a1, q1, &e1);
+    if (rc == 0) {
+        can_subtract_codes(t, q1, a1, n, r);
+        rc = can_phi(r, n, qmin, qmax, G, iters, &a2, q2, &e);
+    }
+    if (rc != 0) {
+        *a1_out = NAN; *a2_out = NAN; *sse_out = NAN;
+        for (int64_t i = 0; i < n; ++i) { q1[i] = 0; q2[i] = 0; }
+        free(r); free(tq1); free(tq2);
+        return -1;
+    }
+    *sweeps_done = 1;
+    for (int s = 1; s < max_sweeps && e > 0.0; ++s) {
+        float ta1, ta2;
+        double te1, te;
+        can_subtract_codes(t, q2, a2, n, r);
+        if (can_phi(r, n, qmin, qmax, G, iters, &ta1, tq1, &te1) != 0) break;
+        can_subtract_codes(t, tq1, ta1, n, r);
+        if (can_phi(r, n, qmin, qmax, G, iters, &ta2, tq2, &te) != 0) break;
+        if (!(te < e)) break;                       /* no gain: keep the previous sweep */
+        {
+            int conv = (e - te) <= eps * e;
+            a1 = ta1; a2 = ta2; e = te;
+            memcpy(q1, tq1, sizeof(int32_t) * nn);
+            memcpy(q2, tq2, sizeof(int32_t) * nn);
+            *sweeps_done = s + 1;
+            if (conv) break;
+        }
+    }
+    *a1_out = a1; *a2_out = a2; *sse_out = e;
+    free(r); free(tq1); free(tq2);
+    return 0;
+}
+
+/* Every kernel of a [K][n] layer on its own; codes are returned packed (two per byte, flat). */
+void can_dual_alternating_kernelwise(const float *w, int64_t K, int64_t n, int qmin, int qmax, int G, int iters,
+                                     double eps, int max_sweeps,
+                                     float *scale1, float *scale2, uint8_t *packed1, uint8_t *packed2,
+                                     double *sse, int32_t *sweeps)
+{
+    size_t tot = (size_t)(K * n > 0 ? K * n : 1);
+    int32_t *q1 = (int32_t *)malloc(sizeof(int32_t) * tot);
+    int32_t *q2 = (int32_t *)malloc(sizeof(int32_t) * tot);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < K; ++k)
+        can_dual_alternating(w + k * n, n, qmin, qmax, G, iters, eps, max_sweeps,
+                             scale1 + k, scale2 + k, q1 + k * n, q2 + k * n, sse + k, sweeps + k);
+    can_pack_int4(q1, K * n, packed1);
+    can_pack_int4(q2, K * n, packed2);
+    free(q1); free(q2);
+}
+
 int oracle_num_threads(void)
 {
     int nthreads = 1;

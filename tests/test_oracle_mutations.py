@@ -34,6 +34,15 @@ MUTATIONS = [
     ("residual uses the wrong sign", "resid[k * n + i] = fmaf(-a1, can_code(x, inv, lo, hi), x);", "resid[k * n + i] = fmaf(a1, can_code(x, inv, lo, hi), x);"),
     ("second tensor searched on the weights, not the residual", "can_search_kernelwise(resid, K, n, qmin, qmax, G, iters, scale2, idx2, sse2);",
      "can_search_kernelwise(w, K, n, qmin, qmax, G, iters, scale2, idx2, sse2);"),
+    ("alternating: first half-step fits the residual of the wrong tensor",
+     "        can_subtract_codes(t, q2, a2, n, r);\n        if (can_phi(r, n, qmin, qmax, G, iters, &ta1, tq1, &te1) != 0) break;",
+     "        can_subtract_codes(t, q1, a1, n, r);\n        if (can_phi(r, n, qmin, qmax, G, iters, &ta1, tq1, &te1) != 0) break;"),
+    ("alternating: second half-step fits the weights, not the residual",
+     "        can_subtract_codes(t, tq1, ta1, n, r);", "        can_subtract_codes(t, tq1, 0.0f, n, r);"),
+    ("alternating: residual added instead of subtracted",
+     "out[i] = fmaf(-alpha, (float)q[i], t[i]);", "out[i] = fmaf(alpha, (float)q[i], t[i]);"),
+    ("alternating: worse sweeps are kept", "if (!(te < e)) break;", ";"),
+    ("alternating: stopping rule ignored", "if (conv) break;", ";"),
     ("tiny tensors not special-cased", "} else if (a < ORACLE_TINY) {", "} else if (a < 0.0f) {"),
     ("non-finite input accepted", "return bad ? NAN : a;", "return a;"),
 ]
