@@ -119,6 +119,22 @@ int residual_quantize(const float *w_dev, int64_t K, int64_t n, const float *sca
                       const mmse_params_t *p, float *scale2_dev, int32_t *idx2_dev, double *sse2_dev,
                       uint8_t *packed2_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
+/* Algorithm 1 of Section 3.5 iterated for two INT4 tensors, every kernel of a [K][n] layer on its own:
+ *   sweep:  (a1,Q1) = phi(w - a2*Q2);  (a2,Q2) = phi(w - a1*Q1)      phi = search + codes of Section 3.4
+ * starting from Q2 = 0 (so max_sweeps = 1 is mmse_scale_search_kernelwise + residual_quantize).  The paper
+ * does not define its "convergence rate > epsilon"; here a kernel stops after a sweep whose relative gain
+ * (E_prev - E)/E_prev is <= eps, when E reaches 0, after max_sweeps (1..64) sweeps, or when a sweep did not
+ * lower E (that sweep is discarded: phi is a grid heuristic).  Outputs per kernel k: scale1_dev[k],
+ * scale2_dev[k], sse_dev[k] = ||w_k - a1*Q1 - a2*Q2||^2, sweeps_dev[k] = sweeps kept (0 for a rejected
+ * kernel); packed1_dev / packed2_dev: codes of the two tensors, ceil(K*n/2) bytes each, layout as in
+ * quantize_pack_int4.  All max_sweeps sweeps are enqueued at once; kernels that have stopped are skipped
+ * on the device.  Workspace: mmse_workspace_bytes_dual. */
+int mmse_workspace_bytes_dual(int64_t K, int64_t n, const mmse_params_t *p, size_t *bytes_out);
+int dual_quantize_alternating(const float *w_dev, int64_t K, int64_t n, const mmse_params_t *p,
+                              double eps, int32_t max_sweeps,
+                              float *scale1_dev, float *scale2_dev, uint8_t *packed1_dev, uint8_t *packed2_dev,
+                              double *sse_dev, int32_t *sweeps_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
 /* Whole network in a handful of launches: `count` weight tensors described in HOST
  * memory (the descriptors are consumed before the call returns).  Semantics per
  * tensor are those of mmse_scale_search_kernelwise / residual_quantize /

@@ -20,7 +20,8 @@ EXPORTS = (
     "mmse_workspace_bytes_kernelwise", "mmse_workspace_bytes_activation",
     "mmse_scale_search_kernelwise", "mmse_scale_search_activation",
     "quantize_pack_int4", "residual_quantize", "mmse_scale_search_batched",
-    "mmse_grid_sse_kernelwise", "mmse_status_string",
+    "mmse_grid_sse_kernelwise", "mmse_workspace_bytes_dual", "dual_quantize_alternating",
+    "mmse_status_string",
 )
 
 
@@ -58,6 +59,9 @@ def load_library() -> C.CDLL:
     lib.residual_quantize.argtypes = [vp, i64, i64, vp, pp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.mmse_scale_search_batched.argtypes = [C.POINTER(MmseTensorDesc), i32, pp, vp, C.c_size_t, vp]
     lib.mmse_grid_sse_kernelwise.argtypes = [vp, i64, i64, pp, vp, vp, vp]
+    lib.mmse_workspace_bytes_dual.argtypes = [i64, i64, pp, szp]
+    lib.dual_quantize_alternating.argtypes = [vp, i64, i64, pp, C.c_double, i32, vp, vp, vp, vp, vp, vp, vp,
+                                              C.c_size_t, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -231,3 +235,40 @@ def mmse_grid_sse_kernelwise(w: torch.Tensor, p: MmseParams):
     _check(load_library().mmse_grid_sse_kernelwise(w.data_ptr(), K, n, C.byref(p), absmax.data_ptr(),
                                                    grid.data_ptr(), _stream()), "mmse_grid_sse_kernelwise")
     return absmax, grid
+
+
+@dataclass
+class DualResult:
+    scale1: torch.Tensor    # fp32 [K]
+    scale2: torch.Tensor    # fp32 [K]
+    packed1: torch.Tensor   # uint8 [ceil(K*n/2)]
+    packed2: torch.Tensor
+    sse: torch.Tensor       # fp64 [K]
+    sweeps: torch.Tensor    # int32 [K]
+
+
+def mmse_workspace_bytes_dual(K: int, n: int, p: MmseParams) -> int:
+    out = C.c_size_t(0)
+    _check(load_library().mmse_workspace_bytes_dual(K, n, C.byref(p), C.byref(out)), "mmse_workspace_bytes_dual")
+    return out.value
+
+
+def dual_quantize_alternating(w: torch.Tensor, p: MmseParams, eps: float, max_sweeps: int,
+                              ws: Optional[torch.Tensor] = None, out: Optional[DualResult] = None) -> DualResult:
+    _dev(w, torch.float32)
+    K, n = w.shape
+    if ws is None:
+        ws = alloc_workspace(mmse_workspace_bytes_dual(K, n, p), w.device)
+    if out is None:
+        nb = (K * n + 1) // 2
+        out = DualResult(torch.empty(K, dtype=torch.float32, device=w.device),
+                         torch.empty(K, dtype=torch.float32, device=w.device),
+                         torch.empty(nb, dtype=torch.uint8, device=w.device),
+                         torch.empty(nb, dtype=torch.uint8, device=w.device),
+                         torch.empty(K, dtype=torch.float64, device=w.device),
+                         torch.empty(K, dtype=torch.int32, device=w.device))
+    _check(load_library().dual_quantize_alternating(
+        w.data_ptr(), K, n, C.byref(p), float(eps), int(max_sweeps), out.scale1.data_ptr(), out.scale2.data_ptr(),
+        out.packed1.data_ptr(), out.packed2.data_ptr(), out.sse.data_ptr(), out.sweeps.data_ptr(),
+        ws.data_ptr(), ws.numel(), _stream()), "dual_quantize_alternating")
+    return out

@@ -58,6 +58,9 @@ struct TensorArgs {
     float* absmax;           // workspace [K]
     double* grid_sse;        // optional [K][G]
     uint8_t* packed;
+    const uint8_t* sub_packed;   // nullptr, or stored codes Q of another tensor: search/pack w - sub_scale*Q
+    const float* sub_scale;      // [K], with sub_packed
+    const uint8_t* active;       // nullptr, or [K]: kernels with 0 are skipped by the search
     int K;
     int n;
 };
@@ -95,10 +98,38 @@ __device__ __forceinline__ float grid_alpha(float absmax, float qmaxf, float Gf,
     return smax * frac;
 }
 
-// One input element, optionally turned into the residual of a first quantization.
-__device__ __forceinline__ float residual_of(float v, bool resid, float s1, float inv1, float lo, float hi)
+// What a search reads: the weights themselves, or what another INT4 tensor leaves of them
+// (Section 3.5: T - sum_{i != j} alpha_i*Q_i), formed with one fused multiply-add per element and
+// never stored.  mode 1 recomputes Q = [w/alpha] from alpha; mode 2 reads Q from packed codes.
+struct Xform {
+    int mode;                // 0 none, 1 subtract alpha*[w/alpha], 2 subtract alpha*stored code
+    float s1, inv1;
+    const uint8_t* sub;
+    bool sub_signed;
+};
+
+__device__ __forceinline__ Xform make_xform(const TensorArgs& A, int k, float lo, bool valid)
 {
-    if (resid) v = __builtin_fmaf(-s1, code_of(v, inv1, lo, hi), v);
+    Xform X;
+    X.mode = A.sub_packed != nullptr ? 2 : (A.scale1 != nullptr ? 1 : 0);
+    X.s1 = 1.0f; X.inv1 = 1.0f; X.sub = A.sub_packed; X.sub_signed = lo < 0.0f;
+    if (valid) {
+        if (X.mode == 1) { X.s1 = A.scale1[k]; X.inv1 = 1.0f / X.s1; }
+        if (X.mode == 2) X.s1 = A.sub_scale[k];
+    }
+    return X;
+}
+
+// v: element number `flat` of the tensor (row-major over [K][n]).
+__device__ __forceinline__ float xform_apply(const Xform& X, float v, long long flat, float lo, float hi)
+{
+    if (X.mode == 1) {
+        v = __builtin_fmaf(-X.s1, code_of(v, X.inv1, lo, hi), v);
+    } else if (X.mode == 2) {
+        int q = (X.sub[flat >> 1] >> ((flat & 1) * 4)) & 0xF;
+        if (X.sub_signed && q >= 8) q -= 16;
+        v = __builtin_fmaf(-X.s1, (float)q, v);
+    }
     return v;
 }
 
@@ -286,9 +317,9 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
     const int n = A.n;
     const float* __restrict__ src = A.w + (size_t)k * n;
     const float lo = B.lo, hi = B.hi;
-    const bool resid = A.scale1 != nullptr;
-    float s1 = 1.0f, inv1 = 1.0f;
-    if (resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+    if (A.active != nullptr && A.active[k] == 0) return;      // uniform: the whole workgroup leaves
+    const Xform X = make_xform(A, k, lo, true);
+    const long long flat0 = (long long)k * n;
 
     const int npad = (n + kChunk - 1) & ~(kChunk - 1);
     const bool single = npad <= kTile;
@@ -297,14 +328,14 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
     unsigned amax = 0;
     if (single) {
         for (int i = tid; i < npad; i += nthreads) {
-            const float v = residual_of(i < n ? src[i] : 0.0f, resid, s1, inv1, lo, hi);
+            const float v = i < n ? xform_apply(X, src[i], flat0 + i, lo, hi) : 0.0f;
             slice[i] = v;
             const unsigned b = abs_bits(v);
             amax = b > amax ? b : amax;
         }
     } else {
         for (int i = tid; i < n; i += nthreads) {
-            const unsigned b = abs_bits(residual_of(src[i], resid, s1, inv1, lo, hi));
+            const unsigned b = abs_bits(xform_apply(X, src[i], flat0 + i, lo, hi));
             amax = b > amax ? b : amax;
         }
     }
@@ -358,7 +389,7 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
             __syncthreads();
             for (int i = tid; i < tlen; i += nthreads) {
                 const int gi = t0 + i;
-                slice[i] = residual_of(gi < n ? src[gi] : 0.0f, resid, s1, inv1, lo, hi);
+                slice[i] = gi < n ? xform_apply(X, src[gi], flat0 + gi, lo, hi) : 0.0f;
             }
             __syncthreads();
             const int valid = ((n + 7) & ~7) - t0;       // the last tile may end in a partial chunk
@@ -450,7 +481,7 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
     const int ch = tid / m, c = tid - ch * m;
     const int k = g * cpw + ch;
     const float lo = B.lo, hi = B.hi;
-    const bool in_range = (ch < cpw) && (k < A.K);
+    const bool in_range = (ch < cpw) && (k < A.K) && (A.active == nullptr || A.active[k < A.K ? k : 0] != 0);
     bool active = in_range;
 
     float a = 0.0f;
@@ -461,9 +492,7 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
 
     // this lane's chunk, kept in registers for all probes (zeros beyond the end are exact no-ops)
     float x[CL];
-    const bool resid = A.scale1 != nullptr;
-    float s1 = 1.0f, inv1 = 1.0f;
-    if (active && resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+    const Xform X = make_xform(A, k, lo, active);
     const bool coalesced = (CL == kChunk) && (n % kChunk == 0) &&
                            ((reinterpret_cast<uintptr_t>(A.w) & 15u) == 0) && tile_chunks > 0;
     if (coalesced) {
@@ -520,9 +549,13 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
             for (int i = 0; i < CL; ++i) x[i] = (i < len) ? src[i] : 0.0f;
         }
     }
-    if (resid) {
+    if (X.mode != 0 && active) {
+        const int e0x = c * kChunk;
+        const int lenx = (n - e0x) < CL ? (n - e0x) : CL;
+        const long long f0 = (long long)k * n + e0x;
 #pragma unroll
-        for (int i = 0; i < CL; ++i) x[i] = residual_of(x[i], true, s1, inv1, lo, hi);
+        for (int i = 0; i < CL; ++i)
+            if (i < lenx) x[i] = xform_apply(X, x[i], f0 + i, lo, hi);
     }
 
     const int G = B.G;
@@ -626,7 +659,6 @@ __global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
     const long long e0 = ((long long)g * kPackThreads + threadIdx.x) * kPackPerThread;
     if (e0 >= total) return;
     const float lo = B.lo, hi = B.hi;
-    const bool resid = A.scale1 != nullptr;
     const float* __restrict__ src = A.w;
     const float* __restrict__ scale = A.scale;
 
@@ -644,20 +676,22 @@ __global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
 
     int k = (int)((unsigned)e0 / (unsigned)n);          // K*n < 2^31: 32-bit division is enough
     int r = (int)((unsigned)e0 - (unsigned)k * (unsigned)n);   // position inside kernel k
-    float inv = 1.0f / scale[k];
-    float s1 = 1.0f, inv1 = 1.0f;
-    if (resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+    float sc = scale[k];
+    float inv = 1.0f / sc;
+    Xform X = make_xform(A, k, lo, true);
     unsigned word = 0;
 #pragma unroll
     for (int i = 0; i < kPackPerThread; ++i) {
         if (i < cnt) {
             if (r == n) {                     // crossed into the next kernel
                 r = 0; ++k;
-                inv = 1.0f / scale[k];
-                if (resid) { s1 = A.scale1[k]; inv1 = 1.0f / s1; }
+                sc = scale[k];
+                inv = 1.0f / sc;
+                X = make_xform(A, k, lo, true);
             }
-            const float x = residual_of(v[i], resid, s1, inv1, lo, hi);
-            const int q = (int)code_of(x, inv, lo, hi);
+            const float x = xform_apply(X, v[i], e0 + i, lo, hi);
+            // a rejected kernel (scale NaN) is coded as zeros
+            const int q = (sc == sc) ? (int)code_of(x, inv, lo, hi) : 0;
             word |= ((unsigned)q & 0xFu) << (4 * i);
             ++r;
         }
@@ -669,6 +703,62 @@ __global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
         const int nbytes = (cnt + 1) >> 1;
         for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));
     }
+}
+
+// ---------------------------------------------------------------------------------
+// Algorithm 1 iterated (Section 3.5): bookkeeping between alternating sweeps, per kernel
+// ---------------------------------------------------------------------------------
+// After the first sweep: a kernel goes on iterating unless it was rejected or is already exact.
+__global__ void __launch_bounds__(256) k_dual_init(int K, const double* __restrict__ sse, uint8_t* active,
+                                                   int32_t* sweeps)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    const double e = sse[k];
+    const bool ok = e == e;
+    sweeps[k] = ok ? 1 : 0;
+    active[k] = (ok && e > 0.0) ? 1 : 0;
+}
+
+// After a later sweep: keep it if it lowered the error; stop when the relative gain is <= eps,
+// when the error reached 0, or when the sweep was no better (then it is discarded).
+__global__ void __launch_bounds__(256) k_dual_accept(int K, double eps, double* sse, const double* __restrict__ t_sse,
+                                                     float* s1, const float* __restrict__ ts1,
+                                                     float* s2, const float* __restrict__ ts2,
+                                                     int32_t* sweeps, uint8_t* active, uint8_t* accepted)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    uint8_t acc = 0;
+    if (active[k]) {
+        const double e = sse[k], te = t_sse[k];
+        if (te < e) {
+            acc = 1;
+            const bool conv = (e - te) <= eps * e;
+            s1[k] = ts1[k]; s2[k] = ts2[k]; sse[k] = te; sweeps[k] += 1;
+            if (conv || !(te > 0.0)) active[k] = 0;
+        } else {
+            active[k] = 0;
+        }
+    }
+    accepted[k] = acc;
+}
+
+// Codes of the kernels whose sweep was kept move from the tentative to the final buffers, nibble by
+// nibble (a byte can hold codes of two kernels when n is odd).
+__global__ void __launch_bounds__(256) k_dual_copy_codes(long long total, int n, const uint8_t* __restrict__ accepted,
+                                                         const uint8_t* __restrict__ t1, uint8_t* p1,
+                                                         const uint8_t* __restrict__ t2, uint8_t* p2)
+{
+    const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (2 * b >= total) return;
+    const unsigned e0 = (unsigned)(2 * b);
+    const bool a0 = accepted[e0 / (unsigned)n] != 0;
+    const bool a1 = (long long)e0 + 1 < total && accepted[(e0 + 1) / (unsigned)n] != 0;
+    if (!a0 && !a1) return;
+    const unsigned mask = (a0 ? 0x0Fu : 0u) | (a1 ? 0xF0u : 0u);
+    p1[b] = (uint8_t)((p1[b] & ~mask) | (t1[b] & mask));
+    p2[b] = (uint8_t)((p2[b] & ~mask) | (t2[b] & mask));
 }
 
 // ---------------------------------------------------------------------------------
@@ -1230,6 +1320,29 @@ int refine_passes(int iters)
     return 1 + (iters > 2 ? (iters - 2 + 2) / 3 : 0);
 }
 
+struct DualPlan {           // workspace of dual_quantize_alternating, byte offsets
+    size_t absmax, idx, ts1, ts2, tsse1, tsse, active, accepted, tp1, tp2, bytes;
+};
+
+DualPlan plan_dual(long long K, long long n)
+{
+    DualPlan P{};
+    const size_t nb = (size_t)((K * n + 1) / 2);
+    size_t off = 0;
+    P.absmax = off; off += round256((size_t)K * sizeof(float));
+    P.idx = off; off += round256((size_t)K * sizeof(int32_t));
+    P.ts1 = off; off += round256((size_t)K * sizeof(float));
+    P.ts2 = off; off += round256((size_t)K * sizeof(float));
+    P.tsse1 = off; off += round256((size_t)K * sizeof(double));
+    P.tsse = off; off += round256((size_t)K * sizeof(double));
+    P.active = off; off += round256((size_t)K);
+    P.accepted = off; off += round256((size_t)K);
+    P.tp1 = off; off += round256(nb);
+    P.tp2 = off; off += round256(nb);
+    P.bytes = off;
+    return P;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------
@@ -1286,7 +1399,7 @@ int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t coun
     }
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < round256((size_t)sumK * sizeof(float)))
         return MMSE_ERR_WORKSPACE;
-    Item* items = new Item[count];
+    Item* items = new Item[count]();       // value-initialised: every optional pointer starts as nullptr
     float* ws = static_cast<float*>(ws_dev);
     long long off = 0;
     for (int i = 0; i < count; ++i) {
@@ -1294,6 +1407,7 @@ int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t coun
         TensorArgs& a = items[i].a;
         a.w = d.w_dev; a.scale1 = d.scale1_dev; a.scale = d.scale_dev; a.idx = d.idx_dev; a.sse = d.sse_dev;
         a.absmax = ws + off; a.grid_sse = nullptr; a.packed = d.packed_dev;
+        a.sub_packed = nullptr; a.sub_scale = nullptr; a.active = nullptr;
         a.K = (int)d.K; a.n = (int)d.n;
         items[i].order = i;
         off += d.K;
@@ -1356,6 +1470,79 @@ int mmse_grid_sse_kernelwise(const float* w_dev, int64_t K, int64_t n, const mms
     it.a.w = w_dev; it.a.absmax = absmax_dev; it.a.grid_sse = grid_sse_dev;
     it.a.K = (int)K; it.a.n = (int)n;
     return run_weight_tensors(&it, 1, &q, true, static_cast<hipStream_t>(stream));
+}
+
+int mmse_workspace_bytes_dual(int64_t K, int64_t n, const mmse_params_t* p, size_t* bytes_out)
+{
+    if (!bytes_out) return MMSE_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc) return rc;
+    if (K <= 0 || n <= 0 || n > MMSE_MAX_KERNEL_ELEMS || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    *bytes_out = plan_dual(K, n).bytes;
+    return MMSE_OK;
+}
+
+int dual_quantize_alternating(const float* w_dev, int64_t K, int64_t n, const mmse_params_t* p,
+                              double eps, int32_t max_sweeps,
+                              float* scale1_dev, float* scale2_dev, uint8_t* packed1_dev, uint8_t* packed2_dev,
+                              double* sse_dev, int32_t* sweeps_dev, void* ws_dev, size_t ws_bytes, void* stream)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (!w_dev || !scale1_dev || !scale2_dev || !packed1_dev || !packed2_dev || !sse_dev || !sweeps_dev)
+        return MMSE_ERR_NULL;
+    if (K <= 0 || n <= 0 || n > MMSE_MAX_KERNEL_ELEMS || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (!(eps >= 0.0) || max_sweeps < 1 || max_sweeps > 64) return MMSE_ERR_PARAMS;
+    if (!aligned_to(w_dev, 4) || !aligned_to(scale1_dev, 4) || !aligned_to(scale2_dev, 4) ||
+        !aligned_to(sse_dev, 8) || !aligned_to(sweeps_dev, 4))
+        return MMSE_ERR_ALIGN;
+    const DualPlan P = plan_dual(K, n);
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < P.bytes) return MMSE_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(ws_dev);
+    float* absmax = reinterpret_cast<float*>(ws + P.absmax);
+    int32_t* idx = reinterpret_cast<int32_t*>(ws + P.idx);
+    float* ts1 = reinterpret_cast<float*>(ws + P.ts1);
+    float* ts2 = reinterpret_cast<float*>(ws + P.ts2);
+    double* tsse1 = reinterpret_cast<double*>(ws + P.tsse1);
+    double* tsse = reinterpret_cast<double*>(ws + P.tsse);
+    uint8_t* active = reinterpret_cast<uint8_t*>(ws + P.active);
+    uint8_t* accepted = reinterpret_cast<uint8_t*>(ws + P.accepted);
+    uint8_t* tp1 = reinterpret_cast<uint8_t*>(ws + P.tp1);
+    uint8_t* tp2 = reinterpret_cast<uint8_t*>(ws + P.tp2);
+
+    auto fit = [&](const uint8_t* sub, const float* sub_scale, const uint8_t* mask,
+                   float* out_scale, double* out_sse, uint8_t* out_packed) -> int {
+        Item it{};
+        it.a.w = w_dev; it.a.scale = out_scale; it.a.idx = idx; it.a.sse = out_sse; it.a.absmax = absmax;
+        it.a.packed = out_packed; it.a.sub_packed = sub; it.a.sub_scale = sub_scale; it.a.active = mask;
+        it.a.K = (int)K; it.a.n = (int)n;
+        return run_weight_tensors(&it, 1, p, true, s);
+    };
+    const int kb = (int)((K + 255) / 256);
+    const long long total = (long long)K * n;
+
+    // first sweep, from an empty second tensor: the plain fit, then the fit of what it leaves
+    rc = fit(nullptr, nullptr, nullptr, scale1_dev, tsse1, packed1_dev);
+    if (rc) return rc;
+    rc = fit(packed1_dev, scale1_dev, nullptr, scale2_dev, sse_dev, packed2_dev);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_dual_init, dim3(kb), dim3(256), 0, s, (int)K, sse_dev, active, sweeps_dev);
+    if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+    for (int sweep = 1; sweep < max_sweeps; ++sweep) {
+        rc = fit(packed2_dev, scale2_dev, active, ts1, tsse1, tp1);          // j = 1: T - a2*Q2
+        if (rc) return rc;
+        rc = fit(tp1, ts1, active, ts2, tsse, tp2);                          // j = 2: T - a1*Q1
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_dual_accept, dim3(kb), dim3(256), 0, s, (int)K, eps, sse_dev, tsse,
+                           scale1_dev, ts1, scale2_dev, ts2, sweeps_dev, active, accepted);
+        if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+        const long long nbytes = (total + 1) / 2;
+        hipLaunchKernelGGL(k_dual_copy_codes, dim3((unsigned)((nbytes + 255) / 256)), dim3(256), 0, s, total, (int)n,
+                           accepted, tp1, packed1_dev, tp2, packed2_dev);
+        if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+    }
+    return MMSE_OK;
 }
 
 int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_params_t* p,

@@ -1,0 +1,112 @@
+"""GPU parity of Algorithm 1 iterated for two INT4 tensors (Section 3.5) against the oracle."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1902_06822_amd import synth
+
+pytestmark = pytest.mark.gpu
+SIGNED = (-8, 7)
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1902_06822_amd import binding
+    binding.load_library()
+    return binding
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def run_and_compare(B, w, G, iters, eps, max_sweeps, tag):
+    import torch
+    p = B.params(*SIGNED, G, iters)
+    r = B.dual_quantize_alternating(torch.from_numpy(w).cuda(), p, eps, max_sweeps)
+    torch.cuda.synchronize()
+    o = oracle.can_dual_alternating(w, *SIGNED, G, iters, eps, max_sweeps)
+    np.testing.assert_array_equal(r.sweeps.cpu().numpy(), o["sweeps"], err_msg=f"sweeps {tag}")
+    np.testing.assert_array_equal(r.packed1.cpu().numpy(), o["packed1"], err_msg=f"codes1 {tag}")
+    np.testing.assert_array_equal(r.packed2.cpu().numpy(), o["packed2"], err_msg=f"codes2 {tag}")
+    for name, got, ref, tol in (("scale1", r.scale1, o["scale1"], 1e-6), ("scale2", r.scale2, o["scale2"], 1e-6),
+                                ("sse", r.sse, o["sse"], 1e-4)):
+        g = got.cpu().numpy()
+        np.testing.assert_allclose(g, ref, rtol=tol, atol=0, err_msg=f"{name} {tag}")
+        np.testing.assert_array_equal(g, ref, err_msg=f"{name} bits {tag}")
+    return r, o
+
+
+@pytest.mark.parametrize("K,n,kind", [(40, 9, "outliers"), (12, 27, "normal"), (12, 147, "laplace"),
+                                      (32, 576, "laplace"), (6, 4608, "student"), (2, 25088, "laplace"),
+                                      (5, 64, "normal"), (7, 130, "laplace")])
+@pytest.mark.parametrize("max_sweeps,eps", [(1, 0.0), (2, 0.0), (6, 1e-2)])
+def test_dual_alternating_matches_oracle(B, K, n, kind, max_sweeps, eps):
+    say(f"dual K={K} n={n} {kind} max_sweeps={max_sweeps} eps={eps}")
+    w = synth.small_weights(K, n, 7000 + K + n, kind)
+    run_and_compare(B, w, 128, 20, eps, max_sweeps, f"K={K} n={n}")
+
+
+def test_dual_alternating_coarse_grid_discards_worse_sweeps(B):
+    say("dual coarse grid")
+    for seed, (K, n, G, kind) in enumerate(((6, 27, 8, "normal"), (6, 9, 8, "outliers"), (4, 64, 16, "laplace"),
+                                            (4, 147, 6, "student"))):
+        w = synth.small_weights(K, n, seed * 7 + n, kind)
+        prev = None
+        for m in (1, 2, 4, 8):
+            r, o = run_and_compare(B, w, G, 3, 0.0, m, f"coarse {K}x{n} G={G} m={m}")
+            e = r.sse.cpu().numpy()
+            if prev is not None:
+                assert np.all(e <= prev)
+            prev = e
+
+
+def test_dual_alternating_degenerate_rows(B):
+    say("dual degenerate rows")
+    w = synth.small_weights(6, 200, 9, "laplace")
+    w[1] = 0.0
+    w[2, 5] = np.nan
+    w[3] = np.array([-7, 0] * 100, np.float32) * 0.25        # exact after one tensor
+    import torch
+    p = B.params(*SIGNED, 64, 10)
+    r = B.dual_quantize_alternating(torch.from_numpy(w).cuda(), p, 1e-3, 5)
+    o = oracle.can_dual_alternating(w, *SIGNED, 64, 10, 1e-3, 5)
+    np.testing.assert_array_equal(r.sweeps.cpu().numpy(), o["sweeps"])
+    ok = [0, 1, 3, 4, 5]
+    np.testing.assert_array_equal(r.scale1.cpu().numpy()[ok], o["scale1"][ok])
+    np.testing.assert_array_equal(r.scale2.cpu().numpy()[ok], o["scale2"][ok])
+    np.testing.assert_array_equal(r.sse.cpu().numpy()[ok], o["sse"][ok])
+    assert np.isnan(r.scale1.cpu().numpy()[2]) and np.isnan(r.sse.cpu().numpy()[2]) and r.sweeps.cpu().numpy()[2] == 0
+    np.testing.assert_array_equal(r.packed1.cpu().numpy(), o["packed1"])
+    np.testing.assert_array_equal(r.packed2.cpu().numpy(), o["packed2"])
+
+
+def test_dual_alternating_config5_layer_sample(B):
+    """A full layer of configuration 5 in the real launch shape (512 kernels of 4608), oracle on sampled kernels."""
+    import torch
+    say("dual cfg5 conv layer 512x4608, G=512")
+    c = synth.config(5)
+    w = c.weight_tensor(9)
+    assert w.shape == (512, 4608)
+    p = B.params(*SIGNED, c.grid_points, c.refine_iters)
+    r = B.dual_quantize_alternating(torch.from_numpy(w).cuda(), p, 1e-3, 4)
+    torch.cuda.synchronize()
+    rows = np.array([0, 17, 100, 255, 256, 400, 511])
+    o = oracle.can_dual_alternating(np.ascontiguousarray(w[rows]), *SIGNED, c.grid_points, c.refine_iters, 1e-3, 4)
+    np.testing.assert_array_equal(r.sweeps.cpu().numpy()[rows], o["sweeps"])
+    np.testing.assert_array_equal(r.scale1.cpu().numpy()[rows], o["scale1"])
+    np.testing.assert_array_equal(r.scale2.cpu().numpy()[rows], o["scale2"])
+    np.testing.assert_array_equal(r.sse.cpu().numpy()[rows], o["sse"])
+    n = 4608
+    p1 = r.packed1.cpu().numpy().reshape(512, n // 2)[rows].ravel()
+    p2 = r.packed2.cpu().numpy().reshape(512, n // 2)[rows].ravel()
+    np.testing.assert_array_equal(p1, o["packed1"])
+    np.testing.assert_array_equal(p2, o["packed2"])
+    one = B.dual_quantize_alternating(torch.from_numpy(w).cuda(), p, 1e-3, 1)
+    assert np.all(r.sse.cpu().numpy() <= one.sse.cpu().numpy())
