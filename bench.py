@@ -111,6 +111,59 @@ def bench_activation(args, cfg, torch, B) -> int:
     return 0
 
 
+def bench_dual(args, cfg, torch, B) -> int:
+    """Algorithm 1 iterated (two INT4 tensors per kernel, eps 1e-3, at most 4 sweeps) on every weight tensor."""
+    G = args.grid_points if args.grid_points > 0 else cfg.grid_points
+    iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
+    eps, max_sweeps = 1e-3, 4
+    host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]
+    dev_w = [torch.from_numpy(w).cuda() for w in host_w]
+    p = B.params(-8, 7, G, iters, args.cands_per_lane)
+    plan = B.DualBatchedPlan(dev_w, p, eps, max_sweeps)
+    outs = plan.run()
+    step = plan.run
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # evaluations of the sweeps whose result was kept (a lower bound of the work done: a last,
+    # discarded sweep is not counted)
+    evals = sum(int(o.sweeps.sum().item()) * w.shape[1] * 2 * (G + 2 + iters) for o, w in zip(outs, host_w))
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        sample_evals, ok = 0, True
+        for w, o in zip(host_w, outs):
+            rows = np.unique(np.linspace(0, w.shape[0] - 1, 8).astype(int))
+            ref = oracle.can_dual_alternating(np.ascontiguousarray(w[rows]), -8, 7, G, iters, eps, max_sweeps)
+            sample_evals += int(ref["sweeps"].sum()) * w.shape[1] * 2 * (G + 2 + iters)
+            ok = ok and np.array_equal(o.sweeps.cpu().numpy()[rows], ref["sweeps"]) \
+                and np.array_equal(o.scale1.cpu().numpy()[rows], ref["scale1"]) \
+                and np.array_equal(o.scale2.cpu().numpy()[rows], ref["scale2"]) \
+                and np.allclose(o.sse.cpu().numpy()[rows], ref["sse"], rtol=1e-4, atol=0)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": sample_evals / dt, "unit": "evals/s", "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": "8 kernels of every tensor", "seconds": round(dt, 3)}
+        parity = bool(ok)
+    print(json.dumps({
+        "metric": METRIC, "value": evals / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] weights, two INT4 tensors per kernel by "
+                               f"alternating optimisation (eps {eps}, <= {max_sweeps} sweeps)",
+                   "tensors": len(host_w), "weights": sum(w.size for w in host_w), "grid_points": G,
+                   "refine_iters": iters, "evals_per_step_kept_sweeps": evals,
+                   "mean_sweeps": float(np.mean(np.concatenate([o.sweeps.cpu().numpy() for o in outs])))},
+        "roofline": None, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,7 +173,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="BASELINE.json configuration (weights part)")
     ap.add_argument("--cands-per-lane", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--part", choices=("weights", "activation"), default="weights",
+    ap.add_argument("--part", choices=("weights", "activation", "dual"), default="weights",
                     help="weights: the whole-net kernel-wise path (default); activation: the largest "
                          "calibration tensor of the configuration through the per-layer path")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -154,6 +207,8 @@ def main() -> int:
     cfg = synth.config(args.config)
     if args.part == "activation":
         return bench_activation(args, cfg, torch, B)
+    if args.part == "dual":
+        return bench_dual(args, cfg, torch, B)
     G = args.grid_points if args.grid_points > 0 else cfg.grid_points
     iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
     host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]

@@ -129,11 +129,29 @@ int residual_quantize(const float *w_dev, int64_t K, int64_t n, const float *sca
  * kernel); packed1_dev / packed2_dev: codes of the two tensors, ceil(K*n/2) bytes each, layout as in
  * quantize_pack_int4.  All max_sweeps sweeps are enqueued at once; kernels that have stopped are skipped
  * on the device.  Workspace: mmse_workspace_bytes_dual. */
+typedef struct mmse_dual_desc_t {
+    const float *w_dev;        /* [K][n]                      */
+    int64_t K, n;
+    float *scale1_dev;         /* [K]                         */
+    float *scale2_dev;         /* [K]                         */
+    uint8_t *packed1_dev;      /* ceil(K*n/2) bytes           */
+    uint8_t *packed2_dev;      /* ceil(K*n/2) bytes           */
+    double *sse_dev;           /* [K]                         */
+    int32_t *sweeps_dev;       /* [K]                         */
+} mmse_dual_desc_t;
+
 int mmse_workspace_bytes_dual(int64_t K, int64_t n, const mmse_params_t *p, size_t *bytes_out);
 int dual_quantize_alternating(const float *w_dev, int64_t K, int64_t n, const mmse_params_t *p,
                               double eps, int32_t max_sweeps,
                               float *scale1_dev, float *scale2_dev, uint8_t *packed1_dev, uint8_t *packed2_dev,
                               double *sse_dev, int32_t *sweeps_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* The same for `count` layers described in HOST memory; every phi runs as one batched launch over
+ * all layers.  Workspace: mmse_workspace_bytes_dual_batched (the sum of the per-layer sizes). */
+int mmse_workspace_bytes_dual_batched(const mmse_dual_desc_t *descs_host, int32_t count,
+                                      const mmse_params_t *p, size_t *bytes_out);
+int dual_quantize_alternating_batched(const mmse_dual_desc_t *descs_host, int32_t count, const mmse_params_t *p,
+                                      double eps, int32_t max_sweeps, void *ws_dev, size_t ws_bytes, void *stream);
 
 /* Whole network in a handful of launches: `count` weight tensors described in HOST
  * memory (the descriptors are consumed before the call returns).  Semantics per

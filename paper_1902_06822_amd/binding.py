@@ -21,6 +21,7 @@ EXPORTS = (
     "mmse_scale_search_kernelwise", "mmse_scale_search_activation",
     "quantize_pack_int4", "residual_quantize", "mmse_scale_search_batched",
     "mmse_grid_sse_kernelwise", "mmse_workspace_bytes_dual", "dual_quantize_alternating",
+    "mmse_workspace_bytes_dual_batched", "dual_quantize_alternating_batched",
     "mmse_status_string",
 )
 
@@ -34,6 +35,12 @@ class MmseTensorDesc(C.Structure):
     _fields_ = [("w_dev", C.c_void_p), ("K", C.c_int64), ("n", C.c_int64),
                 ("scale1_dev", C.c_void_p), ("scale_dev", C.c_void_p), ("idx_dev", C.c_void_p),
                 ("sse_dev", C.c_void_p), ("packed_dev", C.c_void_p)]
+
+
+class MmseDualDesc(C.Structure):
+    _fields_ = [("w_dev", C.c_void_p), ("K", C.c_int64), ("n", C.c_int64),
+                ("scale1_dev", C.c_void_p), ("scale2_dev", C.c_void_p), ("packed1_dev", C.c_void_p),
+                ("packed2_dev", C.c_void_p), ("sse_dev", C.c_void_p), ("sweeps_dev", C.c_void_p)]
 
 
 _lib = None
@@ -62,6 +69,9 @@ def load_library() -> C.CDLL:
     lib.mmse_workspace_bytes_dual.argtypes = [i64, i64, pp, szp]
     lib.dual_quantize_alternating.argtypes = [vp, i64, i64, pp, C.c_double, i32, vp, vp, vp, vp, vp, vp, vp,
                                               C.c_size_t, vp]
+    lib.mmse_workspace_bytes_dual_batched.argtypes = [C.POINTER(MmseDualDesc), i32, pp, szp]
+    lib.dual_quantize_alternating_batched.argtypes = [C.POINTER(MmseDualDesc), i32, pp, C.c_double, i32, vp,
+                                                      C.c_size_t, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -272,3 +282,46 @@ def dual_quantize_alternating(w: torch.Tensor, p: MmseParams, eps: float, max_sw
         out.packed1.data_ptr(), out.packed2.data_ptr(), out.sse.data_ptr(), out.sweeps.data_ptr(),
         ws.data_ptr(), ws.numel(), _stream()), "dual_quantize_alternating")
     return out
+
+
+def _dual_outputs(K: int, n: int, device) -> DualResult:
+    nb = (K * n + 1) // 2
+    return DualResult(torch.empty(K, dtype=torch.float32, device=device),
+                      torch.empty(K, dtype=torch.float32, device=device),
+                      torch.empty(nb, dtype=torch.uint8, device=device),
+                      torch.empty(nb, dtype=torch.uint8, device=device),
+                      torch.empty(K, dtype=torch.float64, device=device),
+                      torch.empty(K, dtype=torch.int32, device=device))
+
+
+class DualBatchedPlan:
+    """Host-side descriptor table for ``dual_quantize_alternating_batched`` (buffers allocated once)."""
+
+    def __init__(self, weights: Sequence[torch.Tensor], p: MmseParams, eps: float, max_sweeps: int):
+        self.p, self.eps, self.max_sweeps = p, float(eps), int(max_sweeps)
+        self.weights = list(weights)
+        self.results: List[DualResult] = []
+        self.descs = (MmseDualDesc * len(self.weights))()
+        for i, w in enumerate(self.weights):
+            _dev(w, torch.float32)
+            K, n = w.shape
+            r = _dual_outputs(K, n, w.device)
+            self.results.append(r)
+            self.descs[i] = MmseDualDesc(w.data_ptr(), K, n, r.scale1.data_ptr(), r.scale2.data_ptr(),
+                                         r.packed1.data_ptr(), r.packed2.data_ptr(), r.sse.data_ptr(),
+                                         r.sweeps.data_ptr())
+        need = C.c_size_t(0)
+        _check(load_library().mmse_workspace_bytes_dual_batched(self.descs, len(self.weights), C.byref(p),
+                                                                C.byref(need)), "mmse_workspace_bytes_dual_batched")
+        self.ws = alloc_workspace(need.value, self.weights[0].device)
+
+    def run(self) -> List[DualResult]:
+        _check(load_library().dual_quantize_alternating_batched(
+            self.descs, len(self.weights), C.byref(self.p), self.eps, self.max_sweeps,
+            self.ws.data_ptr(), self.ws.numel(), _stream()), "dual_quantize_alternating_batched")
+        return self.results
+
+
+def dual_quantize_alternating_batched(weights: Sequence[torch.Tensor], p: MmseParams, eps: float,
+                                      max_sweeps: int) -> List[DualResult]:
+    return DualBatchedPlan(weights, p, eps, max_sweeps).run()

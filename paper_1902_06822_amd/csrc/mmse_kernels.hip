@@ -708,57 +708,88 @@ __global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
 // ---------------------------------------------------------------------------------
 // Algorithm 1 iterated (Section 3.5): bookkeeping between alternating sweeps, per kernel
 // ---------------------------------------------------------------------------------
-// After the first sweep: a kernel goes on iterating unless it was rejected or is already exact.
-__global__ void __launch_bounds__(256) k_dual_init(int K, const double* __restrict__ sse, uint8_t* active,
-                                                   int32_t* sweeps)
+constexpr int kMaxDualBatch = 24;
+
+struct DualTensor {
+    double* sse;             // kept error per kernel
+    const double* tsse;      // error of the tentative sweep
+    float* s1; const float* ts1;
+    float* s2; const float* ts2;
+    int32_t* sweeps;
+    uint8_t* active;
+    uint8_t* accepted;
+    const uint8_t* tp1; uint8_t* p1;     // tentative / kept codes of the first tensor
+    const uint8_t* tp2; uint8_t* p2;
+    int K;
+    int n;
+};
+
+struct DualBatch {
+    DualTensor t[kMaxDualBatch];
+    int start[kMaxDualBatch + 1];        // prefix sum of workgroups per tensor
+    int count;
+    double eps;
+};
+
+__device__ __forceinline__ int find_dual_tensor(const DualBatch& D, int bid)
 {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= K) return;
-    const double e = sse[k];
+    int t = 0;
+    while (t + 1 < D.count && bid >= D.start[t + 1]) ++t;
+    return t;
+}
+
+// After the first sweep: a kernel goes on iterating unless it was rejected or is already exact.
+__global__ void __launch_bounds__(256) k_dual_init(const DualBatch D)
+{
+    const int t = find_dual_tensor(D, blockIdx.x);
+    const DualTensor& T = D.t[t];
+    const int k = (blockIdx.x - D.start[t]) * blockDim.x + threadIdx.x;
+    if (k >= T.K) return;
+    const double e = T.sse[k];
     const bool ok = e == e;
-    sweeps[k] = ok ? 1 : 0;
-    active[k] = (ok && e > 0.0) ? 1 : 0;
+    T.sweeps[k] = ok ? 1 : 0;
+    T.active[k] = (ok && e > 0.0) ? 1 : 0;
 }
 
 // After a later sweep: keep it if it lowered the error; stop when the relative gain is <= eps,
 // when the error reached 0, or when the sweep was no better (then it is discarded).
-__global__ void __launch_bounds__(256) k_dual_accept(int K, double eps, double* sse, const double* __restrict__ t_sse,
-                                                     float* s1, const float* __restrict__ ts1,
-                                                     float* s2, const float* __restrict__ ts2,
-                                                     int32_t* sweeps, uint8_t* active, uint8_t* accepted)
+__global__ void __launch_bounds__(256) k_dual_accept(const DualBatch D)
 {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= K) return;
+    const int t = find_dual_tensor(D, blockIdx.x);
+    const DualTensor& T = D.t[t];
+    const int k = (blockIdx.x - D.start[t]) * blockDim.x + threadIdx.x;
+    if (k >= T.K) return;
     uint8_t acc = 0;
-    if (active[k]) {
-        const double e = sse[k], te = t_sse[k];
+    if (T.active[k]) {
+        const double e = T.sse[k], te = T.tsse[k];
         if (te < e) {
             acc = 1;
-            const bool conv = (e - te) <= eps * e;
-            s1[k] = ts1[k]; s2[k] = ts2[k]; sse[k] = te; sweeps[k] += 1;
-            if (conv || !(te > 0.0)) active[k] = 0;
+            const bool conv = (e - te) <= D.eps * e;
+            T.s1[k] = T.ts1[k]; T.s2[k] = T.ts2[k]; T.sse[k] = te; T.sweeps[k] += 1;
+            if (conv || !(te > 0.0)) T.active[k] = 0;
         } else {
-            active[k] = 0;
+            T.active[k] = 0;
         }
     }
-    accepted[k] = acc;
+    T.accepted[k] = acc;
 }
 
-// Codes of the kernels whose sweep was kept move from the tentative to the final buffers, nibble by
+// Codes of the kernels whose sweep was kept move from the tentative to the kept buffers, nibble by
 // nibble (a byte can hold codes of two kernels when n is odd).
-__global__ void __launch_bounds__(256) k_dual_copy_codes(long long total, int n, const uint8_t* __restrict__ accepted,
-                                                         const uint8_t* __restrict__ t1, uint8_t* p1,
-                                                         const uint8_t* __restrict__ t2, uint8_t* p2)
+__global__ void __launch_bounds__(256) k_dual_copy_codes(const DualBatch D)
 {
-    const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int t = find_dual_tensor(D, blockIdx.x);
+    const DualTensor& T = D.t[t];
+    const long long total = (long long)T.K * T.n;
+    const long long b = (long long)(blockIdx.x - D.start[t]) * blockDim.x + threadIdx.x;
     if (2 * b >= total) return;
     const unsigned e0 = (unsigned)(2 * b);
-    const bool a0 = accepted[e0 / (unsigned)n] != 0;
-    const bool a1 = (long long)e0 + 1 < total && accepted[(e0 + 1) / (unsigned)n] != 0;
+    const bool a0 = T.accepted[e0 / (unsigned)T.n] != 0;
+    const bool a1 = (long long)e0 + 1 < total && T.accepted[(e0 + 1) / (unsigned)T.n] != 0;
     if (!a0 && !a1) return;
     const unsigned mask = (a0 ? 0x0Fu : 0u) | (a1 ? 0xF0u : 0u);
-    p1[b] = (uint8_t)((p1[b] & ~mask) | (t1[b] & mask));
-    p2[b] = (uint8_t)((p2[b] & ~mask) | (t2[b] & mask));
+    T.p1[b] = (uint8_t)((T.p1[b] & ~mask) | (T.tp1[b] & mask));
+    T.p2[b] = (uint8_t)((T.p2[b] & ~mask) | (T.tp2[b] & mask));
 }
 
 // ---------------------------------------------------------------------------------
@@ -1482,67 +1513,136 @@ int mmse_workspace_bytes_dual(int64_t K, int64_t n, const mmse_params_t* p, size
     return MMSE_OK;
 }
 
+int dual_quantize_alternating_batched(const mmse_dual_desc_t* descs_host, int32_t count, const mmse_params_t* p,
+                                      double eps, int32_t max_sweeps, void* ws_dev, size_t ws_bytes, void* stream)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (!descs_host) return MMSE_ERR_NULL;
+    if (count <= 0 || count > 4096) return MMSE_ERR_SIZE;
+    if (!(eps >= 0.0) || max_sweeps < 1 || max_sweeps > 64) return MMSE_ERR_PARAMS;
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) {
+        const mmse_dual_desc_t& d = descs_host[i];
+        if (!d.w_dev || !d.scale1_dev || !d.scale2_dev || !d.packed1_dev || !d.packed2_dev || !d.sse_dev || !d.sweeps_dev)
+            return MMSE_ERR_NULL;
+        if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS || d.K > MMSE_MAX_TENSOR_ELEMS / d.n) return MMSE_ERR_SIZE;
+        if (!aligned_to(d.w_dev, 4) || !aligned_to(d.scale1_dev, 4) || !aligned_to(d.scale2_dev, 4) ||
+            !aligned_to(d.sse_dev, 8) || !aligned_to(d.sweeps_dev, 4))
+            return MMSE_ERR_ALIGN;
+        need += plan_dual(d.K, d.n).bytes;
+    }
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < need) return MMSE_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    struct W { float* absmax; int32_t* idx; float *ts1, *ts2; double *tsse1, *tsse; uint8_t *active, *accepted, *tp1, *tp2; };
+    W* wk = new W[count]();
+    Item* items = new Item[count]();
+    {
+        char* ws = static_cast<char*>(ws_dev);
+        for (int i = 0; i < count; ++i) {
+            const DualPlan P = plan_dual(descs_host[i].K, descs_host[i].n);
+            wk[i].absmax = reinterpret_cast<float*>(ws + P.absmax);
+            wk[i].idx = reinterpret_cast<int32_t*>(ws + P.idx);
+            wk[i].ts1 = reinterpret_cast<float*>(ws + P.ts1);
+            wk[i].ts2 = reinterpret_cast<float*>(ws + P.ts2);
+            wk[i].tsse1 = reinterpret_cast<double*>(ws + P.tsse1);
+            wk[i].tsse = reinterpret_cast<double*>(ws + P.tsse);
+            wk[i].active = reinterpret_cast<uint8_t*>(ws + P.active);
+            wk[i].accepted = reinterpret_cast<uint8_t*>(ws + P.accepted);
+            wk[i].tp1 = reinterpret_cast<uint8_t*>(ws + P.tp1);
+            wk[i].tp2 = reinterpret_cast<uint8_t*>(ws + P.tp2);
+            ws += P.bytes;
+        }
+    }
+    // one phi for every tensor: which = 0 first sweep j=1, 1 first sweep j=2, 2 later sweep j=1, 3 later sweep j=2
+    auto fit = [&](int which) -> int {
+        for (int i = 0; i < count; ++i) {
+            const mmse_dual_desc_t& d = descs_host[i];
+            TensorArgs a{};
+            a.w = d.w_dev; a.idx = wk[i].idx; a.absmax = wk[i].absmax; a.K = (int)d.K; a.n = (int)d.n;
+            if (which == 0) { a.scale = d.scale1_dev; a.sse = wk[i].tsse1; a.packed = d.packed1_dev; }
+            if (which == 1) { a.sub_packed = d.packed1_dev; a.sub_scale = d.scale1_dev;
+                              a.scale = d.scale2_dev; a.sse = d.sse_dev; a.packed = d.packed2_dev; }
+            if (which == 2) { a.sub_packed = d.packed2_dev; a.sub_scale = d.scale2_dev; a.active = wk[i].active;
+                              a.scale = wk[i].ts1; a.sse = wk[i].tsse1; a.packed = wk[i].tp1; }
+            if (which == 3) { a.sub_packed = wk[i].tp1; a.sub_scale = wk[i].ts1; a.active = wk[i].active;
+                              a.scale = wk[i].ts2; a.sse = wk[i].tsse; a.packed = wk[i].tp2; }
+            items[i].a = a;
+            items[i].order = i;
+        }
+        return run_weight_tensors(items, count, p, true, s);
+    };
+    // bookkeeping kernels over all tensors: kind 0 init, 1 accept, 2 copy codes
+    auto book = [&](int kind) -> int {
+        for (int b0 = 0; b0 < count; b0 += kMaxDualBatch) {
+            DualBatch D{};
+            D.eps = eps;
+            const int nb = (count - b0) < kMaxDualBatch ? (count - b0) : kMaxDualBatch;
+            int wg = 0;
+            for (int j = 0; j < nb; ++j) {
+                const mmse_dual_desc_t& d = descs_host[b0 + j];
+                const W& w = wk[b0 + j];
+                DualTensor& T = D.t[j];
+                T.sse = d.sse_dev; T.tsse = w.tsse; T.s1 = d.scale1_dev; T.ts1 = w.ts1; T.s2 = d.scale2_dev; T.ts2 = w.ts2;
+                T.sweeps = d.sweeps_dev; T.active = w.active; T.accepted = w.accepted;
+                T.tp1 = w.tp1; T.p1 = d.packed1_dev; T.tp2 = w.tp2; T.p2 = d.packed2_dev;
+                T.K = (int)d.K; T.n = (int)d.n;
+                D.start[j] = wg;
+                const long long units = kind == 2 ? ((long long)d.K * d.n + 1) / 2 : d.K;
+                wg += (int)((units + 255) / 256);
+            }
+            D.start[nb] = wg;
+            D.count = nb;
+            if (kind == 0) hipLaunchKernelGGL(k_dual_init, dim3(wg), dim3(256), 0, s, D);
+            else if (kind == 1) hipLaunchKernelGGL(k_dual_accept, dim3(wg), dim3(256), 0, s, D);
+            else hipLaunchKernelGGL(k_dual_copy_codes, dim3(wg), dim3(256), 0, s, D);
+            if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+        }
+        return MMSE_OK;
+    };
+
+    // first sweep, from an empty second tensor: the plain fit, then the fit of what it leaves
+    rc = fit(0);
+    if (!rc) rc = fit(1);
+    if (!rc) rc = book(0);
+    for (int sweep = 1; sweep < max_sweeps && !rc; ++sweep) {
+        rc = fit(2);                    // j = 1: T - a2*Q2
+        if (!rc) rc = fit(3);           // j = 2: T - a1*Q1
+        if (!rc) rc = book(1);
+        if (!rc) rc = book(2);
+    }
+    delete[] items;
+    delete[] wk;
+    return rc;
+}
+
+int mmse_workspace_bytes_dual_batched(const mmse_dual_desc_t* descs_host, int32_t count, const mmse_params_t* p,
+                                      size_t* bytes_out)
+{
+    if (!bytes_out || !descs_host) return MMSE_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc) return rc;
+    if (count <= 0 || count > 4096) return MMSE_ERR_SIZE;
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) {
+        const mmse_dual_desc_t& d = descs_host[i];
+        if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS || d.K > MMSE_MAX_TENSOR_ELEMS / d.n) return MMSE_ERR_SIZE;
+        need += plan_dual(d.K, d.n).bytes;
+    }
+    *bytes_out = need;
+    return MMSE_OK;
+}
+
 int dual_quantize_alternating(const float* w_dev, int64_t K, int64_t n, const mmse_params_t* p,
                               double eps, int32_t max_sweeps,
                               float* scale1_dev, float* scale2_dev, uint8_t* packed1_dev, uint8_t* packed2_dev,
                               double* sse_dev, int32_t* sweeps_dev, void* ws_dev, size_t ws_bytes, void* stream)
 {
-    int rc = check_params(p);
-    if (rc) return rc;
-    if (!w_dev || !scale1_dev || !scale2_dev || !packed1_dev || !packed2_dev || !sse_dev || !sweeps_dev)
-        return MMSE_ERR_NULL;
-    if (K <= 0 || n <= 0 || n > MMSE_MAX_KERNEL_ELEMS || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
-    if (!(eps >= 0.0) || max_sweeps < 1 || max_sweeps > 64) return MMSE_ERR_PARAMS;
-    if (!aligned_to(w_dev, 4) || !aligned_to(scale1_dev, 4) || !aligned_to(scale2_dev, 4) ||
-        !aligned_to(sse_dev, 8) || !aligned_to(sweeps_dev, 4))
-        return MMSE_ERR_ALIGN;
-    const DualPlan P = plan_dual(K, n);
-    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < P.bytes) return MMSE_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    char* ws = static_cast<char*>(ws_dev);
-    float* absmax = reinterpret_cast<float*>(ws + P.absmax);
-    int32_t* idx = reinterpret_cast<int32_t*>(ws + P.idx);
-    float* ts1 = reinterpret_cast<float*>(ws + P.ts1);
-    float* ts2 = reinterpret_cast<float*>(ws + P.ts2);
-    double* tsse1 = reinterpret_cast<double*>(ws + P.tsse1);
-    double* tsse = reinterpret_cast<double*>(ws + P.tsse);
-    uint8_t* active = reinterpret_cast<uint8_t*>(ws + P.active);
-    uint8_t* accepted = reinterpret_cast<uint8_t*>(ws + P.accepted);
-    uint8_t* tp1 = reinterpret_cast<uint8_t*>(ws + P.tp1);
-    uint8_t* tp2 = reinterpret_cast<uint8_t*>(ws + P.tp2);
-
-    auto fit = [&](const uint8_t* sub, const float* sub_scale, const uint8_t* mask,
-                   float* out_scale, double* out_sse, uint8_t* out_packed) -> int {
-        Item it{};
-        it.a.w = w_dev; it.a.scale = out_scale; it.a.idx = idx; it.a.sse = out_sse; it.a.absmax = absmax;
-        it.a.packed = out_packed; it.a.sub_packed = sub; it.a.sub_scale = sub_scale; it.a.active = mask;
-        it.a.K = (int)K; it.a.n = (int)n;
-        return run_weight_tensors(&it, 1, p, true, s);
-    };
-    const int kb = (int)((K + 255) / 256);
-    const long long total = (long long)K * n;
-
-    // first sweep, from an empty second tensor: the plain fit, then the fit of what it leaves
-    rc = fit(nullptr, nullptr, nullptr, scale1_dev, tsse1, packed1_dev);
-    if (rc) return rc;
-    rc = fit(packed1_dev, scale1_dev, nullptr, scale2_dev, sse_dev, packed2_dev);
-    if (rc) return rc;
-    hipLaunchKernelGGL(k_dual_init, dim3(kb), dim3(256), 0, s, (int)K, sse_dev, active, sweeps_dev);
-    if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
-    for (int sweep = 1; sweep < max_sweeps; ++sweep) {
-        rc = fit(packed2_dev, scale2_dev, active, ts1, tsse1, tp1);          // j = 1: T - a2*Q2
-        if (rc) return rc;
-        rc = fit(tp1, ts1, active, ts2, tsse, tp2);                          // j = 2: T - a1*Q1
-        if (rc) return rc;
-        hipLaunchKernelGGL(k_dual_accept, dim3(kb), dim3(256), 0, s, (int)K, eps, sse_dev, tsse,
-                           scale1_dev, ts1, scale2_dev, ts2, sweeps_dev, active, accepted);
-        if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
-        const long long nbytes = (total + 1) / 2;
-        hipLaunchKernelGGL(k_dual_copy_codes, dim3((unsigned)((nbytes + 255) / 256)), dim3(256), 0, s, total, (int)n,
-                           accepted, tp1, packed1_dev, tp2, packed2_dev);
-        if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
-    }
-    return MMSE_OK;
+    mmse_dual_desc_t d{};
+    d.w_dev = w_dev; d.K = K; d.n = n; d.scale1_dev = scale1_dev; d.scale2_dev = scale2_dev;
+    d.packed1_dev = packed1_dev; d.packed2_dev = packed2_dev; d.sse_dev = sse_dev; d.sweeps_dev = sweeps_dev;
+    return dual_quantize_alternating_batched(&d, 1, p, eps, max_sweeps, ws_dev, ws_bytes, stream);
 }
 
 int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_params_t* p,

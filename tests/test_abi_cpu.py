@@ -38,6 +38,7 @@ def test_struct_layouts_match_header(B):
     assert C.sizeof(B.MmseParams) == 20
     assert C.sizeof(B.MmseTensorDesc) == 64
     assert B.MmseTensorDesc.K.offset == 8 and B.MmseTensorDesc.packed_dev.offset == 56
+    assert C.sizeof(B.MmseDualDesc) == 72 and B.MmseDualDesc.sweeps_dev.offset == 64
 
 
 def test_status_strings(B):
@@ -84,6 +85,11 @@ def test_entry_points_validate_before_enqueue(B):
     assert lib.residual_quantize(a, 4, 4, None, C.byref(p), a, a, a, a, a, 4096, None) == -1
     assert lib.mmse_scale_search_batched(None, 1, C.byref(p), a, 4096, None) == -1
     assert lib.mmse_grid_sse_kernelwise(a, 4, 4, C.byref(p), None, a, None) == -1
+    assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), 1e-3, 4, a, a, None, a, a, a, a, 1 << 20, None) == -1
+    assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), -1.0, 4, a, a, a, a, a, a, a, 1 << 20, None) == -3
+    assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), 1e-3, 0, a, a, a, a, a, a, a, 1 << 20, None) == -3
+    assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), 1e-3, 4, a, a, a, a, a, a, a, 256, None) == -4
+    assert lib.dual_quantize_alternating_batched(None, 1, C.byref(p), 1e-3, 4, a, 1 << 20, None) == -1
     # sizes
     assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
     assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2

@@ -110,3 +110,23 @@ def test_dual_alternating_config5_layer_sample(B):
     np.testing.assert_array_equal(p2, o["packed2"])
     one = B.dual_quantize_alternating(torch.from_numpy(w).cuda(), p, 1e-3, 1)
     assert np.all(r.sse.cpu().numpy() <= one.sse.cpu().numpy())
+
+
+def test_dual_alternating_batched_whole_network(B):
+    """Configuration 1's layer plus a mix of shapes through the batched entry point (the shape bench.py times)."""
+    import torch
+    say("dual batched")
+    c = synth.config(1)
+    ws = [c.weight_tensor(0), synth.small_weights(40, 9, 1, "outliers"), synth.small_weights(10, 147, 2, "laplace"),
+          synth.small_weights(6, 4608, 3, "student"), synth.small_weights(16, 64, 4, "normal")]
+    p = B.params(*SIGNED, 128, 20)
+    res = B.dual_quantize_alternating_batched([torch.from_numpy(w).cuda() for w in ws], p, 1e-3, 4)
+    torch.cuda.synchronize()
+    for i, (w, r) in enumerate(zip(ws, res)):
+        o = oracle.can_dual_alternating(w, *SIGNED, 128, 20, 1e-3, 4)
+        np.testing.assert_array_equal(r.sweeps.cpu().numpy(), o["sweeps"], err_msg=f"tensor {i}")
+        np.testing.assert_array_equal(r.scale1.cpu().numpy(), o["scale1"], err_msg=f"tensor {i}")
+        np.testing.assert_array_equal(r.scale2.cpu().numpy(), o["scale2"], err_msg=f"tensor {i}")
+        np.testing.assert_array_equal(r.sse.cpu().numpy(), o["sse"], err_msg=f"tensor {i}")
+        np.testing.assert_array_equal(r.packed1.cpu().numpy(), o["packed1"], err_msg=f"tensor {i}")
+        np.testing.assert_array_equal(r.packed2.cpu().numpy(), o["packed2"], err_msg=f"tensor {i}")
