@@ -429,6 +429,85 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 }
 
 // ---------------------------------------------------------------------------------
+// k_sweep_small: the same for kernels of at most 64 elements (depthwise 3x3, first layers,
+// narrow pointwise layers): one WAVE per kernel, four kernels per workgroup, no LDS and no
+// barrier.  Lane i holds element i; an element reaches all lanes as a scalar operand
+// (v_readlane), lanes own C = ceil(G/64) candidates each; a single chunk needs no tree.
+// ---------------------------------------------------------------------------------
+template <int C>
+__global__ void __launch_bounds__(256) k_sweep_small(const Batch B)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = find_tensor(B, blockIdx.x);
+    const TensorArgs& A = B.t[t];
+    const int k = (blockIdx.x - B.start[t]) * 4 + wave;
+    if (k >= A.K) return;                                     // waves are independent: no barrier below
+    if (A.active != nullptr && A.active[k] == 0) return;
+    const int n = A.n;                                        // <= 64
+    const float lo = B.lo, hi = B.hi;
+    const Xform X = make_xform(A, k, lo, true);
+    const long long flat0 = (long long)k * n;
+    const float x = lane < n ? xform_apply(X, A.w[flat0 + lane], flat0 + lane, lo, hi) : 0.0f;
+    const float a = __uint_as_float(wave_max_u32(abs_bits(x)));
+
+    const int G = B.G;
+    if (!(a <= kHuge)) {
+        const float nanf_ = __uint_as_float(0x7fc00000u);
+        if (lane == 0) {
+            if (A.absmax) A.absmax[k] = a;
+            if (A.scale) A.scale[k] = nanf_;
+            if (A.idx) A.idx[k] = -1;
+            if (A.sse) A.sse[k] = (double)nanf_;
+        }
+        if (A.grid_sse)
+            for (int j = lane; j < G; j += 64) A.grid_sse[(size_t)k * G + j] = (double)nanf_;
+        return;
+    }
+    const bool tiny = a < kTiny;
+    const float qmaxf = (float)B.qmax, Gf = (float)G;
+    float alpha[C], inv[C], s[C];
+    int jcand[C];
+#pragma unroll
+    for (int u = 0; u < C; ++u) {
+        const int j = u * 64 + lane;
+        jcand[u] = j;
+        const int jj = j < G ? j : G - 1;
+        alpha[u] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, jj);
+        inv[u] = 1.0f / alpha[u];
+        s[u] = 0.0f;
+    }
+    constexpr int NE = (C >= 4) ? 4 : 8;
+    const int xb = __float_as_int(x);
+    for (int e0 = 0; e0 < n; e0 += NE) {                      // lanes >= n hold 0: exact no-ops
+        float xs[NE];
+#pragma unroll
+        for (int i = 0; i < NE; ++i) xs[i] = __int_as_float(__builtin_amdgcn_readlane(xb, (e0 + i) & 63));
+        eval_stage<NE, C>(xs, alpha, inv, lo, hi, s);
+    }
+    double E[C];
+#pragma unroll
+    for (int u = 0; u < C; ++u) E[u] = (double)s[u];
+    if (A.grid_sse) {
+#pragma unroll
+        for (int u = 0; u < C; ++u)
+            if (jcand[u] < G) A.grid_sse[(size_t)k * G + jcand[u]] = E[u];
+    }
+    double bE = __longlong_as_double(0x7ff0000000000000LL);
+    int bJ = INT_MAX;
+#pragma unroll
+    for (int u = 0; u < C; ++u)
+        if (jcand[u] < G && E[u] < bE) { bE = E[u]; bJ = jcand[u]; }
+    wave_argmin(bE, bJ);
+    if (lane == 0) {
+        if (bJ == INT_MAX) bJ = 0;
+        if (A.absmax) A.absmax[k] = a;
+        if (A.idx) A.idx[k] = bJ;
+        if (A.sse) A.sse[k] = bE;
+        if (A.scale) A.scale[k] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, bJ);
+    }
+}
+
+// ---------------------------------------------------------------------------------
 // k_refine_kernelwise: golden-section refinement between the grid neighbours of j*
 // ---------------------------------------------------------------------------------
 // Pairwise sum across the m lanes (chunks) of one kernel through LDS, three tree levels
@@ -1242,21 +1321,46 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
         items[j + 1] = it;
     }
     if (do_search) {
-        for (int b0 = 0; b0 < count; b0 += kMaxBatch) {
+        // kernels of <= 64 elements go to the one-wave-per-kernel path (when the grid fits 8 candidates a lane)
+        // ... and when there are enough of them to pay for a launch of their own
+        long long small_rows = 0;
+        for (int i = 0; i < count; ++i)
+            if (items[i].a.n <= kChunk) small_rows += items[i].a.K;
+        const bool small_ok = G <= 512 && small_rows >= 2048;
+        for (int pass = 0; pass < 2; ++pass) {                 // 0: general kernels, 1: small ones
             Batch B{};
             fill_common(B, p);
-            const int nb = (count - b0) < kMaxBatch ? (count - b0) : kMaxBatch;
-            int wg = 0, max_npad = 0;
-            for (int i = 0; i < nb; ++i) {
-                B.t[i] = items[b0 + i].a;
-                B.start[i] = wg;
-                wg += B.t[i].K;
-                const int npad = (B.t[i].n + kChunk - 1) & ~(kChunk - 1);
+            int nb = 0, wg = 0, max_npad = 0;
+            auto flush = [&]() -> int {
+                if (nb == 0) return MMSE_OK;
+                B.start[nb] = wg;
+                B.count = nb;
+                int rc = MMSE_OK;
+                if (pass == 0) {
+                    rc = launch_sweep_any(C, B, wg, G, max_npad, s);
+                } else {
+                    const int cs = (G + 63) / 64;
+                    if (cs <= 1) hipLaunchKernelGGL(k_sweep_small<1>, dim3(wg), dim3(256), 0, s, B);
+                    else if (cs <= 2) hipLaunchKernelGGL(k_sweep_small<2>, dim3(wg), dim3(256), 0, s, B);
+                    else if (cs <= 4) hipLaunchKernelGGL(k_sweep_small<4>, dim3(wg), dim3(256), 0, s, B);
+                    else hipLaunchKernelGGL(k_sweep_small<8>, dim3(wg), dim3(256), 0, s, B);
+                    rc = hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+                }
+                nb = 0; wg = 0; max_npad = 0;
+                return rc;
+            };
+            for (int i = 0; i < count; ++i) {
+                const TensorArgs& a = items[i].a;
+                const bool small = small_ok && a.n <= kChunk;
+                if (small != (pass == 1)) continue;
+                B.t[nb] = a;
+                B.start[nb] = wg;
+                wg += pass == 0 ? a.K : (a.K + 3) / 4;
+                const int npad = (a.n + kChunk - 1) & ~(kChunk - 1);
                 max_npad = npad > max_npad ? npad : max_npad;
+                if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
             }
-            B.start[nb] = wg;
-            B.count = nb;
-            const int rc = launch_sweep_any(C, B, wg, G, max_npad, s);
+            const int rc = flush();
             if (rc) return rc;
         }
         if (p->refine_iters > 0) {

@@ -83,6 +83,38 @@ def test_kernelwise_search_matches_oracle(B, K, n, kind):
     assert_search_equal(r.scale.cpu().numpy(), r.idx.cpu().numpy(), r.sse.cpu().numpy(), s, i, e)
 
 
+@pytest.mark.parametrize("K,n,G", [(2500, 9, 256), (2100, 27, 50), (2048, 64, 128), (2300, 16, 512),
+                                   (2050, 33, 500), (4096, 1, 64), (2200, 57, 300)])
+def test_small_kernel_path_matches_oracle(B, K, n, G):
+    """Layers with thousands of kernels of <= 64 elements take the one-wave-per-kernel sweep
+    (1, 2, 4 or 8 candidates per lane depending on G); degenerate rows included."""
+    say(f"small-kernel path K={K} n={n} G={G}")
+    w = synth.small_weights(K, n, 6000 + n + G, "outliers")
+    w[3] = 0.0
+    w[5, 0] = np.nan
+    w[7] = 1e-25
+    p = B.params(*SIGNED, G, 20)
+    wd = to_dev(w)
+    absmax, grid = B.mmse_grid_sse_kernelwise(wd, p)
+    r = B.mmse_scale_search_kernelwise(wd, p)
+    s, i, e = oracle.can_search_kernelwise(w, *SIGNED, G, 20)
+    ok = np.ones(K, bool)
+    ok[5] = False
+    np.testing.assert_array_equal(r.idx.cpu().numpy(), i)
+    np.testing.assert_array_equal(r.scale.cpu().numpy()[ok], s[ok])
+    np.testing.assert_array_equal(r.sse.cpu().numpy()[ok], e[ok])
+    assert np.isnan(r.scale.cpu().numpy()[5]) and np.isnan(r.sse.cpu().numpy()[5])
+    grid = grid.cpu().numpy()
+    for k in (0, 1, 3, 7, 100, K - 1):
+        o = oracle.can_search(w[k], *SIGNED, G, 0, want_grid=True)
+        np.testing.assert_array_equal(grid[k], o["grid_sse"], err_msg=f"k={k}")
+    r2 = B.residual_quantize(wd, r.scale, p)
+    s2, i2, e2, p2 = oracle.can_residual_quantize(w[ok], s[ok], *SIGNED, G, 20)
+    np.testing.assert_array_equal(r2.idx.cpu().numpy()[ok], i2)
+    np.testing.assert_array_equal(r2.scale.cpu().numpy()[ok], s2)
+    np.testing.assert_array_equal(r2.sse.cpu().numpy()[ok], e2)
+
+
 @pytest.mark.parametrize("G,iters,qr", [(128, 20, SIGNED), (500, 20, SIGNED), (50, 20, UNSIGNED),
                                         (256, 0, SIGNED), (512, 20, UNSIGNED), (1, 5, SIGNED),
                                         (2048, 3, SIGNED), (64, 64, SIGNED)])
