@@ -51,6 +51,13 @@ def _load():
         "can_residual_quantize": (None, [f32p, i64, i64, f32p, i32, i32, i32, i32, f32p, i32p, f64p, u8p]),
         "can_dual_alternating_kernelwise": (None, [f32p, i64, i64, i32, i32, i32, i32, f64, i32,
                                                    f32p, f32p, u8p, u8p, f64p, i32p]),
+        "def_dual_sse": (f64, [f32p, i64, f64, f64, i32, i32]),
+        "can_dual_sse": (f64, [f32p, i64, f32, f32, i32, i32]),
+        "can_dual_alpha2": (f32, [f32, i32, i32]),
+        "can_dual_codes": (None, [f32p, i64, f32, f32, i32, i32, i32p, i32p]),
+        "can_dual_linesearch": (i32, [f32p, i64, i32, i32, i32, i32, f32p, f32p, i32p, i32p, f64p, i32p, i32p, f64p]),
+        "can_dual_linesearch_kernelwise": (None, [f32p, i64, i64, i32, i32, i32, i32, f32p, f32p, i32p, i32p, f64p,
+                                                  u8p, u8p]),
         "oracle_num_threads": (i32, []),
     }
     for name, (res, args) in sig.items():
@@ -223,4 +230,60 @@ def can_dual_alternating(w, qmin: int, qmax: int, G: int, iters: int, eps: float
         _p(w, C.c_float), K, n, qmin, qmax, G, iters, float(eps), int(max_sweeps),
         _p(out["scale1"], C.c_float), _p(out["scale2"], C.c_float), _p(out["packed1"], C.c_uint8),
         _p(out["packed2"], C.c_uint8), _p(out["sse"], C.c_double), _p(out["sweeps"], C.c_int32))
+    return out
+
+
+# ------------------------------------------------------------------ dual line search (Eq. 12)
+def def_dual_sse(x, a1: float, a2: float, qmin: int, qmax: int) -> float:
+    x = _f32(x).ravel()
+    return float(_load().def_dual_sse(_p(x, C.c_float), x.size, float(a1), float(a2), qmin, qmax))
+
+
+def can_dual_sse(x, a1, a2, qmin: int, qmax: int) -> float:
+    x = _f32(x).ravel()
+    return float(_load().can_dual_sse(_p(x, C.c_float), x.size, float(np.float32(a1)), float(np.float32(a2)),
+                                      qmin, qmax))
+
+
+def can_dual_alpha2(a1, G2: int, b: int) -> np.float32:
+    return np.float32(_load().can_dual_alpha2(float(np.float32(a1)), G2, b))
+
+
+def can_dual_codes(x, a1, a2, qmin: int, qmax: int):
+    x = _f32(x).ravel()
+    q1 = np.zeros(x.size, np.int32)
+    q2 = np.zeros(x.size, np.int32)
+    _load().can_dual_codes(_p(x, C.c_float), x.size, float(np.float32(a1)), float(np.float32(a2)), qmin, qmax,
+                           _p(q1, C.c_int32), _p(q2, C.c_int32))
+    return q1, q2
+
+
+def can_dual_linesearch(x, qmin: int, qmax: int, G1: int, G2: int, want_grid: bool = False):
+    x = _f32(x).ravel()
+    a1, a2 = np.zeros(1, np.float32), np.zeros(1, np.float32)
+    ia, ib = np.zeros(1, np.int32), np.zeros(1, np.int32)
+    sse = np.zeros(1, np.float64)
+    q1, q2 = np.zeros(x.size, np.int32), np.zeros(x.size, np.int32)
+    grid = np.zeros((G1, G2), np.float64) if want_grid else None
+    rc = _load().can_dual_linesearch(_p(x, C.c_float), x.size, qmin, qmax, G1, G2, _p(a1, C.c_float),
+                                     _p(a2, C.c_float), _p(ia, C.c_int32), _p(ib, C.c_int32), _p(sse, C.c_double),
+                                     _p(q1, C.c_int32), _p(q2, C.c_int32),
+                                     _p(grid, C.c_double) if want_grid else None)
+    out = {"scale1": a1[0], "scale2": a2[0], "idx1": int(ia[0]), "idx2": int(ib[0]), "sse": float(sse[0]),
+           "q1": q1, "q2": q2, "rc": int(rc)}
+    if want_grid:
+        out["grid"] = grid
+    return out
+
+
+def can_dual_linesearch_kernelwise(w, qmin: int, qmax: int, G1: int, G2: int):
+    w = _f32(w)
+    K, n = w.shape
+    out = {"scale1": np.zeros(K, np.float32), "scale2": np.zeros(K, np.float32),
+           "idx1": np.zeros(K, np.int32), "idx2": np.zeros(K, np.int32), "sse": np.zeros(K, np.float64),
+           "packed1": np.zeros((K * n + 1) // 2, np.uint8), "packed2": np.zeros((K * n + 1) // 2, np.uint8)}
+    _load().can_dual_linesearch_kernelwise(
+        _p(w, C.c_float), K, n, qmin, qmax, G1, G2, _p(out["scale1"], C.c_float), _p(out["scale2"], C.c_float),
+        _p(out["idx1"], C.c_int32), _p(out["idx2"], C.c_int32), _p(out["sse"], C.c_double),
+        _p(out["packed1"], C.c_uint8), _p(out["packed2"], C.c_uint8))
     return out

@@ -457,6 +457,146 @@ void can_dual_alternating_kernelwise(const float *w, int64_t K, int64_t n, int q
     free(q1); free(q2);
 }
 
+/* ------------------------------------------------------------------ */
+/* Dual line search (Section 3.5, Eq. 12), two tensors of equal precision */
+/* ------------------------------------------------------------------ */
+
+/* Objective of Eq. 12 for given scales, fp64, true division: per element the best of the
+ * 2^p codes t of the first tensor, the second code being [ (T - a1*t) / a2 ]. */
+double def_dual_sse(const float *x, int64_t n, double a1, double a2, int qmin, int qmax)
+{
+    double e = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double best = INFINITY;
+        for (int t = qmin; t <= qmax; ++t) {
+            double r = (double)x[i] - a1 * (double)t;
+            double d = r - a2 * def_round_sat(r / a2, qmin, qmax);
+            if (d * d < best) best = d * d;
+        }
+        e += best;
+    }
+    return e;
+}
+
+/* One element in the canonical fp32 arithmetic: codes tried in ascending order, the first
+ * of equal errors is kept.  Returns the error; *t_out, *q_out the two codes. */
+static float can_dual_element(float x, float a1, float a2, float inv2, float lo, float hi,
+                              int qmin, int qmax, int *t_out, int *q_out)
+{
+    float best = INFINITY;
+    int bt = qmin, bq = 0;
+    for (int t = qmin; t <= qmax; ++t) {
+        float r = fmaf(-a1, (float)t, x);
+        float q = can_code(r, inv2, lo, hi);
+        float d = fmaf(-a2, q, r);
+        float e = d * d;
+        if (e < best) { best = e; bt = t; bq = (int)q; }
+    }
+    if (t_out) *t_out = bt;
+    if (q_out) *q_out = bq;
+    return best;
+}
+
+/* Canonical objective: fp32 sequential sums over chunks of 64 elements, fp64 pairwise above. */
+static double can_dual_sse_work(const float *x, int64_t n, float a1, float a2, int qmin, int qmax, double *work)
+{
+    const float inv2 = 1.0f / a2, lo = (float)qmin, hi = (float)qmax;
+    const int64_t m = (n + ORACLE_CHUNK - 1) / ORACLE_CHUNK;
+    for (int64_t c = 0; c < m; ++c) {
+        int64_t s0 = c * ORACLE_CHUNK;
+        int64_t len = n - s0 < ORACLE_CHUNK ? n - s0 : ORACLE_CHUNK;
+        float s = 0.0f;
+        for (int64_t i = 0; i < len; ++i)
+            s = s + can_dual_element(x[s0 + i], a1, a2, inv2, lo, hi, qmin, qmax, NULL, NULL);
+        work[c] = (double)s;
+    }
+    return can_pairwise(work, m);
+}
+
+double can_dual_sse(const float *x, int64_t n, float a1, float a2, int qmin, int qmax)
+{
+    int64_t m = (n + ORACLE_CHUNK - 1) / ORACLE_CHUNK;
+    double *work = (double *)malloc(sizeof(double) * (size_t)(m > 0 ? m : 1));
+    double e = can_dual_sse_work(x, n, a1, a2, qmin, qmax, work);
+    free(work);
+    return e;
+}
+
+/* Second-tensor scale number b for a first-tensor scale a1: the paper gives no grid for a2;
+ * the reading here is a linear grid over (0, a1] (the two tensors play symmetric roles, so
+ * a2 <= a1 loses nothing): a2 = a1 * (b+1)/G2. */
+float can_dual_alpha2(float a1, int G2, int b)
+{
+    float frac = (float)(b + 1) / (float)G2;
+    return a1 * frac;
+}
+
+void can_dual_codes(const float *x, int64_t n, float a1, float a2, int qmin, int qmax, int32_t *q1, int32_t *q2)
+{
+    const float inv2 = 1.0f / a2, lo = (float)qmin, hi = (float)qmax;
+    for (int64_t i = 0; i < n; ++i) {
+        int t, q;
+        can_dual_element(x[i], a1, a2, inv2, lo, hi, qmin, qmax, &t, &q);
+        q1[i] = t; q2[i] = q;
+    }
+}
+
+/* Exhaustive search of the G1 x G2 grid for one kernel; the lowest (a, b) in row-major order wins
+ * among equal minima.  grid (optional): G1*G2 errors.  Degenerate inputs as in can_search:
+ * all-zero/tiny -> scales 1, indices 0, codes 0; non-finite -> NaN, indices -1, codes 0. */
+int can_dual_linesearch(const float *x, int64_t n, int qmin, int qmax, int G1, int G2,
+                        float *a1_out, float *a2_out, int32_t *ia, int32_t *ib, double *sse,
+                        int32_t *q1, int32_t *q2, double *grid)
+{
+    int64_t m = (n + ORACLE_CHUNK - 1) / ORACLE_CHUNK;
+    double *work = (double *)malloc(sizeof(double) * (size_t)(m > 0 ? m : 1));
+    float a = can_absmax(x, n);
+    int rc = 0;
+    for (int64_t i = 0; i < n; ++i) { q1[i] = 0; q2[i] = 0; }
+    if (!(a <= ORACLE_HUGE)) {
+        *a1_out = NAN; *a2_out = NAN; *ia = -1; *ib = -1; *sse = NAN; rc = -1;
+        if (grid) for (int i = 0; i < G1 * G2; ++i) grid[i] = NAN;
+    } else if (a < ORACLE_TINY) {
+        *a1_out = 1.0f; *a2_out = 1.0f; *ia = 0; *ib = 0;
+        *sse = can_sse_work(x, n, 1.0f, qmin, qmax, work);
+        if (grid) for (int i = 0; i < G1 * G2; ++i) grid[i] = *sse;
+    } else {
+        double best = INFINITY;
+        int ba = 0, bb = 0;
+        for (int ja = 0; ja < G1; ++ja) {
+            float a1 = can_grid_alpha(a, qmax, G1, ja);
+            for (int jb = 0; jb < G2; ++jb) {
+                float a2 = can_dual_alpha2(a1, G2, jb);
+                double e = can_dual_sse_work(x, n, a1, a2, qmin, qmax, work);
+                if (grid) grid[ja * G2 + jb] = e;
+                if (e < best) { best = e; ba = ja; bb = jb; }
+            }
+        }
+        *ia = ba; *ib = bb; *sse = best;
+        *a1_out = can_grid_alpha(a, qmax, G1, ba);
+        *a2_out = can_dual_alpha2(*a1_out, G2, bb);
+        can_dual_codes(x, n, *a1_out, *a2_out, qmin, qmax, q1, q2);
+    }
+    free(work);
+    return rc;
+}
+
+void can_dual_linesearch_kernelwise(const float *w, int64_t K, int64_t n, int qmin, int qmax, int G1, int G2,
+                                    float *scale1, float *scale2, int32_t *idx1, int32_t *idx2, double *sse,
+                                    uint8_t *packed1, uint8_t *packed2)
+{
+    size_t tot = (size_t)(K * n > 0 ? K * n : 1);
+    int32_t *q1 = (int32_t *)malloc(sizeof(int32_t) * tot);
+    int32_t *q2 = (int32_t *)malloc(sizeof(int32_t) * tot);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t k = 0; k < K; ++k)
+        can_dual_linesearch(w + k * n, n, qmin, qmax, G1, G2, scale1 + k, scale2 + k, idx1 + k, idx2 + k, sse + k,
+                            q1 + k * n, q2 + k * n, NULL);
+    can_pack_int4(q1, K * n, packed1);
+    can_pack_int4(q2, K * n, packed2);
+    free(q1); free(q2);
+}
+
 int oracle_num_threads(void)
 {
     int nthreads = 1;

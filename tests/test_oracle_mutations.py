@@ -43,6 +43,13 @@ MUTATIONS = [
      "out[i] = fmaf(-alpha, (float)q[i], t[i]);", "out[i] = fmaf(alpha, (float)q[i], t[i]);"),
     ("alternating: worse sweeps are kept", "if (!(te < e)) break;", ";"),
     ("alternating: stopping rule ignored", "if (conv) break;", ";"),
+    ("dual search: only the rounded first code is tried", "    for (int t = qmin; t <= qmax; ++t) {\n        float r = fmaf(-a1, (float)t, x);",
+     "    for (int t = (int)can_clamp(rintf(x / a1), lo, hi); t <= (int)can_clamp(rintf(x / a1), lo, hi); ++t) {\n        float r = fmaf(-a1, (float)t, x);"),
+    ("dual search: second code not saturated in the definition", "double d = r - a2 * def_round_sat(r / a2, qmin, qmax);", "double d = r - a2 * nearbyint(r / a2);"),
+    ("dual search: second scale grid is absolute, not relative", "return a1 * frac;", "return frac;"),
+    ("dual search: last of equal minima", "if (e < best) { best = e; ba = ja; bb = jb; }", "if (e <= best) { best = e; ba = ja; bb = jb; }"),
+    ("dual search: codes of the wrong scale pair", "can_dual_codes(x, n, *a1_out, *a2_out, qmin, qmax, q1, q2);", "can_dual_codes(x, n, *a1_out, *a1_out, qmin, qmax, q1, q2);"),
+    ("dual search: highest code wins ties", "if (e < best) { best = e; bt = t; bq = (int)q; }", "if (e <= best) { best = e; bt = t; bq = (int)q; }"),
     ("tiny tensors not special-cased", "} else if (a < ORACLE_TINY) {", "} else if (a < 0.0f) {"),
     ("non-finite input accepted", "return bad ? NAN : a;", "return a;"),
 ]

@@ -511,6 +511,105 @@ def test_alternating_rejects_non_finite_kernels():
     assert np.all(o["sse"] == 0) and np.all(o["sweeps"] == 1) and np.all(o["packed1"] == 0)
 
 
+# ------------------------------------------------------------------ dual line search (Eq. 12)
+def test_dual_objective_is_the_best_of_all_code_pairs():
+    """Eq. 12: for fixed scales the per-element optimum over all 16 x 16 code pairs equals the
+    enumeration over the first code with the second one rounded (brute force, fp64)."""
+    rng = np.random.default_rng(0)
+    x = rng.normal(0, 0.3, 40).astype(np.float32)
+    codes = np.arange(-8, 8, dtype=np.float64)
+    for a1, a2 in ((0.11, 0.013), (0.05, 0.05), (0.3, 0.002), (0.02, 0.015)):
+        rec = a1 * codes[:, None] + a2 * codes[None, :]
+        best = ((x.astype(np.float64)[:, None, None] - rec[None]) ** 2).reshape(x.size, -1).min(axis=1)
+        assert oracle.def_dual_sse(x, a1, a2, *SIGNED) == pytest.approx(best.sum(), rel=1e-12)
+        assert oracle.can_dual_sse(x, a1, a2, *SIGNED) == pytest.approx(best.sum(), rel=2e-5)
+
+
+def test_dual_objective_never_worse_than_quantizing_the_residual():
+    """The enumeration includes t = [T/a1], so with the same scales it cannot lose to the residual fit."""
+    w = synth.small_weights(6, 200, 17, "student")
+    s1, _, _ = oracle.can_search_kernelwise(w, *SIGNED, 64, 20)
+    s2, _, e2, _ = oracle.can_residual_quantize(w, s1, *SIGNED, 64, 20)
+    for k in range(6):
+        assert oracle.can_dual_sse(w[k], s1[k], s2[k], *SIGNED) <= e2[k] * (1 + 1e-6)
+
+
+def test_dual_linesearch_grid_argmin_codes_and_error():
+    K, n, G1, G2 = 4, 150, 12, 10
+    w = synth.small_weights(K, n, 23, "laplace")
+    kw = oracle.can_dual_linesearch_kernelwise(w, *SIGNED, G1, G2)
+    for k in range(K):
+        r = oracle.can_dual_linesearch(w[k], *SIGNED, G1, G2, want_grid=True)
+        g = r["grid"]
+        flat = int(np.argmin(g))                                   # first minimum in row-major order
+        assert (r["idx1"], r["idx2"]) == (flat // G2, flat % G2) and r["sse"] == g.min()
+        a1 = oracle.can_grid(np.abs(w[k]).max(), 7, G1)[r["idx1"]]
+        assert r["scale1"] == a1 and r["scale2"] == oracle.can_dual_alpha2(a1, G2, r["idx2"])
+        assert r["scale2"] == np.float32(a1) * (np.float32(r["idx2"] + 1) / np.float32(G2))
+        for (ja, jb) in ((0, 0), (3, 7), (G1 - 1, G2 - 1)):
+            aa = oracle.can_grid(np.abs(w[k]).max(), 7, G1)[ja]
+            assert g[ja, jb] == oracle.can_dual_sse(w[k], aa, oracle.can_dual_alpha2(aa, G2, jb), *SIGNED)
+        d = oracle.def_sse_dual(w[k], r["q1"], r["q2"], float(r["scale1"]), float(r["scale2"]))
+        assert d == pytest.approx(r["sse"], rel=3e-5)
+        assert r["q1"].min() >= -8 and r["q1"].max() <= 7 and r["q2"].min() >= -8 and r["q2"].max() <= 7
+        assert (kw["scale1"][k], kw["scale2"][k], kw["idx1"][k], kw["idx2"][k], kw["sse"][k]) == \
+               (r["scale1"], r["scale2"], r["idx1"], r["idx2"], r["sse"])
+    q1 = oracle.can_unpack_int4(kw["packed1"], K * n, True).reshape(K, n)
+    np.testing.assert_array_equal(q1[2], oracle.can_dual_linesearch(w[2], *SIGNED, G1, G2)["q1"])
+
+
+def test_dual_linesearch_finds_an_exact_two_grid_tensor():
+    """T = a1*Q1 + a2*Q2 with a1 the max-abs scale and a2 = a1/4 on the grid: error 0 is reachable."""
+    rng = np.random.default_rng(3)
+    n, G1, G2 = 64, 8, 8
+    a1, a2 = 2.0 ** -3, 2.0 ** -5
+    q1 = rng.integers(-6, 7, n)
+    q2 = rng.integers(-1, 2, n)
+    q1[0], q2[0] = 7, 0
+    x = (q1 * a1 + q2 * a2).astype(np.float32)
+    x[0] = 7 * a1
+    r = oracle.can_dual_linesearch(x, *SIGNED, G1, G2, want_grid=True)
+    assert r["sse"] == 0.0 and r["grid"][G1 - 1, G2 // 4 - 1] == 0.0
+    zeros = np.argwhere(r["grid"] == 0.0)
+    assert len(zeros) >= 2                                   # a2 = a1/8 reproduces T as well (codes 2*Q2)
+    assert (r["idx1"], r["idx2"]) == tuple(zeros[0])         # first of the equal minima in row-major order
+    rec = float(r["scale1"]) * r["q1"] + float(r["scale2"]) * r["q2"]
+    np.testing.assert_array_equal(rec.astype(np.float32), x)
+
+
+def test_dual_codes_tie_rule():
+    """2.25*a1 = 2*a1 + 2*a2 = 3*a1 - 6*a2 for a2 = a1/8: both code pairs are exact; the first code tried
+    (the lowest) is kept.  Either pair is a correct answer; the rule only makes the output unique."""
+    a1, a2 = 2.0 ** -3, 2.0 ** -6
+    q1, q2 = oracle.can_dual_codes(np.array([2.25 * a1, 0.0, -2.25 * a1], np.float32), a1, a2, *SIGNED)
+    np.testing.assert_array_equal(q1, [2, 0, -3])
+    np.testing.assert_array_equal(q2, [2, 0, 6])
+
+
+def test_dual_linesearch_beats_the_residual_fit_and_scales_exactly():
+    w = synth.small_weights(5, 576, 3, "laplace")
+    one = oracle.can_dual_alternating(w, *SIGNED, 256, 20, 0.0, 1)["sse"]
+    o = oracle.can_dual_linesearch_kernelwise(w, *SIGNED, 24, 24)
+    assert np.all(o["sse"] < 0.5 * one)            # the paper reports a 5x lower error on average
+    o2 = oracle.can_dual_linesearch_kernelwise((w * np.float32(8)).astype(np.float32), *SIGNED, 24, 24)
+    np.testing.assert_array_equal(o["idx1"], o2["idx1"])
+    np.testing.assert_array_equal(o["idx2"], o2["idx2"])
+    np.testing.assert_array_equal(o["packed1"], o2["packed1"])
+    np.testing.assert_array_equal(o["packed2"], o2["packed2"])
+    np.testing.assert_array_equal(o["sse"] * 64.0, o2["sse"])
+    np.testing.assert_array_equal(o["scale2"] * np.float32(8), o2["scale2"])
+
+
+def test_dual_linesearch_degenerate_inputs():
+    z = np.zeros(30, np.float32)
+    r = oracle.can_dual_linesearch(z, *SIGNED, 4, 4)
+    assert (r["scale1"], r["scale2"], r["idx1"], r["idx2"], r["sse"], r["rc"]) == (1.0, 1.0, 0, 0, 0.0, 0)
+    assert not r["q1"].any() and not r["q2"].any()
+    z[3] = np.nan
+    r = oracle.can_dual_linesearch(z, *SIGNED, 4, 4)
+    assert r["rc"] == -1 and np.isnan(r["scale1"]) and r["idx1"] == -1 and np.isnan(r["sse"])
+
+
 # ------------------------------------------------------------------ workloads
 def test_workload_shapes_match_architectures():
     c = [synth.config(i) for i in range(1, 6)]
