@@ -153,6 +153,21 @@ int mmse_workspace_bytes_dual_batched(const mmse_dual_desc_t *descs_host, int32_
 int dual_quantize_alternating_batched(const mmse_dual_desc_t *descs_host, int32_t count, const mmse_params_t *p,
                                       double eps, int32_t max_sweeps, void *ws_dev, size_t ws_bytes, void *stream);
 
+/* Dual line search (Section 3.5, Eq. 12) for every kernel of a [K][n] layer, n <= 8192 ("reserved to small
+ * tensors (convolutional kernels)"): exhaustive search of a G1 x G2 grid of scale pairs,
+ *   a1_a = (max|w_k|/qmax)*(a+1)/G1,   a2_b = a1_a*(b+1)/G2        (the paper gives no grid for a2; this
+ *   one covers (0, a1]: the two tensors play symmetric roles),
+ * where the error of a pair is sum_i min_t (w_i - a1*t - a2*[(w_i - a1*t)/a2])^2 over all first codes t in
+ * [qmin, qmax].  The first of equal minima in row-major (a, b) order is returned:
+ *   scale1_dev[k], scale2_dev[k], idx1_dev[k] = a, idx2_dev[k] = b, sse_dev[k], and the two code tensors
+ *   (layout of quantize_pack_int4; among equally good first codes the lowest is kept).
+ * grid_dev is optional: [K][G1*G2] errors of every pair.  G1, G2 in 1..1024. */
+int mmse_workspace_bytes_dual_linesearch(int64_t K, int64_t n, int32_t G1, int32_t G2, size_t *bytes_out);
+int dual_line_search(const float *w_dev, int64_t K, int64_t n, int32_t qmin, int32_t qmax, int32_t G1, int32_t G2,
+                     float *scale1_dev, float *scale2_dev, int32_t *idx1_dev, int32_t *idx2_dev, double *sse_dev,
+                     uint8_t *packed1_dev, uint8_t *packed2_dev, double *grid_dev,
+                     void *ws_dev, size_t ws_bytes, void *stream);
+
 /* Whole network in a handful of launches: `count` weight tensors described in HOST
  * memory (the descriptors are consumed before the call returns).  Semantics per
  * tensor are those of mmse_scale_search_kernelwise / residual_quantize /

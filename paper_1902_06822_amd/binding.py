@@ -22,6 +22,7 @@ EXPORTS = (
     "quantize_pack_int4", "residual_quantize", "mmse_scale_search_batched",
     "mmse_grid_sse_kernelwise", "mmse_workspace_bytes_dual", "dual_quantize_alternating",
     "mmse_workspace_bytes_dual_batched", "dual_quantize_alternating_batched",
+    "mmse_workspace_bytes_dual_linesearch", "dual_line_search",
     "mmse_status_string",
 )
 
@@ -72,6 +73,9 @@ def load_library() -> C.CDLL:
     lib.mmse_workspace_bytes_dual_batched.argtypes = [C.POINTER(MmseDualDesc), i32, pp, szp]
     lib.dual_quantize_alternating_batched.argtypes = [C.POINTER(MmseDualDesc), i32, pp, C.c_double, i32, vp,
                                                       C.c_size_t, vp]
+    lib.mmse_workspace_bytes_dual_linesearch.argtypes = [i64, i64, i32, i32, szp]
+    lib.dual_line_search.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                     C.c_size_t, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -325,3 +329,40 @@ class DualBatchedPlan:
 def dual_quantize_alternating_batched(weights: Sequence[torch.Tensor], p: MmseParams, eps: float,
                                       max_sweeps: int) -> List[DualResult]:
     return DualBatchedPlan(weights, p, eps, max_sweeps).run()
+
+
+@dataclass
+class DualLineSearchResult:
+    scale1: torch.Tensor
+    scale2: torch.Tensor
+    idx1: torch.Tensor
+    idx2: torch.Tensor
+    sse: torch.Tensor
+    packed1: torch.Tensor
+    packed2: torch.Tensor
+    grid: Optional[torch.Tensor] = None
+
+
+def dual_line_search(w: torch.Tensor, qmin: int, qmax: int, G1: int, G2: int, want_grid: bool = False,
+                     ws: Optional[torch.Tensor] = None, out: Optional[DualLineSearchResult] = None
+                     ) -> DualLineSearchResult:
+    _dev(w, torch.float32)
+    K, n = w.shape
+    if ws is None:
+        need = C.c_size_t(0)
+        _check(load_library().mmse_workspace_bytes_dual_linesearch(K, n, G1, G2, C.byref(need)),
+               "mmse_workspace_bytes_dual_linesearch")
+        ws = alloc_workspace(need.value, w.device)
+    if out is None:
+        nb = (K * n + 1) // 2
+        f32 = lambda: torch.empty(K, dtype=torch.float32, device=w.device)
+        i32t = lambda: torch.empty(K, dtype=torch.int32, device=w.device)
+        out = DualLineSearchResult(f32(), f32(), i32t(), i32t(), torch.empty(K, dtype=torch.float64, device=w.device),
+                                   torch.empty(nb, dtype=torch.uint8, device=w.device),
+                                   torch.empty(nb, dtype=torch.uint8, device=w.device),
+                                   torch.empty((K, G1 * G2), dtype=torch.float64, device=w.device) if want_grid else None)
+    _check(load_library().dual_line_search(
+        w.data_ptr(), K, n, qmin, qmax, G1, G2, out.scale1.data_ptr(), out.scale2.data_ptr(), out.idx1.data_ptr(),
+        out.idx2.data_ptr(), out.sse.data_ptr(), out.packed1.data_ptr(), out.packed2.data_ptr(), _ptr(out.grid),
+        ws.data_ptr(), ws.numel(), _stream()), "dual_line_search")
+    return out

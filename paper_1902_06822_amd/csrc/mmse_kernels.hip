@@ -872,6 +872,233 @@ __global__ void __launch_bounds__(256) k_dual_copy_codes(const DualBatch D)
 }
 
 // ---------------------------------------------------------------------------------
+// Dual line search (Section 3.5, Eq. 12): exhaustive G1 x G2 grid over (a1, a2), per element the
+// best of the 2^p first codes with the second code rounded
+// ---------------------------------------------------------------------------------
+struct DualLsArgs {
+    const float* w;
+    int K, n, G1, G2, splits;
+    int qmin, qmax;
+    float lo, hi;
+    float* absmax;           // workspace [K]
+    double* part_e;          // workspace [K][splits]: best error found by one workgroup
+    int* part_idx;           // workspace [K][splits]: its flat grid index a*G2 + b
+    double* grid;            // optional [K][G1*G2]
+    float* scale1; float* scale2; int32_t* idx1; int32_t* idx2; double* sse;
+    uint8_t* packed1; uint8_t* packed2;
+};
+
+// Error of one element for the pair (a1, a2): min over the first code t of
+// (x - a1*t - a2*[(x - a1*t)/a2])^2; 7 VALU instructions per code.
+template <bool FULL16>
+__device__ __forceinline__ float dual_elem_err(float x, float a1, float a2, float inv2, float lo, float hi,
+                                               int qmin, int qmax)
+{
+    float best = __uint_as_float(0x7f800000u);
+    if constexpr (FULL16) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float r = __builtin_fmaf(-a1, (float)(qmin + i), x);
+            const float d = __builtin_fmaf(-a2, code_of(r, inv2, lo, hi), r);
+            best = __builtin_fminf(best, d * d);
+        }
+    } else {
+        for (int t = qmin; t <= qmax; ++t) {
+            const float r = __builtin_fmaf(-a1, (float)t, x);
+            const float d = __builtin_fmaf(-a2, code_of(r, inv2, lo, hi), r);
+            best = __builtin_fminf(best, d * d);
+        }
+    }
+    return best;
+}
+
+// One workgroup per (kernel, split): the kernel's slice sits in LDS; a wave takes units
+// (first scale a, group of 64 second scales), lane = second scale; every unit is a full sweep of the
+// slice.  The best (error, flat index) of the workgroup goes to the workspace; k_dual_ls_pick
+// takes the minimum over the splits.  The splits exist so that a layer with few kernels still
+// fills the GPU.
+template <bool FULL16>
+__global__ void __launch_bounds__(512) k_dual_ls(const DualLsArgs A)
+{
+    extern __shared__ float4 smem4[];
+    float* slice = reinterpret_cast<float*>(smem4);
+    __shared__ unsigned s_amax[8];
+    __shared__ double s_bestE[8];
+    __shared__ int s_bestI[8];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+    const int k = blockIdx.x / A.splits, sp = blockIdx.x - k * A.splits;
+    const int n = A.n;
+    const float* __restrict__ src = A.w + (size_t)k * n;
+    const float lo = A.lo, hi = A.hi;
+    const int npad = (n + kChunk - 1) & ~(kChunk - 1);
+    unsigned amax = 0;
+    for (int i = tid; i < npad; i += nthreads) {
+        const float v = i < n ? src[i] : 0.0f;
+        slice[i] = v;
+        const unsigned b = abs_bits(v);
+        amax = b > amax ? b : amax;
+    }
+    amax = wave_max_u32(amax);
+    if (lane == 0) s_amax[wave] = amax;
+    __syncthreads();
+    unsigned am = 0;
+    for (int w = 0; w < nwaves; ++w) am = s_amax[w] > am ? s_amax[w] : am;
+    const float a = __uint_as_float(am);
+    const size_t pslot = (size_t)k * A.splits + sp;
+    const double inf = __longlong_as_double(0x7ff0000000000000LL);
+    if (sp == 0 && tid == 0) A.absmax[k] = a;
+    if (!(a <= kHuge)) {                                      // rejected: k_dual_ls_pick writes the NaNs
+        if (tid == 0) { A.part_e[pslot] = inf; A.part_idx[pslot] = INT_MAX; }
+        if (A.grid && sp == 0)
+            for (int j = tid; j < A.G1 * A.G2; j += nthreads)
+                A.grid[(size_t)k * A.G1 * A.G2 + j] = (double)__uint_as_float(0x7fc00000u);
+        return;
+    }
+    const int n8 = (n + 7) & ~7;
+    if (a < kTiny) {                                          // all-zero kernel: scales 1, codes 0, error = sum x^2
+        double E = inf;
+        if (sp == 0 && wave == 0) {
+            const float one[1] = {1.0f};
+            double st[1][kLevelsKWSmall];
+#pragma unroll
+            for (int l = 0; l < kLevelsKWSmall; ++l) st[0][l] = 0.0;
+            unsigned ci = 0;
+            sweep_slice<1, kLevelsKWSmall>(slice, n8, ci, one, one, lo, hi, st);
+            double e1[1];
+            tree_fold<1, kLevelsKWSmall>(st, ci, e1);
+            E = e1[0];
+        }
+        if (tid == 0) { A.part_e[pslot] = E; A.part_idx[pslot] = sp == 0 ? 0 : INT_MAX; }
+        if (A.grid && sp == 0 && wave == 0)
+            for (int j = lane; j < A.G1 * A.G2; j += 64) A.grid[(size_t)k * A.G1 * A.G2 + j] = E;
+        return;
+    }
+
+    const float qmaxf = (float)A.qmax, G1f = (float)A.G1, G2f = (float)A.G2;
+    const int nbg = (A.G2 + 63) >> 6;
+    const int units = A.G1 * nbg;
+    const float4* s4 = reinterpret_cast<const float4*>(slice);
+    double bE = inf;
+    int bI = INT_MAX;
+    for (int u = sp * nwaves + wave; u < units; u += A.splits * nwaves) {
+        const int ja = u / nbg, bg = u - ja * nbg;
+        const int jb = bg * 64 + lane;
+        const bool valid = jb < A.G2;
+        const float a1 = grid_alpha(a, qmaxf, G1f, ja);
+        const float a2 = a1 * ((float)((valid ? jb : A.G2 - 1) + 1) / G2f);
+        const float inv2 = 1.0f / a2;
+        double st[1][kLevelsKWSmall];
+#pragma unroll
+        for (int l = 0; l < kLevelsKWSmall; ++l) st[0][l] = 0.0;
+        unsigned ci = 0;
+        for (int c0 = 0; c0 < n8; c0 += kChunk, ++ci) {
+            const int len = (n8 - c0) < kChunk ? (n8 - c0) : kChunk;   // multiple of 8; zeros pad to 8: exact no-ops
+            float sum = 0.0f;
+            for (int e = 0; e < len; e += 4) {
+                const float4 v = s4[(c0 + e) >> 2];
+                sum = sum + dual_elem_err<FULL16>(v.x, a1, a2, inv2, lo, hi, A.qmin, A.qmax);
+                sum = sum + dual_elem_err<FULL16>(v.y, a1, a2, inv2, lo, hi, A.qmin, A.qmax);
+                sum = sum + dual_elem_err<FULL16>(v.z, a1, a2, inv2, lo, hi, A.qmin, A.qmax);
+                sum = sum + dual_elem_err<FULL16>(v.w, a1, a2, inv2, lo, hi, A.qmin, A.qmax);
+            }
+            double t[1] = {(double)sum};
+            tree_push<1, kLevelsKWSmall>(st, t, ci);
+        }
+        double E1[1];
+        tree_fold<1, kLevelsKWSmall>(st, ci, E1);
+        const double E = E1[0];
+        const int flat = ja * A.G2 + jb;
+        if (valid) {
+            if (A.grid) A.grid[(size_t)k * A.G1 * A.G2 + flat] = E;
+            if (E < bE || (E == bE && flat < bI)) { bE = E; bI = flat; }
+        }
+    }
+    wave_argmin(bE, bI);
+    if (lane == 0) { s_bestE[wave] = bE; s_bestI[wave] = bI; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < nwaves; ++w) {
+            const double oe = s_bestE[w];
+            const int oi = s_bestI[w];
+            if (oe < bE || (oe == bE && oi < bI)) { bE = oe; bI = oi; }
+        }
+        A.part_e[pslot] = bE;
+        A.part_idx[pslot] = bI;
+    }
+}
+
+// Minimum over the splits of every kernel (first flat index among equal errors) and the outputs.
+__global__ void __launch_bounds__(256) k_dual_ls_pick(const DualLsArgs A)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= A.K) return;
+    const float a = A.absmax[k];
+    if (!(a <= kHuge)) {
+        const float nanf_ = __uint_as_float(0x7fc00000u);
+        A.scale1[k] = nanf_; A.scale2[k] = nanf_; A.idx1[k] = -1; A.idx2[k] = -1; A.sse[k] = (double)nanf_;
+        return;
+    }
+    double bE = A.part_e[(size_t)k * A.splits];
+    int bI = A.part_idx[(size_t)k * A.splits];
+    for (int sp = 1; sp < A.splits; ++sp) {
+        const double oe = A.part_e[(size_t)k * A.splits + sp];
+        const int oi = A.part_idx[(size_t)k * A.splits + sp];
+        if (oe < bE || (oe == bE && oi < bI)) { bE = oe; bI = oi; }
+    }
+    if (bI == INT_MAX) bI = 0;
+    A.sse[k] = bE;
+    if (a < kTiny) {
+        A.scale1[k] = 1.0f; A.scale2[k] = 1.0f; A.idx1[k] = 0; A.idx2[k] = 0;
+        return;
+    }
+    const int ja = bI / A.G2, jb = bI - ja * A.G2;
+    const float a1 = grid_alpha(a, (float)A.qmax, (float)A.G1, ja);
+    A.scale1[k] = a1;
+    A.scale2[k] = a1 * ((float)(jb + 1) / (float)A.G2);
+    A.idx1[k] = ja;
+    A.idx2[k] = jb;
+}
+
+// Both code tensors for the chosen scales, 8 elements per thread; the first of equally good first
+// codes is kept.  All-zero and rejected kernels are coded as zeros.
+__global__ void __launch_bounds__(kPackThreads) k_dual_ls_codes(const DualLsArgs A)
+{
+    const int n = A.n;
+    const long long total = (long long)A.K * n;
+    const long long e0 = ((long long)blockIdx.x * kPackThreads + threadIdx.x) * kPackPerThread;
+    if (e0 >= total) return;
+    const float lo = A.lo, hi = A.hi;
+    const int cnt = (total - e0) < kPackPerThread ? (int)(total - e0) : kPackPerThread;
+    int k = (int)((unsigned)e0 / (unsigned)n);
+    int r = (int)((unsigned)e0 - (unsigned)k * (unsigned)n);
+    unsigned w1 = 0, w2 = 0;
+    for (int i = 0; i < cnt; ++i) {
+        if (r == n) { r = 0; ++k; }
+        const float am = A.absmax[k];
+        int t1 = 0, t2 = 0;
+        if (am <= kHuge && !(am < kTiny)) {
+            const float x = A.w[e0 + i], a1 = A.scale1[k], a2 = A.scale2[k], inv2 = 1.0f / a2;
+            float best = __uint_as_float(0x7f800000u);
+            for (int t = A.qmin; t <= A.qmax; ++t) {
+                const float rr = __builtin_fmaf(-a1, (float)t, x);
+                const float q = code_of(rr, inv2, lo, hi);
+                const float d = __builtin_fmaf(-a2, q, rr);
+                const float e = d * d;
+                if (e < best) { best = e; t1 = t; t2 = (int)q; }
+            }
+        }
+        w1 |= ((unsigned)t1 & 0xFu) << (4 * i);
+        w2 |= ((unsigned)t2 & 0xFu) << (4 * i);
+        ++r;
+    }
+    const int nbytes = (cnt + 1) >> 1;
+    uint8_t* d1 = A.packed1 + (e0 >> 1);
+    uint8_t* d2 = A.packed2 + (e0 >> 1);
+    for (int b = 0; b < nbytes; ++b) { d1[b] = (uint8_t)(w1 >> (8 * b)); d2[b] = (uint8_t)(w2 >> (8 * b)); }
+}
+
+// ---------------------------------------------------------------------------------
 // activation tensor: one problem of N elements over the whole GPU
 // ---------------------------------------------------------------------------------
 // Workspace layout (all offsets multiples of 256 bytes):
@@ -1756,6 +1983,71 @@ int dual_quantize_alternating(const float* w_dev, int64_t K, int64_t n, const mm
     d.w_dev = w_dev; d.K = K; d.n = n; d.scale1_dev = scale1_dev; d.scale2_dev = scale2_dev;
     d.packed1_dev = packed1_dev; d.packed2_dev = packed2_dev; d.sse_dev = sse_dev; d.sweeps_dev = sweeps_dev;
     return dual_quantize_alternating_batched(&d, 1, p, eps, max_sweeps, ws_dev, ws_bytes, stream);
+}
+
+static int dual_ls_splits(int64_t K, int G1, int G2)
+{
+    // enough workgroups of 8 waves to give every SIMD about four waves, but never more splits than units per wave
+    const int units = G1 * ((G2 + 63) / 64);
+    long long want = (4096 + K * 8 - 1) / (K * 8);
+    const int cap = (units + 7) / 8;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+int mmse_workspace_bytes_dual_linesearch(int64_t K, int64_t n, int32_t G1, int32_t G2, size_t* bytes_out)
+{
+    if (!bytes_out) return MMSE_ERR_NULL;
+    if (K <= 0 || n <= 0 || n > kTile || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (G1 < 1 || G2 < 1 || G1 > 1024 || G2 > 1024) return MMSE_ERR_PARAMS;
+    const int sp = dual_ls_splits(K, G1, G2);
+    *bytes_out = round256((size_t)K * sizeof(float)) + round256((size_t)K * sp * sizeof(double)) +
+                 round256((size_t)K * sp * sizeof(int));
+    return MMSE_OK;
+}
+
+int dual_line_search(const float* w_dev, int64_t K, int64_t n, int32_t qmin, int32_t qmax, int32_t G1, int32_t G2,
+                     float* scale1_dev, float* scale2_dev, int32_t* idx1_dev, int32_t* idx2_dev, double* sse_dev,
+                     uint8_t* packed1_dev, uint8_t* packed2_dev, double* grid_dev,
+                     void* ws_dev, size_t ws_bytes, void* stream)
+{
+    if (!w_dev || !scale1_dev || !scale2_dev || !idx1_dev || !idx2_dev || !sse_dev || !packed1_dev || !packed2_dev)
+        return MMSE_ERR_NULL;
+    if (K <= 0 || n <= 0 || n > kTile || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (!(qmin <= 0 && qmax > 0 && qmax - qmin <= 15)) return MMSE_ERR_PARAMS;
+    if (G1 < 1 || G2 < 1 || G1 > 1024 || G2 > 1024) return MMSE_ERR_PARAMS;
+    if (!aligned_to(w_dev, 4) || !aligned_to(scale1_dev, 4) || !aligned_to(scale2_dev, 4) || !aligned_to(idx1_dev, 4) ||
+        !aligned_to(idx2_dev, 4) || !aligned_to(sse_dev, 8) || !aligned_to(grid_dev, 8))
+        return MMSE_ERR_ALIGN;
+    size_t need = 0;
+    mmse_workspace_bytes_dual_linesearch(K, n, G1, G2, &need);
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < need) return MMSE_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    DualLsArgs A{};
+    A.w = w_dev; A.K = (int)K; A.n = (int)n; A.G1 = G1; A.G2 = G2; A.splits = dual_ls_splits(K, G1, G2);
+    A.qmin = qmin; A.qmax = qmax; A.lo = (float)qmin; A.hi = (float)qmax;
+    char* ws = static_cast<char*>(ws_dev);
+    A.absmax = reinterpret_cast<float*>(ws);
+    ws += round256((size_t)K * sizeof(float));
+    A.part_e = reinterpret_cast<double*>(ws);
+    ws += round256((size_t)K * A.splits * sizeof(double));
+    A.part_idx = reinterpret_cast<int*>(ws);
+    A.grid = grid_dev;
+    A.scale1 = scale1_dev; A.scale2 = scale2_dev; A.idx1 = idx1_dev; A.idx2 = idx2_dev; A.sse = sse_dev;
+    A.packed1 = packed1_dev; A.packed2 = packed2_dev;
+    const int npad = (int)((n + kChunk - 1) & ~(int64_t)(kChunk - 1));
+    const size_t lds = (size_t)npad * sizeof(float);
+    const unsigned nwg = (unsigned)(K * A.splits);
+    if (qmax - qmin == 15) hipLaunchKernelGGL(k_dual_ls<true>, dim3(nwg), dim3(512), lds, s, A);
+    else hipLaunchKernelGGL(k_dual_ls<false>, dim3(nwg), dim3(512), lds, s, A);
+    if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+    hipLaunchKernelGGL(k_dual_ls_pick, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s, A);
+    if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+    const long long total = (long long)K * n, per_wg = (long long)kPackThreads * kPackPerThread;
+    hipLaunchKernelGGL(k_dual_ls_codes, dim3((unsigned)((total + per_wg - 1) / per_wg)), dim3(kPackThreads), 0, s, A);
+    if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+    return MMSE_OK;
 }
 
 int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_params_t* p,

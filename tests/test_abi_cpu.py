@@ -90,6 +90,14 @@ def test_entry_points_validate_before_enqueue(B):
     assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), 1e-3, 0, a, a, a, a, a, a, a, 1 << 20, None) == -3
     assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), 1e-3, 4, a, a, a, a, a, a, a, 256, None) == -4
     assert lib.dual_quantize_alternating_batched(None, 1, C.byref(p), 1e-3, 4, a, 1 << 20, None) == -1
+    dls = lambda **kw: lib.dual_line_search(*[kw.get(k, d) for k, d in (
+        ("w", a), ("K", 4), ("n", 4), ("qmin", -8), ("qmax", 7), ("G1", 8), ("G2", 8), ("s1", a), ("s2", a), ("i1", a),
+        ("i2", a), ("sse", a), ("p1", a), ("p2", a), ("grid", None), ("ws", a), ("ws_bytes", 1 << 20), ("stream", None))])
+    assert dls(w=None) == -1 and dls(p2=None) == -1 and dls(sse=None) == -1
+    assert dls(n=8193) == -2 and dls(K=0) == -2
+    assert dls(G1=0) == -3 and dls(G2=1025) == -3 and dls(qmin=1) == -3 and dls(qmin=-9) == -3
+    assert dls(ws=None) == -4 and dls(ws_bytes=16) == -4 and dls(ws=a + 8) == -4
+    assert dls(sse=a + 4) == -6 and dls(grid=a + 4) == -6
     # sizes
     assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
     assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2
