@@ -164,6 +164,68 @@ def bench_dual(args, cfg, torch, B) -> int:
     return 0
 
 
+def bench_dual_linesearch(args, cfg, torch, B) -> int:
+    """Dual line search (Eq. 12) over a G1 x G2 grid of scale pairs for every kernel of at most 8192 weights."""
+    G1 = G2 = args.pair_grid
+    host_w = [w for w in (cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))) if w.shape[1] <= 8192]
+    dev_w = [torch.from_numpy(w).cuda() for w in host_w]
+    ws = [B.alloc_workspace(B.mmse_workspace_bytes_dual_linesearch(w.shape[0], w.shape[1], G1, G2)) for w in host_w]
+    outs = [B.dual_line_search(d, -8, 7, G1, G2, ws=s) for d, s in zip(dev_w, ws)]
+
+    def step():
+        for d, s, o in zip(dev_w, ws, outs):
+            B.dual_line_search(d, -8, 7, G1, G2, ws=s, out=o)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    gpu_ms = e0.elapsed_time(e1) / args.steps
+    weights = sum(w.size for w in host_w)
+    pair_evals = weights * G1 * G2                    # (element, scale pair) errors, each a minimum over 16 codes
+    code_evals = pair_evals * 16
+    ops = pair_evals * (16 * 5.5 + 2)                 # VALU instructions per (element, pair)
+    roofline = {"bound": "alu", "kernel": "k_dual_ls (+ pick and codes kernels, < 1 % of the time)",
+                "achieved": ops / (gpu_ms * 1e-3) / 1e12, "peak": LANE_OPS_PER_S / 1e12,
+                "unit": "T lane-instructions/s", "frac": ops / (gpu_ms * 1e-3) / LANE_OPS_PER_S,
+                "avg_step_ms_on_stream": gpu_ms, "traffic": None,
+                "note": "5.5 VALU instructions per (element, pair, first code): fma, mul, rndne, med3, fma, half a min3; 2 per (element, pair)"}
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        sample, ok = 0, True
+        for w, o in zip(host_w, outs):
+            rows = np.unique(np.linspace(0, w.shape[0] - 1, 3).astype(int))
+            if w.shape[1] > 1200:
+                rows = rows[:1]
+            ref = oracle.can_dual_linesearch_kernelwise(np.ascontiguousarray(w[rows]), -8, 7, G1, G2)
+            sample += len(rows) * w.shape[1] * G1 * G2 * 16
+            ok = ok and all(np.array_equal(getattr(o, k).cpu().numpy()[rows], ref[k])
+                            for k in ("scale1", "scale2", "idx1", "idx2", "sse"))
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": sample / dt, "unit": "evals/s", "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": "1 to 3 kernels of every tensor", "seconds": round(dt, 3)}
+        parity = bool(ok)
+    print(json.dumps({
+        "metric": METRIC, "value": code_evals / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] weights, dual line search of two INT4 tensors "
+                               f"per kernel over a {G1} x {G2} grid of scale pairs",
+                   "tensors": len(host_w), "weights": weights, "pair_grid": [G1, G2],
+                   "evals_per_step": code_evals, "eval": "one (element, scale pair, first code) squared error"},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -173,12 +235,13 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="BASELINE.json configuration (weights part)")
     ap.add_argument("--cands-per-lane", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--part", choices=("weights", "activation", "dual"), default="weights",
+    ap.add_argument("--part", choices=("weights", "activation", "dual", "dual-ls"), default="weights",
                     help="weights: the whole-net kernel-wise path (default); activation: the largest "
                          "calibration tensor of the configuration through the per-layer path")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run plain device copies of this many MiB (for scaling FETCH_SIZE/WRITE_SIZE "
                          "counters under rocprofv3 --pmc); not part of any timed region")
+    ap.add_argument("--pair-grid", type=int, default=32, help="G1 = G2 of --part dual-ls")
     ap.add_argument("--grid-points", type=int, default=0, help="override G of the configuration")
     ap.add_argument("--refine-iters", type=int, default=-1, help="override the refinement iterations")
     args = ap.parse_args()
@@ -209,6 +272,8 @@ def main() -> int:
         return bench_activation(args, cfg, torch, B)
     if args.part == "dual":
         return bench_dual(args, cfg, torch, B)
+    if args.part == "dual-ls":
+        return bench_dual_linesearch(args, cfg, torch, B)
     G = args.grid_points if args.grid_points > 0 else cfg.grid_points
     iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
     host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]

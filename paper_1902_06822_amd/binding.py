@@ -343,16 +343,20 @@ class DualLineSearchResult:
     grid: Optional[torch.Tensor] = None
 
 
+def mmse_workspace_bytes_dual_linesearch(K: int, n: int, G1: int, G2: int) -> int:
+    out = C.c_size_t(0)
+    _check(load_library().mmse_workspace_bytes_dual_linesearch(K, n, G1, G2, C.byref(out)),
+           "mmse_workspace_bytes_dual_linesearch")
+    return out.value
+
+
 def dual_line_search(w: torch.Tensor, qmin: int, qmax: int, G1: int, G2: int, want_grid: bool = False,
                      ws: Optional[torch.Tensor] = None, out: Optional[DualLineSearchResult] = None
                      ) -> DualLineSearchResult:
     _dev(w, torch.float32)
     K, n = w.shape
     if ws is None:
-        need = C.c_size_t(0)
-        _check(load_library().mmse_workspace_bytes_dual_linesearch(K, n, G1, G2, C.byref(need)),
-               "mmse_workspace_bytes_dual_linesearch")
-        ws = alloc_workspace(need.value, w.device)
+        ws = alloc_workspace(mmse_workspace_bytes_dual_linesearch(K, n, G1, G2), w.device)
     if out is None:
         nb = (K * n + 1) // 2
         f32 = lambda: torch.empty(K, dtype=torch.float32, device=w.device)

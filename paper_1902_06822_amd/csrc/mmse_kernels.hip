@@ -889,7 +889,9 @@ struct DualLsArgs {
 };
 
 // Error of one element for the pair (a1, a2): min over the first code t of
-// (x - a1*t - a2*[(x - a1*t)/a2])^2; 7 VALU instructions per code.
+// (x - a1*t - a2*[(x - a1*t)/a2])^2.  The minimum is taken over |d| and squared once: rounding is
+// monotonic, so fl(min|d| ^2) is the minimum of the fl(d^2) bit for bit.  6 VALU instructions per code
+// (fma, mul, rndne, med3, fma, min with |.| as a source modifier).
 template <bool FULL16>
 __device__ __forceinline__ float dual_elem_err(float x, float a1, float a2, float inv2, float lo, float hi,
                                                int qmin, int qmax)
@@ -900,20 +902,20 @@ __device__ __forceinline__ float dual_elem_err(float x, float a1, float a2, floa
         for (int i = 0; i < 16; ++i) {
             const float r = __builtin_fmaf(-a1, (float)(qmin + i), x);
             const float d = __builtin_fmaf(-a2, code_of(r, inv2, lo, hi), r);
-            best = __builtin_fminf(best, d * d);
+            best = __builtin_fminf(best, __builtin_fabsf(d));
         }
     } else {
         for (int t = qmin; t <= qmax; ++t) {
             const float r = __builtin_fmaf(-a1, (float)t, x);
             const float d = __builtin_fmaf(-a2, code_of(r, inv2, lo, hi), r);
-            best = __builtin_fminf(best, d * d);
+            best = __builtin_fminf(best, __builtin_fabsf(d));
         }
     }
-    return best;
+    return best * best;
 }
 
-// One workgroup per (kernel, split): the kernel's slice sits in LDS; a wave takes units
-// (first scale a, group of 64 second scales), lane = second scale; every unit is a full sweep of the
+// One workgroup per (kernel, split): the kernel's slice sits in LDS; a wave takes units of 64
+// consecutive pairs in row-major (a, b) order, lane = pair; every unit is a full sweep of the
 // slice.  The best (error, flat index) of the workgroup goes to the workspace; k_dual_ls_pick
 // takes the minimum over the splits.  The splits exist so that a layer with few kernels still
 // fills the GPU.
@@ -976,17 +978,17 @@ __global__ void __launch_bounds__(512) k_dual_ls(const DualLsArgs A)
     }
 
     const float qmaxf = (float)A.qmax, G1f = (float)A.G1, G2f = (float)A.G2;
-    const int nbg = (A.G2 + 63) >> 6;
-    const int units = A.G1 * nbg;
+    const int pairs = A.G1 * A.G2;
+    const int units = (pairs + 63) >> 6;
     const float4* s4 = reinterpret_cast<const float4*>(slice);
     double bE = inf;
     int bI = INT_MAX;
     for (int u = sp * nwaves + wave; u < units; u += A.splits * nwaves) {
-        const int ja = u / nbg, bg = u - ja * nbg;
-        const int jb = bg * 64 + lane;
-        const bool valid = jb < A.G2;
+        const bool valid = u * 64 + lane < pairs;
+        const int flat = valid ? u * 64 + lane : pairs - 1;
+        const int ja = flat / A.G2, jb = flat - ja * A.G2;
         const float a1 = grid_alpha(a, qmaxf, G1f, ja);
-        const float a2 = a1 * ((float)((valid ? jb : A.G2 - 1) + 1) / G2f);
+        const float a2 = a1 * ((float)(jb + 1) / G2f);
         const float inv2 = 1.0f / a2;
         double st[1][kLevelsKWSmall];
 #pragma unroll
@@ -1008,7 +1010,6 @@ __global__ void __launch_bounds__(512) k_dual_ls(const DualLsArgs A)
         double E1[1];
         tree_fold<1, kLevelsKWSmall>(st, ci, E1);
         const double E = E1[0];
-        const int flat = ja * A.G2 + jb;
         if (valid) {
             if (A.grid) A.grid[(size_t)k * A.G1 * A.G2 + flat] = E;
             if (E < bE || (E == bE && flat < bI)) { bE = E; bI = flat; }
@@ -1985,12 +1986,18 @@ int dual_quantize_alternating(const float* w_dev, int64_t K, int64_t n, const mm
     return dual_quantize_alternating_batched(&d, 1, p, eps, max_sweeps, ws_dev, ws_bytes, stream);
 }
 
+static int dual_ls_waves(int G1, int G2)
+{
+    const int units = (G1 * G2 + 63) / 64;
+    return units < 8 ? units : 8;
+}
+
 static int dual_ls_splits(int64_t K, int G1, int G2)
 {
-    // enough workgroups of 8 waves to give every SIMD about four waves, but never more splits than units per wave
-    const int units = G1 * ((G2 + 63) / 64);
-    long long want = (4096 + K * 8 - 1) / (K * 8);
-    const int cap = (units + 7) / 8;
+    // enough workgroups to give every SIMD about four waves, but never more splits than units per wave
+    const int units = (G1 * G2 + 63) / 64, nw = dual_ls_waves(G1, G2);
+    long long want = (4096 + K * nw - 1) / (K * nw);
+    const int cap = (units + nw - 1) / nw;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
     return (int)want;
@@ -2039,8 +2046,9 @@ int dual_line_search(const float* w_dev, int64_t K, int64_t n, int32_t qmin, int
     const int npad = (int)((n + kChunk - 1) & ~(int64_t)(kChunk - 1));
     const size_t lds = (size_t)npad * sizeof(float);
     const unsigned nwg = (unsigned)(K * A.splits);
-    if (qmax - qmin == 15) hipLaunchKernelGGL(k_dual_ls<true>, dim3(nwg), dim3(512), lds, s, A);
-    else hipLaunchKernelGGL(k_dual_ls<false>, dim3(nwg), dim3(512), lds, s, A);
+    const unsigned nthr = 64u * (unsigned)dual_ls_waves(G1, G2);
+    if (qmax - qmin == 15) hipLaunchKernelGGL(k_dual_ls<true>, dim3(nwg), dim3(nthr), lds, s, A);
+    else hipLaunchKernelGGL(k_dual_ls<false>, dim3(nwg), dim3(nthr), lds, s, A);
     if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
     hipLaunchKernelGGL(k_dual_ls_pick, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s, A);
     if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
