@@ -58,6 +58,10 @@ def _load():
         "can_dual_linesearch": (i32, [f32p, i64, i32, i32, i32, i32, f32p, f32p, i32p, i32p, f64p, i32p, i32p, f64p]),
         "can_dual_linesearch_kernelwise": (None, [f32p, i64, i64, i32, i32, i32, i32, f32p, f32p, i32p, i32p, f64p,
                                                   u8p, u8p]),
+        "can_act_residual_quantize": (i32, [f32p, i64, f32, i32, i32, i32, i32, i32, i32, f32p, i32p, f64p, u8p]),
+        "def_offset_sse": (f64, [f32p, i64, f64, f64, i32]),
+        "can_min": (f32, [f32p, i64]),
+        "can_offset_search": (i32, [f32p, i64, i32, i32, i32, f32p, f32p, i32p, f64p, u8p]),
         "oracle_num_threads": (i32, []),
     }
     for name, (res, args) in sig.items():
@@ -287,3 +291,35 @@ def can_dual_linesearch_kernelwise(w, qmin: int, qmax: int, G1: int, G2: int):
         _p(out["idx1"], C.c_int32), _p(out["idx2"], C.c_int32), _p(out["sse"], C.c_double),
         _p(out["packed1"], C.c_uint8), _p(out["packed2"], C.c_uint8))
     return out
+
+
+def can_act_residual_quantize(x, beta1, q1, q2, G: int, iters: int):
+    """Eq. 16: second tensor of an activation.  q1, q2 = (qmin, qmax) of the first and second tensor."""
+    x = _f32(x).ravel()
+    b2, idx, sse = np.zeros(1, np.float32), np.zeros(1, np.int32), np.zeros(1, np.float64)
+    packed = np.zeros((x.size + 1) // 2, np.uint8)
+    rc = _load().can_act_residual_quantize(_p(x, C.c_float), x.size, float(beta1), q1[0], q1[1], q2[0], q2[1],
+                                           G, iters, _p(b2, C.c_float), _p(idx, C.c_int32), _p(sse, C.c_double),
+                                           _p(packed, C.c_uint8))
+    return {"scale": b2[0], "idx": int(idx[0]), "sse": float(sse[0]), "packed": packed, "rc": int(rc)}
+
+
+def def_offset_sse(x, delta: float, alpha: float, qmax: int) -> float:
+    x = _f32(x).ravel()
+    return float(_load().def_offset_sse(_p(x, C.c_float), x.size, float(delta), float(alpha), qmax))
+
+
+def can_min(x) -> np.float32:
+    x = _f32(x).ravel()
+    return np.float32(_load().can_min(_p(x, C.c_float), x.size))
+
+
+def can_offset_search(x, qmax: int, G: int, iters: int):
+    """Eq. 2 with the MMSE scale: dict(delta, scale, idx, sse, packed, rc)."""
+    x = _f32(x).ravel()
+    d, a = np.zeros(1, np.float32), np.zeros(1, np.float32)
+    idx, sse = np.zeros(1, np.int32), np.zeros(1, np.float64)
+    packed = np.zeros((x.size + 1) // 2, np.uint8)
+    rc = _load().can_offset_search(_p(x, C.c_float), x.size, qmax, G, iters, _p(d, C.c_float), _p(a, C.c_float),
+                                   _p(idx, C.c_int32), _p(sse, C.c_double), _p(packed, C.c_uint8))
+    return {"delta": d[0], "scale": a[0], "idx": int(idx[0]), "sse": float(sse[0]), "packed": packed, "rc": int(rc)}

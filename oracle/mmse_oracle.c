@@ -597,6 +597,69 @@ void can_dual_linesearch_kernelwise(const float *w, int64_t K, int64_t n, int qm
     free(q1); free(q2);
 }
 
+/* ------------------------------------------------------------------ */
+/* Activation variants: second tensor (Section 3.7, Eq. 16), offset     */
+/* form (Section 3.1, Eq. 2)                                            */
+/* ------------------------------------------------------------------ */
+
+/* Eq. 16: X ~ beta1*[X/beta1] + beta2*[(X - beta1*X1)/beta2].  beta1 comes from the per-layer search
+ * (Eq. 15) and is given; the residual is formed like a weight residual (one fused multiply-add per
+ * element, first tensor saturated to [qmin1, qmax1]) and then searched and coded as a tensor of its
+ * own in [qmin2, qmax2] ("one iteration only").  The residual of unsigned codes is signed, so the two
+ * ranges are separate arguments. */
+int can_act_residual_quantize(const float *x, int64_t N, float beta1, int qmin1, int qmax1,
+                              int qmin2, int qmax2, int G, int iters,
+                              float *beta2, int32_t *idx2, double *sse2, uint8_t *packed2)
+{
+    float *resid = (float *)malloc(sizeof(float) * (size_t)(N > 0 ? N : 1));
+    can_residual(x, 1, N, &beta1, qmin1, qmax1, resid);
+    int rc = can_search(resid, N, qmin2, qmax2, G, iters, beta2, idx2, sse2, NULL, NULL);
+    if (packed2) can_quantize_pack_int4(resid, 1, N, beta2, qmin2, qmax2, packed2);
+    free(resid);
+    return rc;
+}
+
+/* Eq. 2 as written, in fp64: sum_i (T_i - (alpha*[(T_i - delta)/alpha] + delta))^2 over 0..qmax. */
+double def_offset_sse(const float *x, int64_t n, double delta, double alpha, int qmax)
+{
+    double s = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double that = alpha * def_round_sat(((double)x[i] - delta) / alpha, 0, qmax) + delta;
+        double r = (double)x[i] - that;
+        s += r * r;
+    }
+    return s;
+}
+
+/* delta = min_i T_i (Eq. 2); NaN if any element is not finite. */
+float can_min(const float *x, int64_t n)
+{
+    float m = INFINITY;
+    int bad = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (!isfinite(x[i])) bad = 1;
+        if (x[i] < m) m = x[i];
+    }
+    return bad ? NAN : m;
+}
+
+/* Offset form with the scale found by the MMSE search instead of Eq. 2's (max - delta)/(2^p - 1):
+ * the shifted tensor T - delta (one fp32 subtraction per element) is searched and coded in the
+ * unsigned range 0..qmax; the last grid point is Eq. 2's uniform scale.  T ~ alpha*codes + delta.
+ * Rejected input: delta, scale and sse NaN, idx -1, codes 0. */
+int can_offset_search(const float *x, int64_t N, int qmax, int G, int iters,
+                      float *delta, float *scale, int32_t *idx, double *sse, uint8_t *packed)
+{
+    float *y = (float *)malloc(sizeof(float) * (size_t)(N > 0 ? N : 1));
+    float d = can_min(x, N);
+    for (int64_t i = 0; i < N; ++i) y[i] = x[i] - d;
+    int rc = can_search(y, N, 0, qmax, G, iters, scale, idx, sse, NULL, NULL);
+    *delta = rc == 0 ? d : NAN;
+    if (packed) can_quantize_pack_int4(y, 1, N, scale, 0, qmax, packed);
+    free(y);
+    return rc;
+}
+
 int oracle_num_threads(void)
 {
     int nthreads = 1;

@@ -50,7 +50,27 @@ MUTATIONS = [
     ("dual search: last of equal minima", "if (e < best) { best = e; ba = ja; bb = jb; }", "if (e <= best) { best = e; ba = ja; bb = jb; }"),
     ("dual search: codes of the wrong scale pair", "can_dual_codes(x, n, *a1_out, *a2_out, qmin, qmax, q1, q2);", "can_dual_codes(x, n, *a1_out, *a1_out, qmin, qmax, q1, q2);"),
     ("dual search: highest code wins ties", "if (e < best) { best = e; bt = t; bq = (int)q; }", "if (e <= best) { best = e; bt = t; bq = (int)q; }"),
-    ("tiny tensors not special-cased", "} else if (a < ORACLE_TINY) {", "} else if (a < 0.0f) {"),
+    ("activation residual: second tensor saturated to the first range",
+     "int rc = can_search(resid, N, qmin2, qmax2, G, iters, beta2, idx2, sse2, NULL, NULL);",
+     "int rc = can_search(resid, N, qmin1, qmax1, G, iters, beta2, idx2, sse2, NULL, NULL);"),
+    ("activation residual: first tensor saturated to the second range",
+     "can_residual(x, 1, N, &beta1, qmin1, qmax1, resid);", "can_residual(x, 1, N, &beta1, qmin2, qmax2, resid);"),
+    ("activation residual: codes of the input, not of the residual",
+     "if (packed2) can_quantize_pack_int4(resid, 1, N, beta2, qmin2, qmax2, packed2);",
+     "if (packed2) can_quantize_pack_int4(x, 1, N, beta2, qmin2, qmax2, packed2);"),
+    ("offset: delta is the maximum", "if (x[i] < m) m = x[i];\n    }\n    return bad ? NAN : m;", "if (-x[i] < m) m = -x[i];\n    }\n    return bad ? NAN : -m;"),
+    ("offset: delta added, not subtracted", "for (int64_t i = 0; i < N; ++i) y[i] = x[i] - d;", "for (int64_t i = 0; i < N; ++i) y[i] = x[i] + d;"),
+    ("offset: shifted tensor searched in a signed range", "int rc = can_search(y, N, 0, qmax, G, iters, scale, idx, sse, NULL, NULL);",
+     "int rc = can_search(y, N, -qmax / 2 - 1, qmax / 2, G, iters, scale, idx, sse, NULL, NULL);"),
+    ("offset: definition forgets to add delta back", "double that = alpha * def_round_sat(((double)x[i] - delta) / alpha, 0, qmax) + delta;",
+     "double that = alpha * def_round_sat(((double)x[i] - delta) / alpha, 0, qmax);"),
+    ("offset: codes of the unshifted tensor", "if (packed) can_quantize_pack_int4(y, 1, N, scale, 0, qmax, packed);",
+     "if (packed) can_quantize_pack_int4(x, 1, N, scale, 0, qmax, packed);"),
+    ("offset: non-finite input accepted", "*delta = rc == 0 ? d : NAN;", "*delta = d;"),
+    ("tiny tensors not special-cased", "} else if (a < ORACLE_TINY) {\n        *scale = 1.0f; *idx = 0;",
+     "} else if (a < 0.0f) {\n        *scale = 1.0f; *idx = 0;"),
+    ("dual search: tiny tensors not special-cased", "} else if (a < ORACLE_TINY) {\n        *a1_out = 1.0f;",
+     "} else if (a < 0.0f) {\n        *a1_out = 1.0f;"),
     ("non-finite input accepted", "return bad ? NAN : a;", "return a;"),
 ]
 

@@ -610,6 +610,128 @@ def test_dual_linesearch_degenerate_inputs():
     assert r["rc"] == -1 and np.isnan(r["scale1"]) and r["idx1"] == -1 and np.isnan(r["sse"])
 
 
+# ------------------------------------------------------------------ activation variants (Eq. 16, Eq. 2)
+def test_activation_second_tensor_closed_form():
+    """x = m + f/16 with first scale 1: the residual is f/16, f in -7..7, which a signed second tensor
+    represents exactly with scale 1/16 = the last grid point, and with no smaller one."""
+    rng = np.random.default_rng(11)
+    m = rng.integers(0, 16, 300)
+    f = rng.integers(-7, 8, 300)
+    f[:2] = (-7, 7)
+    m[f < 0] = np.maximum(m[f < 0], 1)                      # keep x >= 0
+    x = (m + f / 16.0).astype(np.float32)
+    for G in (8, 100):
+        r = oracle.can_act_residual_quantize(x, 1.0, UNSIGNED, SIGNED, G, 20)
+        assert (r["scale"], r["idx"], r["sse"]) == (np.float32(1 / 16), G - 1, 0.0)
+        np.testing.assert_array_equal(oracle.can_unpack_int4(r["packed"], x.size, True), f)
+    # an unsigned second range cannot code the negative residuals: their squares stay
+    ru = oracle.can_act_residual_quantize(x, 1.0, UNSIGNED, UNSIGNED, 8, 0)
+    assert ru["sse"] >= float(np.sum((f[f < 0] / 16.0) ** 2)) > 0
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_activation_second_tensor_error_is_the_reconstruction_error(seed):
+    x = synth.acts_relu_normal(30000, seed)
+    first = oracle.can_search(x, *UNSIGNED, 128, 20)
+    b1 = first["scale"]
+    for q2 in (SIGNED, UNSIGNED):
+        r = oracle.can_act_residual_quantize(x, b1, UNSIGNED, q2, 128, 20)
+        q1 = np.clip(np.rint(x.astype(np.float64) / float(b1)), *UNSIGNED)
+        q2c = oracle.can_unpack_int4(r["packed"], x.size, q2[0] < 0).astype(np.float64)
+        assert q2c.min() >= q2[0] and q2c.max() <= q2[1]
+        rec = float(b1) * q1 + float(r["scale"]) * q2c                       # Eq. 16, in fp64
+        err = float(np.sum((x.astype(np.float64) - rec) ** 2))
+        assert abs(err - r["sse"]) <= 2e-5 * err
+        assert r["sse"] < first["sse"]
+    # the signed second range is the better choice for the (two-sided) residual
+    assert oracle.can_act_residual_quantize(x, b1, UNSIGNED, SIGNED, 128, 20)["sse"] < \
+        oracle.can_act_residual_quantize(x, b1, UNSIGNED, UNSIGNED, 128, 20)["sse"]
+
+
+def test_activation_second_tensor_reduces_to_the_weight_residual_for_equal_ranges():
+    w = synth.small_weights(1, 700, 9, "laplace")
+    s1 = oracle.can_search(w[0], *SIGNED, 64, 10)["scale"]
+    s2, j2, e2, p2 = oracle.can_residual_quantize(w, [s1], *SIGNED, 64, 10)
+    r = oracle.can_act_residual_quantize(w[0], s1, SIGNED, SIGNED, 64, 10)
+    assert (r["scale"], r["idx"], r["sse"]) == (s2[0], j2[0], e2[0])
+    np.testing.assert_array_equal(r["packed"], p2)
+
+
+def test_activation_second_tensor_of_an_exact_first_tensor_is_zero():
+    x = (np.float32(0.375) * np.random.default_rng(2).integers(0, 16, 500)).astype(np.float32)
+    r = oracle.can_act_residual_quantize(x, 0.375, UNSIGNED, SIGNED, 32, 5)
+    assert (r["scale"], r["idx"], r["sse"], r["rc"]) == (1.0, 0, 0.0, 0) and not r["packed"].any()
+    r = oracle.can_act_residual_quantize(x, np.nan, UNSIGNED, SIGNED, 32, 5)
+    assert r["rc"] == -1 and np.isnan(r["scale"]) and r["idx"] == -1
+
+
+def test_offset_form_hand_example():
+    """T = {-1, 0, 1, 2}, 2 bits: delta = -1, shifted tensor {0,1,2,3}; scale 1 is exact, scale 1/2
+    saturates 2 -> 1.5 and 3 -> 1.5: error 0.25 + 2.25."""
+    x = np.array([1, -1, 0, 2], np.float32)
+    o = oracle.can_offset_search(x, 3, 2, 0)
+    assert (o["delta"], o["scale"], o["idx"], o["sse"]) == (-1.0, 1.0, 1, 0.0)
+    np.testing.assert_array_equal(oracle.can_unpack_int4(o["packed"], 4, False), [2, 0, 1, 3])
+    assert oracle.def_offset_sse(x, -1.0, 0.5, 3) == 2.5
+    assert oracle.def_offset_sse(x, -1.0, 1.0, 3) == 0.0
+    assert oracle.can_min(x) == -1.0
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_offset_form_last_grid_point_is_the_uniform_quantizer_of_eq2(seed):
+    rng = np.random.default_rng(seed)
+    x = rng.normal(1.5, 1.0, 4000).astype(np.float32)
+    delta = np.float32(x.min())
+    alpha_u = np.float32(np.float32(x.max() - delta) / np.float32(15))        # Eq. 2
+    y = (x - delta).astype(np.float32)
+    assert oracle.can_grid(oracle.can_absmax(y), 15, 37)[-1] == alpha_u
+    # Eq. 2 evaluated directly in numpy fp64
+    xd = x.astype(np.float64)
+    that = float(alpha_u) * np.clip(np.rint((xd - float(delta)) / float(alpha_u)), 0, 15) + float(delta)
+    e_u = float(np.sum((xd - that) ** 2))
+    assert abs(oracle.def_offset_sse(x, delta, alpha_u, 15) - e_u) <= 1e-12 * e_u
+    o = oracle.can_offset_search(x, 15, 37, 20)
+    assert o["delta"] == delta and o["sse"] <= e_u * (1 + 1e-5)
+    # the canonical error is that of the reconstruction alpha*codes + delta
+    codes = oracle.can_unpack_int4(o["packed"], x.size, False).astype(np.float64)
+    err = float(np.sum((xd - (float(o["scale"]) * codes + float(delta))) ** 2))
+    assert abs(err - o["sse"]) <= 2e-5 * err
+    assert abs(oracle.def_offset_sse(x, delta, o["scale"], 15) - o["sse"]) <= 2e-5 * err
+
+
+def test_offset_form_is_shift_invariant_and_equals_the_unsigned_search_at_min_zero():
+    rng = np.random.default_rng(4)
+    x = (rng.integers(0, 4096, 3000) / 256.0).astype(np.float32)              # multiples of 2^-8 below 16
+    x[0] = 0.0
+    a = oracle.can_offset_search(x, 15, 64, 20)
+    plain = oracle.can_search(x, *UNSIGNED, 64, 20)
+    assert (a["delta"], a["scale"], a["idx"], a["sse"]) == (0.0, plain["scale"], plain["idx"], plain["sse"])
+    np.testing.assert_array_equal(a["packed"], oracle.can_quantize_pack_int4(x, [plain["scale"]], *UNSIGNED))
+    for c in (-8.0, 32.0, -1024.0):                                             # exact shifts
+        b = oracle.can_offset_search((x + np.float32(c)).astype(np.float32), 15, 64, 20)
+        assert (b["delta"], b["scale"], b["idx"], b["sse"]) == (c, a["scale"], a["idx"], a["sse"])
+        np.testing.assert_array_equal(b["packed"], a["packed"])
+
+
+def test_offset_form_beats_the_signed_form_on_asymmetric_data():
+    x = np.random.default_rng(8).normal(3.0, 1.0, 6000).astype(np.float32)
+    assert oracle.can_offset_search(x, 15, 128, 20)["sse"] < 0.5 * oracle.can_search(x, *SIGNED, 128, 20)["sse"]
+
+
+def test_offset_form_degenerate_inputs():
+    c = np.full(100, 2.5, np.float32)
+    o = oracle.can_offset_search(c, 15, 16, 4)
+    assert (o["delta"], o["scale"], o["idx"], o["sse"], o["rc"]) == (2.5, 1.0, 0, 0.0, 0) and not o["packed"].any()
+    for bad in (np.nan, np.inf, -np.inf):
+        c[7] = bad
+        o = oracle.can_offset_search(c, 15, 16, 4)
+        assert o["rc"] == -1 and np.isnan(o["delta"]) and np.isnan(o["scale"]) and o["idx"] == -1
+        assert np.isnan(oracle.can_min(c))
+    wide = np.array([2.0 ** 61, 0.0, 1.0], np.float32)       # finite, but the shifted range exceeds the accepted one
+    o = oracle.can_offset_search(wide, 15, 16, 4)
+    assert o["rc"] == -1 and np.isnan(o["delta"]) and np.isnan(o["scale"]) and not o["packed"].any()
+
+
 # ------------------------------------------------------------------ workloads
 def test_workload_shapes_match_architectures():
     c = [synth.config(i) for i in range(1, 6)]
