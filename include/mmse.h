@@ -104,6 +104,29 @@ int mmse_scale_search_activation(const float *x_dev, int64_t N, const mmse_param
                                  float *scale_dev, int32_t *idx_dev, double *sse_dev,
                                  void *ws_dev, size_t ws_bytes, void *stream);
 
+/* Second tensor of an activation (Section 3.7, Eq. 16): X ~ beta1*[X/beta1] + beta2*[(X - beta1*X1)/beta2].
+ * scale1_dev holds beta1 (one float, device; normally the output of mmse_scale_search_activation), the
+ * first codes X1 = [X/beta1] saturate to [qmin1, qmax1]; the residual X - beta1*X1 (one fused
+ * multiply-add per element, never stored) is searched in p's range with p's grid and refinement
+ * ("one iteration only" of Algorithm 1).  The residual of unsigned first codes has both signs, so the
+ * second range is independent of the first: p->qmin..p->qmax, e.g. -8..7.  Outputs as in
+ * mmse_scale_search_activation, plus the residual's codes in packed2_dev (ceil(N/2) bytes, layout of
+ * quantize_pack_int4) when it is not NULL.  A NaN or rejected beta1 rejects the residual too.
+ * Workspace: mmse_workspace_bytes_activation(N, p). */
+int activation_residual_quantize(const float *x_dev, int64_t N, const float *scale1_dev, int32_t qmin1, int32_t qmax1,
+                                 const mmse_params_t *p, float *scale2_dev, int32_t *idx2_dev, double *sse2_dev,
+                                 uint8_t *packed2_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Offset form (Section 3.1, Eq. 2) with the scale found by the MMSE search: delta = min_i x_i, the shifted
+ * tensor x - delta (one fp32 subtraction per element, never stored) is searched in the unsigned range
+ * 0..p->qmax (p->qmin must be 0); the last grid point is Eq. 2's own scale (max - delta)/qmax.
+ * x ~ scale*codes + delta.  delta_dev: one float out (NaN when the tensor is rejected: a non-finite element,
+ * or max - min above 2^60); sse_dev is the error of the shifted tensor; packed_dev (optional) its codes.
+ * Workspace: mmse_workspace_bytes_activation(N, p). */
+int mmse_scale_search_offset(const float *x_dev, int64_t N, const mmse_params_t *p, float *delta_dev,
+                             float *scale_dev, int32_t *idx_dev, double *sse_dev, uint8_t *packed_dev,
+                             void *ws_dev, size_t ws_bytes, void *stream);
+
 /* Q = [x/scale]_Zp (Section 3.4) for a [K][n] tensor with one scale per row, packed
  * two codes per byte in memory order over the whole tensor: element 2m in the low
  * nibble of byte m, element 2m+1 in the high nibble, two's-complement nibbles, a

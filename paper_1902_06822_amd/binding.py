@@ -23,6 +23,7 @@ EXPORTS = (
     "mmse_grid_sse_kernelwise", "mmse_workspace_bytes_dual", "dual_quantize_alternating",
     "mmse_workspace_bytes_dual_batched", "dual_quantize_alternating_batched",
     "mmse_workspace_bytes_dual_linesearch", "dual_line_search",
+    "activation_residual_quantize", "mmse_scale_search_offset",
     "mmse_status_string",
 )
 
@@ -76,6 +77,9 @@ def load_library() -> C.CDLL:
     lib.mmse_workspace_bytes_dual_linesearch.argtypes = [i64, i64, i32, i32, szp]
     lib.dual_line_search.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                      C.c_size_t, vp]
+    lib.activation_residual_quantize.argtypes = [vp, i64, vp, i32, i32, C.POINTER(MmseParams), vp, vp, vp, vp, vp,
+                                                 C.c_size_t, vp]
+    lib.mmse_scale_search_offset.argtypes = [vp, i64, C.POINTER(MmseParams), vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -369,4 +373,52 @@ def dual_line_search(w: torch.Tensor, qmin: int, qmax: int, G1: int, G2: int, wa
         w.data_ptr(), K, n, qmin, qmax, G1, G2, out.scale1.data_ptr(), out.scale2.data_ptr(), out.idx1.data_ptr(),
         out.idx2.data_ptr(), out.sse.data_ptr(), out.packed1.data_ptr(), out.packed2.data_ptr(), _ptr(out.grid),
         ws.data_ptr(), ws.numel(), _stream()), "dual_line_search")
+    return out
+
+
+def activation_residual_quantize(x: torch.Tensor, scale1: torch.Tensor, qmin1: int, qmax1: int, p: MmseParams,
+                                 ws: Optional[torch.Tensor] = None, out: Optional[SearchResult] = None,
+                                 want_packed: bool = True) -> SearchResult:
+    """Eq. 16: search (and codes) of the residual of the first tensor; p describes the second tensor."""
+    _dev(x, torch.float32)
+    _dev(scale1, torch.float32)
+    N = x.numel()
+    if ws is None:
+        ws = alloc_workspace(mmse_workspace_bytes_activation(N, p), x.device)
+    if out is None:
+        out = SearchResult(torch.empty(1, dtype=torch.float32, device=x.device),
+                           torch.empty(1, dtype=torch.int32, device=x.device),
+                           torch.empty(1, dtype=torch.float64, device=x.device),
+                           torch.empty((N + 1) // 2, dtype=torch.uint8, device=x.device) if want_packed else None)
+    _check(load_library().activation_residual_quantize(
+        x.data_ptr(), N, scale1.data_ptr(), qmin1, qmax1, C.byref(p), out.scale.data_ptr(), out.idx.data_ptr(),
+        out.sse.data_ptr(), _ptr(out.packed), ws.data_ptr(), ws.numel(), _stream()), "activation_residual_quantize")
+    return out
+
+
+@dataclass
+class OffsetResult:
+    delta: torch.Tensor
+    scale: torch.Tensor
+    idx: torch.Tensor
+    sse: torch.Tensor
+    packed: Optional[torch.Tensor] = None
+
+
+def mmse_scale_search_offset(x: torch.Tensor, p: MmseParams, ws: Optional[torch.Tensor] = None,
+                             out: Optional[OffsetResult] = None, want_packed: bool = True) -> OffsetResult:
+    """Eq. 2 with the MMSE scale: delta = min x, unsigned codes of x - delta."""
+    _dev(x, torch.float32)
+    N = x.numel()
+    if ws is None:
+        ws = alloc_workspace(mmse_workspace_bytes_activation(N, p), x.device)
+    if out is None:
+        out = OffsetResult(torch.empty(1, dtype=torch.float32, device=x.device),
+                           torch.empty(1, dtype=torch.float32, device=x.device),
+                           torch.empty(1, dtype=torch.int32, device=x.device),
+                           torch.empty(1, dtype=torch.float64, device=x.device),
+                           torch.empty((N + 1) // 2, dtype=torch.uint8, device=x.device) if want_packed else None)
+    _check(load_library().mmse_scale_search_offset(
+        x.data_ptr(), N, C.byref(p), out.delta.data_ptr(), out.scale.data_ptr(), out.idx.data_ptr(),
+        out.sse.data_ptr(), _ptr(out.packed), ws.data_ptr(), ws.numel(), _stream()), "mmse_scale_search_offset")
     return out

@@ -1121,7 +1121,46 @@ struct ActState {
     float lo_a, hi_a, pc, pd, best_a;
     float probes[kMaxProbes];
     double ec, ed, best;
+    unsigned min_key, max_key;   // offset form: order-preserving keys of min and max
+    float delta;                 // offset form: min of the tensor
 };
+
+// What the activation kernels search instead of the stored tensor (never written to memory):
+//   mode 1: the residual of a first tensor, x - s*[x/s] saturated to [lo1, hi1]   (Section 3.7, Eq. 16)
+//   mode 2: the shifted tensor x - delta, delta = min x                            (Section 3.1, Eq. 2)
+struct ActPre {
+    int mode;
+    const float* s;              // device: the first scale (mode 1) or delta (mode 2)
+    float lo1, hi1;
+};
+struct ActPreV { int mode; float s, inv, lo1, hi1; };
+
+__device__ __forceinline__ ActPreV act_pre_load(const ActPre& P)
+{
+    ActPreV V;
+    V.mode = P.mode; V.lo1 = P.lo1; V.hi1 = P.hi1;
+    V.s = P.mode != 0 ? *P.s : 0.0f;
+    V.inv = P.mode == 1 ? 1.0f / V.s : 0.0f;
+    return V;
+}
+
+__device__ __forceinline__ float act_pre(const ActPreV& V, float v)
+{
+    if (V.mode == 1) return __builtin_fmaf(-V.s, code_of(v, V.inv, V.lo1, V.hi1), v);
+    if (V.mode == 2) return v - V.s;
+    return v;
+}
+
+// Order-preserving map of fp32 bit patterns to unsigned integers (-NaN < -inf < ... < +inf < +NaN).
+__device__ __forceinline__ unsigned order_key(float v)
+{
+    const unsigned b = __float_as_uint(v);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float order_unkey(unsigned k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
 
 __global__ void k_act_init(ActState* S)
 {
@@ -1131,6 +1170,7 @@ __global__ void k_act_init(ActState* S)
         S->lo_a = S->hi_a = S->pc = S->pd = S->best_a = 1.0f;
         for (int i = 0; i < kMaxProbes; ++i) S->probes[i] = 1.0f;
         S->ec = S->ed = S->best = 0.0;
+        S->min_key = 0xffffffffu; S->max_key = 0u; S->delta = 0.0f;
     }
 }
 
@@ -1218,11 +1258,28 @@ __device__ void act_advance(ActState* S, const double* vals, int iters)
     S->have_c = have_c; S->have_d = have_d; S->it = it; S->done = done;
 }
 
-template <int U>
-__global__ void __launch_bounds__(256) k_act_absmax(const float* __restrict__ x, long long N, ActState* S)
+// MODE 0: max |x| (integer max of the bit patterns); 1: max |residual of the first tensor|;
+// 2: min and max of x as order-preserving keys (offset form).
+template <int U, int MODE>
+__global__ void __launch_bounds__(256) k_act_absmax(const float* __restrict__ x, long long N, ActState* S,
+                                                    const ActPre pre)
 {
     __shared__ unsigned s_amax[4];
-    unsigned amax = 0;
+    __shared__ unsigned s_amin[4];
+    unsigned amax = 0, amin = 0xffffffffu;
+    ActPreV V{};
+    if constexpr (MODE == 1) V = act_pre_load(pre);
+    auto take = [&](float v) {
+        if constexpr (MODE == 2) {
+            const unsigned k = order_key(v);
+            amax = k > amax ? k : amax;
+            amin = k < amin ? k : amin;
+        } else {
+            if constexpr (MODE == 1) v = act_pre(V, v);
+            const unsigned b = abs_bits(v);
+            amax = b > amax ? b : amax;
+        }
+    };
     const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
     // U independent 16-byte loads per thread and trip: enough bytes in flight to fill HBM
     const long long tile = (long long)blockDim.x * 4 * U;                 // elements per workgroup and trip
@@ -1234,33 +1291,49 @@ __global__ void __launch_bounds__(256) k_act_absmax(const float* __restrict__ x,
             for (int u = 0; u < U; ++u)
                 v[u] = *reinterpret_cast<const float4*>(x + base + ((long long)u * blockDim.x + threadIdx.x) * 4);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                unsigned b = abs_bits(v[u].x); amax = b > amax ? b : amax;
-                b = abs_bits(v[u].y); amax = b > amax ? b : amax;
-                b = abs_bits(v[u].z); amax = b > amax ? b : amax;
-                b = abs_bits(v[u].w); amax = b > amax ? b : amax;
-            }
+            for (int u = 0; u < U; ++u) { take(v[u].x); take(v[u].y); take(v[u].z); take(v[u].w); }
         } else {
-            for (long long i = base + threadIdx.x; i < base + tile && i < N; i += blockDim.x) {
-                const unsigned b = abs_bits(x[i]);
-                amax = b > amax ? b : amax;
-            }
+            for (long long i = base + threadIdx.x; i < base + tile && i < N; i += blockDim.x) take(x[i]);
         }
     }
     amax = wave_max_u32(amax);
-    if ((threadIdx.x & 63) == 0) s_amax[threadIdx.x >> 6] = amax;
+    if constexpr (MODE == 2) amin = ~wave_max_u32(~amin);
+    if ((threadIdx.x & 63) == 0) { s_amax[threadIdx.x >> 6] = amax; s_amin[threadIdx.x >> 6] = amin; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned am = s_amax[0];
-        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) am = s_amax[w] > am ? s_amax[w] : am;
-        atomicMax(&S->absmax_bits, am);       // integer max: exact and order-free
+        unsigned am = s_amax[0], an = s_amin[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) {
+            am = s_amax[w] > am ? s_amax[w] : am;
+            an = s_amin[w] < an ? s_amin[w] : an;
+        }
+        if constexpr (MODE == 2) {
+            atomicMax(&S->max_key, am);
+            atomicMin(&S->min_key, an);
+        } else {
+            atomicMax(&S->absmax_bits, am);       // integer max: exact and order-free
+        }
     }
+}
+
+// Offset form: delta = min x; the search range is that of x - delta, whose largest element is
+// fl(max - delta) because rounding is monotonic.  Anything not finite rejects the tensor.
+__global__ void k_act_offset_setup(ActState* S, float* delta_out)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const float mn = order_unkey(S->min_key), mx = order_unkey(S->max_key);
+    const float nanf_ = __uint_as_float(0x7fc00000u);
+    const bool finite = (abs_bits(mn) < 0x7f800000u) && (abs_bits(mx) < 0x7f800000u);
+    const float range = finite ? mx - mn : nanf_;
+    S->delta = mn;
+    S->absmax_bits = abs_bits(range);
+    *delta_out = (range <= kHuge) ? mn : nanf_;
 }
 
 // Grid sweep of one 4096-element block per workgroup; waves split the candidates.
 template <int C>
 __global__ void __launch_bounds__(512) k_act_sweep(const float* __restrict__ x, long long N, int G, int qmax,
-                                                    float lo, float hi, const ActState* S, double* part0)
+                                                    float lo, float hi, const ActState* S, double* part0,
+                                                    const ActPre pre)
 {
     __shared__ float4 slice4[kBlockElems / 4];
     float* slice = reinterpret_cast<float*>(slice4);
@@ -1271,7 +1344,8 @@ __global__ void __launch_bounds__(512) k_act_sweep(const float* __restrict__ x, 
     const long long base = (long long)blockIdx.x * kBlockElems;
     const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
     const int npad = (len + kChunk - 1) & ~(kChunk - 1);
-    for (int i = tid; i < npad; i += nthreads) slice[i] = i < len ? x[base + i] : 0.0f;
+    const ActPreV V = act_pre_load(pre);
+    for (int i = tid; i < npad; i += nthreads) slice[i] = i < len ? act_pre(V, x[base + i]) : 0.0f;
     __syncthreads();
 
     const float qmaxf = (float)qmax, Gf = (float)G;
@@ -1377,10 +1451,11 @@ __global__ void __launch_bounds__(1024) k_act_argmin(const double* __restrict__ 
 // turns them into one chunk per lane through a wave-private LDS tile (32 chunks at a time);
 // fp32 chunk sums per scale, then the first six tree levels by wave shuffles.
 __global__ void __launch_bounds__(256) k_act_probe(const float* __restrict__ x, long long N, float lo, float hi,
-                                                   const ActState* S, double* probe0)
+                                                   const ActState* S, double* probe0, const ActPre pre)
 {
     __shared__ float4 tile4[4][32 * kTileStride / 4];
     if (S->status != 0 || S->done) return;
+    const ActPreV V = act_pre_load(pre);
     const int np = S->nprobe;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long long blk = (long long)blockIdx.x * 4 + wave;
@@ -1400,11 +1475,12 @@ __global__ void __launch_bounds__(256) k_act_probe(const float* __restrict__ x, 
             float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             if (aligned && e + 4 <= N) {
                 v = *reinterpret_cast<const float4*>(x + e);
-            } else if (e < N) {
-                v.x = x[e];
-                if (e + 1 < N) v.y = x[e + 1];
-                if (e + 2 < N) v.z = x[e + 2];
-                if (e + 3 < N) v.w = x[e + 3];
+                if (V.mode != 0) { v.x = act_pre(V, v.x); v.y = act_pre(V, v.y); v.z = act_pre(V, v.z); v.w = act_pre(V, v.w); }
+            } else if (e < N) {                                    // padding stays exactly zero
+                v.x = act_pre(V, x[e]);
+                if (e + 1 < N) v.y = act_pre(V, x[e + 1]);
+                if (e + 2 < N) v.z = act_pre(V, x[e + 2]);
+                if (e + 3 < N) v.w = act_pre(V, x[e + 3]);
             }
             *reinterpret_cast<float4*>(tile + (f >> 4) * kTileStride + (f & 15) * 4) = v;
         }
@@ -1657,6 +1733,44 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
         if (rc) return rc;
     }
     return MMSE_OK;
+}
+
+// Codes of the searched tensor (residual or shifted input) for its final scale, 8 elements per
+// thread, two per byte; a rejected tensor (scale NaN) is coded as zeros.
+__global__ void __launch_bounds__(kPackThreads) k_act_pack(const float* __restrict__ x, long long N, const ActPre pre,
+                                                           const float* __restrict__ scale, float lo, float hi,
+                                                           uint8_t* __restrict__ packed)
+{
+    const long long e0 = ((long long)blockIdx.x * kPackThreads + threadIdx.x) * kPackPerThread;
+    if (e0 >= N) return;
+    const int cnt = (N - e0) < kPackPerThread ? (int)(N - e0) : kPackPerThread;
+    const ActPreV V = act_pre_load(pre);
+    const float sc = *scale, inv = 1.0f / sc;
+    float v[kPackPerThread];
+    if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
+        const float4 p0 = reinterpret_cast<const float4*>(x + e0)[0];
+        const float4 p1 = reinterpret_cast<const float4*>(x + e0)[1];
+        v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w;
+        v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < kPackPerThread; ++i) v[i] = (i < cnt) ? x[e0 + i] : 0.0f;
+    }
+    unsigned word = 0;
+#pragma unroll
+    for (int i = 0; i < kPackPerThread; ++i) {
+        if (i < cnt) {
+            const int q = (sc == sc) ? (int)code_of(act_pre(V, v[i]), inv, lo, hi) : 0;
+            word |= ((unsigned)q & 0xFu) << (4 * i);
+        }
+    }
+    uint8_t* dst = packed + (e0 >> 1);
+    if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(packed) & 3u) == 0) {
+        *reinterpret_cast<unsigned*>(dst) = word;
+    } else {
+        const int nbytes = (cnt + 1) >> 1;
+        for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));
+    }
 }
 
 struct ActPlan {
@@ -2058,9 +2172,12 @@ int dual_line_search(const float* w_dev, int64_t K, int64_t n, int32_t qmin, int
     return MMSE_OK;
 }
 
-int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_params_t* p,
-                                 float* scale_dev, int32_t* idx_dev, double* sse_dev,
-                                 void* ws_dev, size_t ws_bytes, void* stream)
+// The per-layer search; pre_mode selects what is searched (the tensor, the residual of a first
+// tensor, the tensor shifted by its minimum); packed_dev != nullptr also writes the codes.
+static int run_activation(const float* x_dev, int64_t N, const mmse_params_t* p, int pre_mode,
+                          const float* scale1_dev, int qmin1, int qmax1, float* delta_dev,
+                          float* scale_dev, int32_t* idx_dev, double* sse_dev, uint8_t* packed_dev,
+                          void* ws_dev, size_t ws_bytes, void* stream)
 {
     int rc = check_params(p);
     if (rc) return rc;
@@ -2075,6 +2192,10 @@ int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_param
     char* ws = static_cast<char*>(ws_dev);
     ActState* S = reinterpret_cast<ActState*>(ws);
     const float lo = (float)p->qmin, hi = (float)p->qmax;
+    ActPre pre{};
+    pre.mode = pre_mode;
+    pre.s = pre_mode == 1 ? scale1_dev : (pre_mode == 2 ? &S->delta : nullptr);
+    pre.lo1 = (float)qmin1; pre.hi1 = (float)qmax1;
 #define MMSE_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH; } while (0)
 
     hipLaunchKernelGGL(k_act_init, dim3(1), dim3(64), 0, s, S);
@@ -2085,16 +2206,22 @@ int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_param
         constexpr int U = 8;
         long long want = (N + 1024 * U - 1) / (1024 * U);
         const int grid = (int)(want < 256 ? (want < 1 ? 1 : want) : 256);
-        hipLaunchKernelGGL(k_act_absmax<U>, dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S);
+        if (pre_mode == 0) hipLaunchKernelGGL((k_act_absmax<U, 0>), dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S, pre);
+        else if (pre_mode == 1) hipLaunchKernelGGL((k_act_absmax<U, 1>), dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S, pre);
+        else hipLaunchKernelGGL((k_act_absmax<U, 2>), dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S, pre);
         MMSE_CHECK_LAUNCH();
+        if (pre_mode == 2) {
+            hipLaunchKernelGGL(k_act_offset_setup, dim3(1), dim3(64), 0, s, S, delta_dev);
+            MMSE_CHECK_LAUNCH();
+        }
     }
     {
         const int C = pick_cands(p);
         const int waves = (G + 64 * C - 1) / (64 * C);
         double* part0 = reinterpret_cast<double*>(ws + P.off_part[0]);
-        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0);
-        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0);
-        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0);
+        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0, pre);
+        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0, pre);
+        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0, pre);
         MMSE_CHECK_LAUNCH();
     }
     for (int l = 0; l < P.levels; ++l) {
@@ -2113,7 +2240,7 @@ int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_param
     }
     for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
         hipLaunchKernelGGL(k_act_probe, dim3((P.nb + 3) / 4), dim3(256), 0, s, x_dev, (long long)N, lo, hi, S,
-                           reinterpret_cast<double*>(ws + P.off_probe[0]));
+                           reinterpret_cast<double*>(ws + P.off_probe[0]), pre);
         MMSE_CHECK_LAUNCH();
         for (int l = 0; l < P.plevels; ++l) {
             hipLaunchKernelGGL(k_act_reduce64, dim3(1, P.rows[l + 1]), dim3(64), 0, s,
@@ -2126,8 +2253,44 @@ int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_param
                            p->refine_iters, S, scale_dev, sse_dev);
         MMSE_CHECK_LAUNCH();
     }
+    if (packed_dev) {
+        const long long per_wg = (long long)kPackThreads * kPackPerThread;
+        hipLaunchKernelGGL(k_act_pack, dim3((unsigned)((N + per_wg - 1) / per_wg)), dim3(kPackThreads), 0, s,
+                           x_dev, (long long)N, pre, scale_dev, lo, hi, packed_dev);
+        MMSE_CHECK_LAUNCH();
+    }
 #undef MMSE_CHECK_LAUNCH
     return MMSE_OK;
+}
+
+int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_params_t* p,
+                                 float* scale_dev, int32_t* idx_dev, double* sse_dev,
+                                 void* ws_dev, size_t ws_bytes, void* stream)
+{
+    return run_activation(x_dev, N, p, 0, nullptr, 0, 0, nullptr, scale_dev, idx_dev, sse_dev, nullptr,
+                          ws_dev, ws_bytes, stream);
+}
+
+int activation_residual_quantize(const float* x_dev, int64_t N, const float* scale1_dev, int32_t qmin1, int32_t qmax1,
+                                 const mmse_params_t* p, float* scale2_dev, int32_t* idx2_dev, double* sse2_dev,
+                                 uint8_t* packed2_dev, void* ws_dev, size_t ws_bytes, void* stream)
+{
+    if (!scale1_dev) return MMSE_ERR_NULL;
+    if (!(qmin1 <= 0 && qmax1 > 0 && qmax1 - qmin1 <= 15)) return MMSE_ERR_PARAMS;
+    if (!aligned_to(scale1_dev, 4)) return MMSE_ERR_ALIGN;
+    return run_activation(x_dev, N, p, 1, scale1_dev, qmin1, qmax1, nullptr, scale2_dev, idx2_dev, sse2_dev,
+                          packed2_dev, ws_dev, ws_bytes, stream);
+}
+
+int mmse_scale_search_offset(const float* x_dev, int64_t N, const mmse_params_t* p, float* delta_dev,
+                             float* scale_dev, int32_t* idx_dev, double* sse_dev, uint8_t* packed_dev,
+                             void* ws_dev, size_t ws_bytes, void* stream)
+{
+    if (!delta_dev) return MMSE_ERR_NULL;
+    if (p && p->qmin != 0) return MMSE_ERR_PARAMS;           // Eq. 2 is stated for the unsigned range
+    if (!aligned_to(delta_dev, 4)) return MMSE_ERR_ALIGN;
+    return run_activation(x_dev, N, p, 2, nullptr, 0, 0, delta_dev, scale_dev, idx_dev, sse_dev, packed_dev,
+                          ws_dev, ws_bytes, stream);
 }
 
 }  // extern "C"

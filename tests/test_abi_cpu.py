@@ -98,6 +98,17 @@ def test_entry_points_validate_before_enqueue(B):
     assert dls(G1=0) == -3 and dls(G2=1025) == -3 and dls(qmin=1) == -3 and dls(qmin=-9) == -3
     assert dls(ws=None) == -4 and dls(ws_bytes=16) == -4 and dls(ws=a + 8) == -4
     assert dls(sse=a + 4) == -6 and dls(grid=a + 4) == -6
+    pu = B.params(0, 15, 256, 20)
+    assert lib.activation_residual_quantize(a, 64, None, 0, 15, C.byref(p), a, a, a, a, a, 1 << 20, None) == -1
+    assert lib.activation_residual_quantize(a, 64, a, 1, 15, C.byref(p), a, a, a, a, a, 1 << 20, None) == -3
+    assert lib.activation_residual_quantize(a, 64, a, 0, 16, C.byref(p), a, a, a, a, a, 1 << 20, None) == -3
+    assert lib.activation_residual_quantize(a, 0, a, 0, 15, C.byref(p), a, a, a, a, a, 1 << 20, None) == -2
+    assert lib.activation_residual_quantize(a, 64, a, 0, 15, C.byref(p), a, a, a, a, a, 16, None) == -4
+    assert lib.mmse_scale_search_offset(a, 64, C.byref(pu), None, a, a, a, a, a, 1 << 20, None) == -1
+    assert lib.mmse_scale_search_offset(a, 64, C.byref(p), a, a, a, a, a, a, 1 << 20, None) == -3      # signed range
+    assert lib.mmse_scale_search_offset(None, 64, C.byref(pu), a, a, a, a, a, a, 1 << 20, None) == -1
+    assert lib.mmse_scale_search_offset(a, 64, C.byref(pu), a + 2, a, a, a, a, a, 1 << 20, None) == -6
+    assert lib.mmse_scale_search_offset(a, 64, C.byref(pu), a, a, a, a, a, None, 0, None) == -4
     # sizes
     assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
     assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2

@@ -105,6 +105,38 @@ def test_full_size_activation_tensors(B, cfg, which):
     assert float(r.sse[0]) <= oracle.can_sse(x, np.float32(x.max()) / np.float32(15), *UNSIGNED)
 
 
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_full_size_activation_second_tensor_and_offset_form(B, cfg):
+    """Eq. 16 and Eq. 2 on the largest calibration tensor of the configuration, complete comparison."""
+    import torch
+    c = synth.config(cfg)
+    li = int(np.argmax([a.per_image for a in c.act_shapes]))
+    x = c.act_tensor(li)
+    say(f"config {cfg}: second tensor and offset form of {c.act_shapes[li].name} N={x.size}")
+    xd = to_dev(x)
+    G, it = c.grid_points, c.refine_iters
+    first = B.mmse_scale_search_activation(xd, B.params(*UNSIGNED, G, it))
+    r2 = B.activation_residual_quantize(xd, first.scale, *UNSIGNED, B.params(*SIGNED, G, it))
+    torch.cuda.synchronize()
+    o1 = oracle.can_search(x, *UNSIGNED, G, it)
+    o2 = oracle.can_act_residual_quantize(x, o1["scale"], UNSIGNED, SIGNED, G, it)
+    assert float(first.scale[0]) == o1["scale"]
+    check_equal(r2, np.array([o2["scale"]], np.float32), np.array([o2["idx"]], np.int32), np.array([o2["sse"]]),
+                f"cfg{cfg} second tensor")
+    np.testing.assert_array_equal(r2.packed.cpu().numpy(), o2["packed"])
+    assert float(r2.sse[0]) < o1["sse"]
+    del r2
+    y = x - np.float32(0.75)                       # a pre-activation-like tensor with a negative floor
+    yd = to_dev(y)
+    ro = B.mmse_scale_search_offset(yd, B.params(*UNSIGNED, G, it))
+    torch.cuda.synchronize()
+    oo = oracle.can_offset_search(y, 15, G, it)
+    assert float(ro.delta[0]) == oo["delta"] == -0.75
+    check_equal(ro, np.array([oo["scale"]], np.float32), np.array([oo["idx"]], np.int32), np.array([oo["sse"]]),
+                f"cfg{cfg} offset")
+    np.testing.assert_array_equal(ro.packed.cpu().numpy(), oo["packed"])
+
+
 def test_config5_weights_and_residual_on_sampled_kernels(B):
     import torch
     c = synth.config(5)
