@@ -54,9 +54,25 @@ def bench_activation(args, cfg, torch, B) -> int:
                          torch.empty(1, dtype=torch.float64, device="cuda"))
     packed = torch.empty((N + 1) // 2, dtype=torch.uint8, device="cuda")
 
+    variant = args.act_variant
+    if variant == "offset":
+        x = x - np.float32(0.75)                  # a tensor with a negative floor, so that delta matters
+        xd = torch.from_numpy(x).cuda()
+    p2 = B.params(-8, 7, G, iters, args.cands_per_lane)
+    out2 = B.SearchResult(torch.empty(1, dtype=torch.float32, device="cuda"),
+                          torch.empty(1, dtype=torch.int32, device="cuda"),
+                          torch.empty(1, dtype=torch.float64, device="cuda"),
+                          torch.empty((N + 1) // 2, dtype=torch.uint8, device="cuda") if variant == "residual" else None)
+    outo = B.OffsetResult(torch.empty(1, dtype=torch.float32, device="cuda"), out.scale, out.idx, out.sse, packed)
+
     def step():
+        if variant == "offset":
+            B.mmse_scale_search_offset(xd, p, ws, outo)
+            return
         B.mmse_scale_search_activation(xd, p, ws, out)
         B.quantize_pack_int4(xd, out.scale, 0, 15, packed)
+        if variant == "residual":
+            B.activation_residual_quantize(xd, out.scale, 0, 15, p2, ws, out2)
 
     for _ in range(args.warmup):
         step()
@@ -66,16 +82,32 @@ def bench_activation(args, cfg, torch, B) -> int:
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    evals = N * (G + 2 + iters)
+    evals = N * (G + 2 + iters) * (2 if variant == "residual" else 1)
 
     # dominant kernel alone: grid sweep (refine_iters = 0 leaves abs-max, sweep, reduction, argmin)
     p0 = B.params(0, 15, G, 0, args.cands_per_lane)
-    B.mmse_scale_search_activation(xd, p0, ws, out)
+    p20 = B.params(-8, 7, G, 0, args.cands_per_lane)
+    step()
+    s1 = out.scale.clone()
+    outs0 = B.SearchResult(torch.empty(1, dtype=torch.float32, device="cuda"),
+                           torch.empty(1, dtype=torch.int32, device="cuda"),
+                           torch.empty(1, dtype=torch.float64, device="cuda"))
+    outo0 = B.OffsetResult(torch.empty(1, dtype=torch.float32, device="cuda"), outs0.scale, outs0.idx, outs0.sse, None)
+
+    def sweep_only():
+        if variant == "offset":
+            B.mmse_scale_search_offset(xd, p0, ws, outo0)
+        elif variant == "residual":
+            B.activation_residual_quantize(xd, s1, 0, 15, p20, ws, outs0)
+        else:
+            B.mmse_scale_search_activation(xd, p0, ws, outs0)
+
+    sweep_only()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     ev0.record()
     for _ in range(args.steps):
-        B.mmse_scale_search_activation(xd, p0, ws, out)
+        sweep_only()
     ev1.record()
     torch.cuda.synchronize()
     sweep_ms = ev0.elapsed_time(ev1) / args.steps
@@ -91,20 +123,33 @@ def bench_activation(args, cfg, torch, B) -> int:
         step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        o = oracle.can_search(x, 0, 15, G, iters)
-        ref_packed = oracle.can_quantize_pack_int4(x, [o["scale"]], 0, 15)
+        if variant == "offset":
+            o = oracle.can_offset_search(x, 15, G, iters)
+            ref_packed = o["packed"]
+            parity = float(outo.delta[0]) == float(o["delta"])
+        else:
+            o = oracle.can_search(x, 0, 15, G, iters)
+            ref_packed = oracle.can_quantize_pack_int4(x, [o["scale"]], 0, 15)
+            parity = True
+            if variant == "residual":
+                o2 = oracle.can_act_residual_quantize(x, o["scale"], (0, 15), (-8, 7), G, iters)
+                parity = (int(out2.idx[0]) == o2["idx"] and float(out2.scale[0]) == float(o2["scale"])
+                          and abs(float(out2.sse[0]) - o2["sse"]) <= 1e-4 * o2["sse"]
+                          and np.array_equal(out2.packed.cpu().numpy(), o2["packed"]))
         dt = time.perf_counter() - t0
         cpu_baseline = {"value": evals / dt, "unit": "evals/s", "cores": oracle.num_threads(), "kind": "oracle",
                         "sample": f"the full tensor once ({N} elements): search + codes", "seconds": round(dt, 3)}
-        parity = (int(out.idx[0]) == o["idx"] and float(out.scale[0]) == float(o["scale"])
-                  and abs(float(out.sse[0]) - o["sse"]) <= 1e-4 * o["sse"]
-                  and np.array_equal(packed.cpu().numpy(), ref_packed))
+        parity = bool(parity and int(out.idx[0]) == o["idx"] and float(out.scale[0]) == float(o["scale"])
+                      and abs(float(out.sse[0]) - o["sse"]) <= 1e-4 * o["sse"]
+                      and np.array_equal(packed.cpu().numpy(), ref_packed))
     print(json.dumps({
         "metric": METRIC, "value": evals / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] largest activation tensor "
                                f"({cfg.act_shapes[li].name}, batch {cfg.act_batch})",
+                   "variant": {"plain": "Eq. 15", "residual": "Eq. 15 then the second tensor of Eq. 16 (signed)",
+                               "offset": "Eq. 2 with the MMSE scale (tensor shifted by -0.75)"}[variant],
                    "elements": N, "grid_points": G, "refine_iters": iters, "range": "unsigned INT4 (0..15)",
                    "outputs": "scale, argmin index, sse, packed INT4 codes", "evals_per_step": evals},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
@@ -242,6 +287,8 @@ def main() -> int:
                     help="also run plain device copies of this many MiB (for scaling FETCH_SIZE/WRITE_SIZE "
                          "counters under rocprofv3 --pmc); not part of any timed region")
     ap.add_argument("--pair-grid", type=int, default=32, help="G1 = G2 of --part dual-ls")
+    ap.add_argument("--act-variant", choices=("plain", "residual", "offset"), default="plain",
+                    help="--part activation: the per-layer search alone, with the second tensor, or in offset form")
     ap.add_argument("--grid-points", type=int, default=0, help="override G of the configuration")
     ap.add_argument("--refine-iters", type=int, default=-1, help="override the refinement iterations")
     args = ap.parse_args()
