@@ -62,6 +62,8 @@ def _load():
         "def_offset_sse": (f64, [f32p, i64, f64, f64, i32]),
         "can_min": (f32, [f32p, i64]),
         "can_offset_search": (i32, [f32p, i64, i32, i32, i32, f32p, f32p, i32p, f64p, u8p]),
+        "can_alternating_scale": (i32, [f32p, i64, i32, i32, i32, f32p, f64p, i32p]),
+        "can_alternating_scale_kernelwise": (None, [f32p, i64, i64, i32, i32, i32, f32p, f64p, i32p]),
         "oracle_num_threads": (i32, []),
     }
     for name, (res, args) in sig.items():
@@ -323,3 +325,21 @@ def can_offset_search(x, qmax: int, G: int, iters: int):
     rc = _load().can_offset_search(_p(x, C.c_float), x.size, qmax, G, iters, _p(d, C.c_float), _p(a, C.c_float),
                                    _p(idx, C.c_int32), _p(sse, C.c_double), _p(packed, C.c_uint8))
     return {"delta": d[0], "scale": a[0], "idx": int(idx[0]), "sse": float(sse[0]), "packed": packed, "rc": int(rc)}
+
+
+def can_alternating_scale(x, qmin: int, qmax: int, max_iters: int):
+    """Alternating optimisation of Section 3.4's comparison: dict(scale, sse, updates, rc)."""
+    x = _f32(x).ravel()
+    a, e, u = np.zeros(1, np.float32), np.zeros(1, np.float64), np.zeros(1, np.int32)
+    rc = _load().can_alternating_scale(_p(x, C.c_float), x.size, qmin, qmax, max_iters, _p(a, C.c_float),
+                                       _p(e, C.c_double), _p(u, C.c_int32))
+    return {"scale": a[0], "sse": float(e[0]), "updates": int(u[0]), "rc": int(rc)}
+
+
+def can_alternating_scale_kernelwise(w, qmin: int, qmax: int, max_iters: int):
+    w = _f32(w)
+    K, n = w.shape
+    a, e, u = np.zeros(K, np.float32), np.zeros(K, np.float64), np.zeros(K, np.int32)
+    _load().can_alternating_scale_kernelwise(_p(w, C.c_float), K, n, qmin, qmax, max_iters, _p(a, C.c_float),
+                                             _p(e, C.c_double), _p(u, C.c_int32))
+    return a, e, u

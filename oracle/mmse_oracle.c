@@ -660,6 +660,69 @@ int can_offset_search(const float *x, int64_t N, int qmax, int G, int iters,
     return rc;
 }
 
+/* ------------------------------------------------------------------ */
+/* Comparison optimisers of Section 3.4 (Table 2), error only           */
+/* ------------------------------------------------------------------ */
+
+/* Alternating optimisation (the "Altern." column): from the max-abs scale of Section 3.1, repeat
+ *   codes  Q = [T/alpha]_Zp                 (optimal for the scale)
+ *   scale  alpha = sum T_i Q_i / sum Q_i^2   (least squares for the codes)
+ * until the scale repeats or max_iters updates were made.  Canonical arithmetic: per chunk of 64
+ * elements sum T_i*Q_i sequentially in fp64 (each product is exact), chunk sums added pairwise as
+ * everywhere else; sum Q^2 is an integer; alpha = (float)(num/den) with an fp64 division.
+ * Returns the last scale, the canonical f of it, and the number of updates made. */
+int can_alternating_scale(const float *x, int64_t n, int qmin, int qmax, int max_iters,
+                          float *scale, double *sse, int32_t *updates)
+{
+    int64_t m = (n + ORACLE_CHUNK - 1) / ORACLE_CHUNK;
+    double *work = (double *)malloc(sizeof(double) * (size_t)(m > 0 ? m : 1));
+    const float lo = (float)qmin, hi = (float)qmax;
+    float a = can_absmax(x, n);
+    int rc = 0;
+    *updates = 0;
+    if (!(a <= ORACLE_HUGE)) {
+        *scale = NAN; *sse = NAN; rc = -1;
+    } else if (a < ORACLE_TINY) {
+        *scale = 1.0f;
+        *sse = can_sse_work(x, n, 1.0f, qmin, qmax, work);
+    } else {
+        float alpha = a / (float)qmax;
+        for (int it = 0; it < max_iters; ++it) {
+            const float inv = 1.0f / alpha;
+            int64_t den = 0;
+            for (int64_t c = 0; c < m; ++c) {
+                int64_t s0 = c * ORACLE_CHUNK;
+                int64_t len = n - s0 < ORACLE_CHUNK ? n - s0 : ORACLE_CHUNK;
+                double num = 0.0;
+                for (int64_t i = 0; i < len; ++i) {
+                    float q = can_code(x[s0 + i], inv, lo, hi);
+                    num = fma((double)x[s0 + i], (double)q, num);
+                    den += (int64_t)q * (int64_t)q;
+                }
+                work[c] = num;
+            }
+            double num = can_pairwise(work, m);
+            if (den == 0) break;
+            float next = (float)(num / (double)den);
+            if (next == alpha) break;
+            alpha = next;
+            *updates = it + 1;
+        }
+        *scale = alpha;
+        *sse = can_sse_work(x, n, alpha, qmin, qmax, work);
+    }
+    free(work);
+    return rc;
+}
+
+void can_alternating_scale_kernelwise(const float *w, int64_t K, int64_t n, int qmin, int qmax, int max_iters,
+                                      float *scale, double *sse, int32_t *updates)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t k = 0; k < K; ++k)
+        can_alternating_scale(w + k * n, n, qmin, qmax, max_iters, scale + k, sse + k, updates + k);
+}
+
 int oracle_num_threads(void)
 {
     int nthreads = 1;

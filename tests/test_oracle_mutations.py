@@ -67,6 +67,14 @@ MUTATIONS = [
     ("offset: codes of the unshifted tensor", "if (packed) can_quantize_pack_int4(y, 1, N, scale, 0, qmax, packed);",
      "if (packed) can_quantize_pack_int4(x, 1, N, scale, 0, qmax, packed);"),
     ("offset: non-finite input accepted", "*delta = rc == 0 ? d : NAN;", "*delta = d;"),
+    ("comparison: alternating update divides by the sum of |codes|", "den += (int64_t)q * (int64_t)q;", "den += (int64_t)fabsf(q);"),
+    ("comparison: alternating numerator uses the codes twice", "num = fma((double)x[s0 + i], (double)q, num);",
+     "num = fma((double)q, (double)q, num);"),
+    ("comparison: alternating update inverted", "float next = (float)(num / (double)den);", "float next = (float)((double)den / num);"),
+    ("comparison: alternating starts from half the max-abs scale", "float alpha = a / (float)qmax;\n        for (int it = 0; it < max_iters; ++it) {",
+     "float alpha = 0.5f * a / (float)qmax;\n        for (int it = 0; it < max_iters; ++it) {"),
+    ("comparison: alternating stops after one update", "alpha = next;\n            *updates = it + 1;", "alpha = next;\n            *updates = it + 1; break;"),
+    ("comparison: alternating keeps the old scale", "alpha = next;\n            *updates = it + 1;", "*updates = it + 1;"),
     ("tiny tensors not special-cased", "} else if (a < ORACLE_TINY) {\n        *scale = 1.0f; *idx = 0;",
      "} else if (a < 0.0f) {\n        *scale = 1.0f; *idx = 0;"),
     ("dual search: tiny tensors not special-cased", "} else if (a < ORACLE_TINY) {\n        *a1_out = 1.0f;",

@@ -732,6 +732,108 @@ def test_offset_form_degenerate_inputs():
     assert o["rc"] == -1 and np.isnan(o["delta"]) and np.isnan(o["scale"]) and not o["packed"].any()
 
 
+# ------------------------------------------------------------------ comparison optimisers (Section 3.4, Table 2)
+def np_ls_scale(x, alpha, qmin, qmax):
+    """One alternating update in numpy fp64: codes for alpha, then the least-squares scale for those codes."""
+    x = np.asarray(x, np.float64)
+    q = np.clip(np.rint(x * float(np.float32(1.0) / np.float32(alpha))), qmin, qmax)
+    return float(np.sum(x * q) / np.sum(q * q)), q
+
+
+@pytest.mark.parametrize("kind", ["normal", "laplace", "outliers"])
+def test_uniform_mode_is_the_max_abs_quantizer(kind):
+    """One grid point and no refinement is Section 3.1's quantizer without offset."""
+    w = synth.small_weights(6, 300, 12, kind)
+    s, j, e = oracle.can_search_kernelwise(w, *SIGNED, 1, 0)
+    for k in range(6):
+        smax = np.float32(np.abs(w[k]).max()) / np.float32(7)
+        assert s[k] == smax and j[k] == 0
+        assert abs(e[k] - np_def_sse(w[k], smax, *SIGNED)) <= 1e-5 * e[k]
+
+
+def test_golden_mode_searches_the_whole_range():
+    """One grid point plus refinement is a golden-section search over (0, max-abs scale]."""
+    x = synth.small_weights(1, 700, 5, "laplace")[0]
+    smax = np.float32(np.abs(x).max()) / np.float32(7)
+    o = oracle.can_search(x, *SIGNED, 1, 24, want_probes=True)
+    pr = o["probes"]
+    phi = np.float32(0.6180339887)
+    assert abs(pr[0] - smax * (1 - phi)) <= 1e-6 * smax and abs(pr[1] - smax * phi) <= 1e-6 * smax
+    assert np.all(pr > 0) and np.all(pr <= smax) and len(pr) == 26
+    assert o["sse"] <= oracle.can_sse(x, smax, *SIGNED)
+    # 24 iterations shrink the bracket to phi^24 of the range: the result is a local minimum at that resolution
+    width = float(smax) * float(phi) ** 24
+    for d in (-4 * width, 4 * width):
+        assert o["sse"] <= oracle.can_sse(x, np.float32(o["scale"] + d), *SIGNED) * (1 + 1e-6)
+
+
+@pytest.mark.parametrize("q", [SIGNED, UNSIGNED, (-1, 1)])
+def test_alternating_first_update_is_the_least_squares_scale(q):
+    x = synth.small_weights(1, 500, 21, "normal")[0]
+    if q[0] == 0:
+        x = np.abs(x)
+    smax = np.float32(np.abs(x).max()) / np.float32(q[1])
+    o = oracle.can_alternating_scale(x, *q, 1)
+    ls, codes = np_ls_scale(x, smax, *q)
+    assert o["updates"] == 1 and abs(float(o["scale"]) - ls) <= 1e-7 * ls
+    # least squares: no other scale is better for these codes
+    for f in (0.99, 1.01):
+        assert oracle.def_sse_codes(x, codes.astype(np.int32), ls) < oracle.def_sse_codes(x, codes.astype(np.int32), ls * f)
+    if q == (-1, 1):
+        # ternary closed form: the mean magnitude of the elements beyond half the scale
+        big = np.abs(x.astype(np.float64)) * float(np.float32(1) / smax) > 0.5
+        assert abs(ls - np.abs(x.astype(np.float64))[big].mean()) <= 1e-12 * ls
+
+
+def test_alternating_follows_the_update_rule_and_descends():
+    x = synth.small_weights(1, 800, 33, "student")[0]
+    alpha = np.float32(np.abs(x).max()) / np.float32(7)
+    prev = oracle.can_sse(x, alpha, *SIGNED)
+    for it in range(1, 12):
+        o = oracle.can_alternating_scale(x, *SIGNED, it)
+        ls, _ = np_ls_scale(x, alpha, *SIGNED)
+        if np.float32(ls) == alpha:
+            assert o["updates"] < it and o["scale"] == alpha
+            break
+        assert o["updates"] == it and abs(float(o["scale"]) - ls) <= 2e-7 * ls
+        assert o["sse"] <= prev * (1 + 1e-6)                    # each half-step is optimal for its variable
+        assert abs(o["sse"] - np_def_sse(x, o["scale"], *SIGNED)) <= 1e-5 * o["sse"]
+        alpha, prev = o["scale"], o["sse"]
+
+
+def test_alternating_closed_form_and_degenerate_inputs():
+    x = (np.float32(0.25) * np.random.default_rng(3).integers(-7, 8, 400)).astype(np.float32)
+    x[:2] = (-1.75, 1.75)
+    o = oracle.can_alternating_scale(x, *SIGNED, 10)
+    assert (o["scale"], o["sse"], o["updates"], o["rc"]) == (0.25, 0.0, 0, 0)        # the max-abs scale is already exact
+    y = x.copy()
+    y[0] = 4.0                                                 # one outlier: max-abs scale 4/7, optimum back at 0.25-ish
+    o = oracle.can_alternating_scale(y, *SIGNED, 50)
+    assert o["updates"] >= 1 and o["sse"] < oracle.can_sse(y, np.float32(4.0) / np.float32(7), *SIGNED)
+    z = np.zeros(100, np.float32)
+    o = oracle.can_alternating_scale(z, *SIGNED, 10)
+    assert (o["scale"], o["sse"], o["updates"], o["rc"]) == (1.0, 0.0, 0, 0)
+    z[5] = np.inf
+    o = oracle.can_alternating_scale(z, *SIGNED, 10)
+    assert o["rc"] == -1 and np.isnan(o["scale"]) and np.isnan(o["sse"])
+
+
+def test_comparison_modes_order_as_in_table_2():
+    """Uniform is the start of both iterative methods, so neither can be worse than it; the grid search with
+    refinement is the best of the four on aggregate (the paper's accuracy ordering, here in MSE)."""
+    for kind in ("normal", "laplace", "student"):
+        w = synth.small_weights(48, 576, 17, kind)
+        e_uni = oracle.can_search_kernelwise(w, *SIGNED, 1, 0)[2]
+        e_gold = oracle.can_search_kernelwise(w, *SIGNED, 1, 20)[2]
+        e_omse = oracle.can_search_kernelwise(w, *SIGNED, 256, 20)[2]
+        a_alt, e_alt, _ = oracle.can_alternating_scale_kernelwise(w, *SIGNED, 50)
+        assert np.all(e_alt <= e_uni * (1 + 1e-6)) and np.all(e_gold <= e_uni) and np.all(e_omse <= e_uni)
+        assert e_omse.sum() < e_gold.sum() < e_uni.sum() and e_omse.sum() < e_alt.sum() < e_uni.sum()
+        for k in (0, 47):
+            one = oracle.can_alternating_scale(w[k], *SIGNED, 50)
+            assert (one["scale"], one["sse"]) == (a_alt[k], e_alt[k])
+
+
 # ------------------------------------------------------------------ workloads
 def test_workload_shapes_match_architectures():
     c = [synth.config(i) for i in range(1, 6)]
