@@ -271,6 +271,58 @@ def bench_dual_linesearch(args, cfg, torch, B) -> int:
     return 0
 
 
+def bench_compare(args, cfg, torch, B) -> int:
+    """The four optimisers of Section 3.4 (Table 2) on every weight tensor: total squared error and time."""
+    host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]
+    dev_w = [torch.from_numpy(w).cuda() for w in host_w]
+    G = args.grid_points if args.grid_points > 0 else cfg.grid_points
+    iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
+    energy = sum(float(np.sum(w.astype(np.float64) ** 2)) for w in host_w)
+    modes = {"uniform": (1, 0), "golden": (1, iters), "omse": (G, iters)}
+    rows = {}
+
+    def timed(fn):
+        for _ in range(max(1, args.warmup // 5)):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(1, args.steps // 5)):
+            out = fn()
+        torch.cuda.synchronize()
+        return out, (time.perf_counter() - t0) * 1e3 / max(1, args.steps // 5)
+
+    for name, (g, it) in modes.items():
+        plan = B.BatchedPlan(dev_w, B.params(-8, 7, g, it), want_packed=False)
+        res, ms = timed(plan.run)
+        rows[name] = {"sse": sum(float(r.sse.sum().item()) for r in res), "ms": ms}
+    res, ms = timed(lambda: [B.mmse_scale_alternating_kernelwise(d, -8, 7, 50) for d in dev_w])
+    rows["alternating"] = {"sse": sum(float(r[1].sum().item()) for r in res), "ms": ms,
+                           "mean_updates": float(np.mean(np.concatenate([r[2].cpu().numpy() for r in res])))}
+    for r in rows.values():
+        r["normalized_mse"] = r["sse"] / energy
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        ok = True
+        for w, r in zip(host_w, res):
+            sel = np.unique(np.linspace(0, w.shape[0] - 1, 16).astype(int))
+            rs, re, ru = oracle.can_alternating_scale_kernelwise(np.ascontiguousarray(w[sel]), -8, 7, 50)
+            ok = ok and np.array_equal(r[0].cpu().numpy()[sel], rs) and np.array_equal(r[2].cpu().numpy()[sel], ru)
+        cpu_baseline = {"kind": "oracle", "sample": "16 kernels of every tensor, alternating mode",
+                        "seconds": round(time.perf_counter() - t0, 3), "cores": oracle.num_threads(), "value": None,
+                        "unit": "evals/s"}
+        parity = bool(ok)
+    print(json.dumps({
+        "metric": METRIC, "value": None, "unit": "evals/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rows["omse"]["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] weights under the four optimisers of Section 3.4",
+                   "grid_points": G, "refine_iters": iters, "alternating_max_updates": 50},
+        "modes": rows, "roofline": None, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -280,7 +332,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="BASELINE.json configuration (weights part)")
     ap.add_argument("--cands-per-lane", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--part", choices=("weights", "activation", "dual", "dual-ls"), default="weights",
+    ap.add_argument("--part", choices=("weights", "activation", "dual", "dual-ls", "compare"), default="weights",
                     help="weights: the whole-net kernel-wise path (default); activation: the largest "
                          "calibration tensor of the configuration through the per-layer path")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -321,6 +373,8 @@ def main() -> int:
         return bench_dual(args, cfg, torch, B)
     if args.part == "dual-ls":
         return bench_dual_linesearch(args, cfg, torch, B)
+    if args.part == "compare":
+        return bench_compare(args, cfg, torch, B)
     G = args.grid_points if args.grid_points > 0 else cfg.grid_points
     iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
     host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]

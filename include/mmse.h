@@ -191,6 +191,17 @@ int dual_line_search(const float *w_dev, int64_t K, int64_t n, int32_t qmin, int
                      uint8_t *packed1_dev, uint8_t *packed2_dev, double *grid_dev,
                      void *ws_dev, size_t ws_bytes, void *stream);
 
+/* Comparison optimisers of Section 3.4 (Table 2), error only.  Two of them are grid modes of the search
+ * entry points above: grid_points = 1, refine_iters = 0 is the max-abs "Uniform" quantizer of Section 3.1;
+ * grid_points = 1, refine_iters = N is a golden-section search over (0, max-abs scale] ("Golden").  The third,
+ * alternating optimisation ("Altern."), is this entry point: for every row of a [K][n] tensor start from the
+ * max-abs scale and repeat  Q = [w/alpha]_Zp,  alpha = sum_i w_i*Q_i / sum_i Q_i^2  until the scale repeats
+ * or max_iters (0..1000) updates were made.  scale_dev[k]: the last scale; sse_dev[k]: the error at it;
+ * updates_dev[k]: updates made.  All-zero and rejected rows as in the search entry points.  No workspace. */
+int mmse_scale_alternating_kernelwise(const float *w_dev, int64_t K, int64_t n, int32_t qmin, int32_t qmax,
+                                      int32_t max_iters, float *scale_dev, double *sse_dev, int32_t *updates_dev,
+                                      void *stream);
+
 /* Whole network in a handful of launches: `count` weight tensors described in HOST
  * memory (the descriptors are consumed before the call returns).  Semantics per
  * tensor are those of mmse_scale_search_kernelwise / residual_quantize /

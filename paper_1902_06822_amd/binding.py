@@ -23,7 +23,7 @@ EXPORTS = (
     "mmse_grid_sse_kernelwise", "mmse_workspace_bytes_dual", "dual_quantize_alternating",
     "mmse_workspace_bytes_dual_batched", "dual_quantize_alternating_batched",
     "mmse_workspace_bytes_dual_linesearch", "dual_line_search",
-    "activation_residual_quantize", "mmse_scale_search_offset",
+    "activation_residual_quantize", "mmse_scale_search_offset", "mmse_scale_alternating_kernelwise",
     "mmse_status_string",
 )
 
@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
     lib.activation_residual_quantize.argtypes = [vp, i64, vp, i32, i32, C.POINTER(MmseParams), vp, vp, vp, vp, vp,
                                                  C.c_size_t, vp]
     lib.mmse_scale_search_offset.argtypes = [vp, i64, C.POINTER(MmseParams), vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.mmse_scale_alternating_kernelwise.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -422,3 +423,16 @@ def mmse_scale_search_offset(x: torch.Tensor, p: MmseParams, ws: Optional[torch.
         x.data_ptr(), N, C.byref(p), out.delta.data_ptr(), out.scale.data_ptr(), out.idx.data_ptr(),
         out.sse.data_ptr(), _ptr(out.packed), ws.data_ptr(), ws.numel(), _stream()), "mmse_scale_search_offset")
     return out
+
+
+def mmse_scale_alternating_kernelwise(w: torch.Tensor, qmin: int, qmax: int, max_iters: int):
+    """Alternating optimisation of Section 3.4's comparison: (scale [K], sse [K], updates [K])."""
+    _dev(w, torch.float32)
+    K, n = w.shape
+    scale = torch.empty(K, dtype=torch.float32, device=w.device)
+    sse = torch.empty(K, dtype=torch.float64, device=w.device)
+    upd = torch.empty(K, dtype=torch.int32, device=w.device)
+    _check(load_library().mmse_scale_alternating_kernelwise(
+        w.data_ptr(), K, n, qmin, qmax, max_iters, scale.data_ptr(), sse.data_ptr(), upd.data_ptr(), _stream()),
+        "mmse_scale_alternating_kernelwise")
+    return scale, sse, upd

@@ -109,6 +109,10 @@ def test_entry_points_validate_before_enqueue(B):
     assert lib.mmse_scale_search_offset(None, 64, C.byref(pu), a, a, a, a, a, a, 1 << 20, None) == -1
     assert lib.mmse_scale_search_offset(a, 64, C.byref(pu), a + 2, a, a, a, a, a, 1 << 20, None) == -6
     assert lib.mmse_scale_search_offset(a, 64, C.byref(pu), a, a, a, a, a, None, 0, None) == -4
+    assert lib.mmse_scale_alternating_kernelwise(a, 4, 4, -8, 7, 10, None, a, a, None) == -1
+    assert lib.mmse_scale_alternating_kernelwise(a, 4, 65537, -8, 7, 10, a, a, a, None) == -2
+    assert lib.mmse_scale_alternating_kernelwise(a, 4, 4, -8, 7, 1001, a, a, a, None) == -3
+    assert lib.mmse_scale_alternating_kernelwise(a, 4, 4, -8, 7, 10, a, a + 4, a, None) == -6
     # sizes
     assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
     assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2
