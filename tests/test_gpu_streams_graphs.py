@@ -116,3 +116,56 @@ def test_graph_capture_and_replay_of_the_activation_path(B):
         torch.cuda.synchronize()
         assert (out.scale.item(), out.idx.item(), out.sse.item()) == ref[:3]
         np.testing.assert_array_equal(packed.cpu().numpy(), ref[3])
+
+
+def test_graph_capture_and_replay_of_the_later_entry_points(B):
+    """Dual line search, the activation variants and the alternating comparison mode under capture: every
+    replay, with the outputs and the workspaces scribbled over in between, gives the eager result."""
+    import torch
+    say("graph replay: dual line search, activation variants, alternating mode")
+    w = torch.from_numpy(synth.small_weights(70, 147, 5, "laplace")).cuda()
+    x = torch.from_numpy(synth.acts_relu_normal(123457, 98) - np.float32(0.5)).cuda()
+    pu, ps = B.params(*UNSIGNED, 64, 10), B.params(*SIGNED, 64, 10)
+    ws_d = B.alloc_workspace(B.mmse_workspace_bytes_dual_linesearch(70, 147, 16, 20))
+    ws_a = B.alloc_workspace(B.mmse_workspace_bytes_activation(x.numel(), pu))
+    ws_b = B.alloc_workspace(B.mmse_workspace_bytes_activation(x.numel(), pu))
+    ws_c = B.alloc_workspace(B.mmse_workspace_bytes_activation(x.numel(), pu))
+    d = B.dual_line_search(w, *SIGNED, 16, 20, ws=ws_d)
+    first = B.mmse_scale_search_activation(x, pu, ws_a)
+    second = B.activation_residual_quantize(x, first.scale, *UNSIGNED, ps, ws_b)
+    off = B.mmse_scale_search_offset(x, pu, ws_c)
+    torch.cuda.synchronize()
+    alt = B.mmse_scale_alternating_kernelwise(w, *SIGNED, 20)
+    torch.cuda.synchronize()
+    outs = [d.scale1, d.scale2, d.idx1, d.idx2, d.sse, d.packed1, d.packed2, first.scale, second.scale, second.idx,
+            second.sse, second.packed, off.delta, off.scale, off.idx, off.sse, off.packed]
+    ref = [t.cpu().numpy().copy() for t in outs]
+    ref_alt = [t.cpu().numpy().copy() for t in alt]
+
+    def work():
+        B.dual_line_search(w, *SIGNED, 16, 20, ws=ws_d, out=d)
+        B.mmse_scale_search_activation(x, pu, ws_a, first)
+        B.activation_residual_quantize(x, first.scale, *UNSIGNED, ps, ws_b, second)
+        B.mmse_scale_search_offset(x, pu, ws_c, off)
+
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        work()
+    s.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        work()
+    for rep in range(3):
+        for t in outs:
+            t.fill_(3)
+        for t in (ws_d, ws_a, ws_b, ws_c):
+            t.fill_(0xCD)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for t, r in zip(outs, ref):
+            np.testing.assert_array_equal(t.cpu().numpy(), r)
+        again = B.mmse_scale_alternating_kernelwise(w, *SIGNED, 20)
+        torch.cuda.synchronize()
+        for t, r in zip(again, ref_alt):
+            np.testing.assert_array_equal(t.cpu().numpy(), r)
