@@ -397,6 +397,17 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = evals_per_step / (ms_per_step * 1e-3)
 
+    # ---- the same step, one at a time between HIP events on the launch stream: median and minimum
+    nrep = max(20, min(args.steps, 100))
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nrep)]
+    for a, b in evs:
+        a.record()
+        plan.run()
+        b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in evs)
+    step_stats = {"runs": nrep, "median_ms": per_step[nrep // 2], "min_ms": per_step[0]}
+
     # ---- dominant kernel alone: grid sweep + argmin (refine_iters = 0, no packing => one kernel per launch)
     p_sweep = B.params(-8, 7, G, 0, args.cands_per_lane)
     sweep_plan = B.BatchedPlan(dev_w, p_sweep, want_packed=False)
@@ -481,6 +492,7 @@ def main() -> int:
             "range": "signed INT4 (-8..7)", "outputs": "scale, argmin index, sse, packed INT4 codes",
             "evals_per_step": evals_per_step, "cands_per_lane": args.cands_per_lane,
         },
+        "step_ms_by_events": step_stats,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "matches_oracle": parity,
