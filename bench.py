@@ -323,6 +323,115 @@ def bench_compare(args, cfg, torch, B) -> int:
     return 0
 
 
+def bench_whole(args, cfg, torch, B) -> int:
+    """Everything the configuration names, first enqueue to last kernel: weights (search + codes), the second
+    tensor on the selected layers, and search + codes of every layer's calibration activations."""
+    from paper_1902_06822_amd import select
+    G = args.grid_points if args.grid_points > 0 else cfg.grid_points
+    iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
+    t_gen = time.perf_counter()
+    host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]
+    dev_w = [torch.from_numpy(w).cuda() for w in host_w]
+    energy = [float(np.sum(w.astype(np.float64) ** 2)) for w in host_w]        # constants of the network
+    dev_x = []
+    for i in range(len(cfg.act_shapes)):
+        dev_x.append(torch.from_numpy(cfg.act_tensor(i)).cuda())
+    print(f"bench.py: inputs generated in {time.perf_counter() - t_gen:.1f} s", file=sys.stderr, flush=True)
+    pw = B.params(-8, 7, G, iters, args.cands_per_lane)
+    pa = B.params(0, 15, G, iters, args.cands_per_lane)
+    plan_w = B.BatchedPlan(dev_w, pw, want_packed=True)
+    nlayers = len(dev_w)
+    if cfg.residual == "all":
+        fixed_key = list(range(nlayers))
+    else:
+        fixed_key = None
+    nkey = nlayers if cfg.residual == "all" else (max(1, round(0.10 * nlayers)) if cfg.residual == "top10pct" else 0)
+    # residual plans are built per selection; buffers for the largest possible selection are kept so that the
+    # timed region allocates nothing: one plan per layer, run individually
+    res_plans = [B.BatchedPlan([dev_w[i]], pw, want_packed=True, scale1=[plan_w.results[i].scale]) for i in range(nlayers)] \
+        if nkey else []
+    res_all = B.BatchedPlan(dev_w, pw, want_packed=True, scale1=[r.scale for r in plan_w.results]) if fixed_key else None
+    nstreams = max(1, args.streams)
+    streams = [torch.cuda.Stream() for _ in range(nstreams)]
+    act_ws = [B.alloc_workspace(B.mmse_workspace_bytes_activation(x.numel(), pa)) for x in dev_x]
+    act_out = [B.SearchResult(torch.empty(1, dtype=torch.float32, device="cuda"),
+                              torch.empty(1, dtype=torch.int32, device="cuda"),
+                              torch.empty(1, dtype=torch.float64, device="cuda"),
+                              torch.empty((x.numel() + 1) // 2, dtype=torch.uint8, device="cuda")) for x in dev_x]
+    order = sorted(range(len(dev_x)), key=lambda i: -dev_x[i].numel())            # large tensors first
+    key_used = []
+
+    def step():
+        main = torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(main)
+        # activations on side streams, largest first, while the weight path runs on the main stream
+        for n_, i in enumerate(order):
+            st = streams[n_ % nstreams]
+            if n_ < nstreams:
+                st.wait_event(start)
+            with torch.cuda.stream(st):
+                B.mmse_scale_search_activation(dev_x[i], pa, act_ws[i], act_out[i])
+                B.quantize_pack_int4(dev_x[i], act_out[i].scale, 0, 15, act_out[i].packed)
+        res = plan_w.run()
+        if res_all is not None:
+            res_all.run()
+        elif nkey:
+            sums = torch.stack([r.sse.sum() for r in res]).cpu().numpy()          # device-to-host: the selection is host logic
+            key = select.select_top_fraction(select.normalized_mse(list(sums), energy), 0.10)
+            key_used[:] = key
+            for i in key:
+                res_plans[i].run()
+        for st in streams:
+            main.wait_stream(st)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    P = G + 2 + iters
+    w_elems = sum(w.size for w in host_w)
+    key_elems = w_elems if fixed_key else sum(host_w[i].size for i in key_used)
+    a_elems = sum(x.numel() for x in dev_x)
+    evals = (w_elems + key_elems + a_elems) * P
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        small = sorted(range(len(dev_x)), key=lambda i: dev_x[i].numel())[:3]
+        ok, sample = True, 0
+        for i in small:
+            x = cfg.act_tensor(i)
+            o = oracle.can_search(x, 0, 15, G, iters)
+            ok = ok and int(act_out[i].idx[0]) == o["idx"] and float(act_out[i].scale[0]) == float(o["scale"]) \
+                and np.array_equal(act_out[i].packed.cpu().numpy(), oracle.can_quantize_pack_int4(x, [o["scale"]], 0, 15))
+            sample += x.size * P
+        for i in (0, nlayers - 1):
+            sref, jref, eref = oracle.can_search_kernelwise(host_w[i], -8, 7, G, iters)
+            ok = ok and np.array_equal(plan_w.results[i].scale.cpu().numpy(), sref)
+            sample += host_w[i].size * P
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": sample / dt, "unit": "evals/s", "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": "the three smallest activation tensors and the first and last weight tensor",
+                        "seconds": round(dt, 3)}
+        parity = bool(ok)
+    print(json.dumps({
+        "metric": METRIC, "value": evals / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] whole network: weights, second tensor "
+                               f"({cfg.residual}), all calibration activations",
+                   "weight_tensors": nlayers, "weights": w_elems, "second_tensor_layers": (nlayers if fixed_key else key_used),
+                   "activation_tensors": len(dev_x), "activation_elements": a_elems, "grid_points": G,
+                   "refine_iters": iters, "streams_for_activations": nstreams, "evals_per_step": evals},
+        "roofline": None, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -332,13 +441,14 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="BASELINE.json configuration (weights part)")
     ap.add_argument("--cands-per-lane", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--part", choices=("weights", "activation", "dual", "dual-ls", "compare"), default="weights",
+    ap.add_argument("--part", choices=("weights", "activation", "dual", "dual-ls", "compare", "whole"), default="weights",
                     help="weights: the whole-net kernel-wise path (default); activation: the largest "
                          "calibration tensor of the configuration through the per-layer path")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run plain device copies of this many MiB (for scaling FETCH_SIZE/WRITE_SIZE "
                          "counters under rocprofv3 --pmc); not part of any timed region")
     ap.add_argument("--pair-grid", type=int, default=32, help="G1 = G2 of --part dual-ls")
+    ap.add_argument("--streams", type=int, default=4, help="--part whole: side streams the activation tensors are spread over")
     ap.add_argument("--act-variant", choices=("plain", "residual", "offset"), default="plain",
                     help="--part activation: the per-layer search alone, with the second tensor, or in offset form")
     ap.add_argument("--grid-points", type=int, default=0, help="override G of the configuration")
@@ -375,6 +485,8 @@ def main() -> int:
         return bench_dual_linesearch(args, cfg, torch, B)
     if args.part == "compare":
         return bench_compare(args, cfg, torch, B)
+    if args.part == "whole":
+        return bench_whole(args, cfg, torch, B)
     G = args.grid_points if args.grid_points > 0 else cfg.grid_points
     iters = args.refine_iters if args.refine_iters >= 0 else cfg.refine_iters
     host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]

@@ -51,6 +51,7 @@ typedef enum mmse_status_t {
 #define MMSE_MAX_GRID_POINTS 2048        /* G                                           */
 #define MMSE_MAX_REFINE_ITERS 64
 #define MMSE_MAX_TENSOR_ELEMS 2147483647 /* K*n and N                                   */
+#define MMSE_MAX_BATCH_TENSORS 1024      /* activation tensors of one batched call      */
 
 /* Search parameters.
  *   qmin,qmax     integer range Z_p of Section 3.1: -8,7 (signed INT4) or 0,15
@@ -208,6 +209,27 @@ int mmse_scale_alternating_kernelwise(const float *w_dev, int64_t K, int64_t n, 
  * quantize_pack_int4.  Workspace: mmse_workspace_bytes_kernelwise(sum K, ...). */
 int mmse_scale_search_batched(const mmse_tensor_desc_t *descs_host, int32_t count,
                               const mmse_params_t *p, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* One activation tensor of a batched call; outputs as in mmse_scale_search_activation (one element each),
+ * packed_dev (ceil(N/2) bytes, layout of quantize_pack_int4) optional. */
+typedef struct mmse_act_desc_t {
+    const float *x_dev;        /* [N]                                      */
+    int64_t N;
+    float *scale_dev;          /* [1]                                      */
+    int32_t *idx_dev;          /* [1]                                      */
+    double *sse_dev;           /* [1]                                      */
+    uint8_t *packed_dev;       /* ceil(N/2) bytes or NULL                  */
+} mmse_act_desc_t;
+
+/* The calibration activations of a whole network (Section 3.7, Eq. 15: one scale per layer input) in one set
+ * of launches instead of one per tensor: `count` tensors (1..MMSE_MAX_BATCH_TENSORS) described in HOST memory
+ * (consumed before the call returns), every tensor searched exactly as by mmse_scale_search_activation, with
+ * the same results; a per-layer search is some thirty dependent launches, most of them tiny, so for a
+ * network of many layers sharing them is what keeps the GPU busy.  N_host: the `count` element counts. */
+int mmse_workspace_bytes_activation_batched(const int64_t *N_host, int32_t count, const mmse_params_t *p,
+                                            size_t *bytes_out);
+int mmse_scale_search_activation_batched(const mmse_act_desc_t *descs_host, int32_t count, const mmse_params_t *p,
+                                         void *ws_dev, size_t ws_bytes, void *stream);
 
 /* The grid evaluation alone (the f(alpha_j) of Eq. 8 for every candidate):
  * absmax_dev[k] = max_i |w_ki|, grid_sse_dev[k*G + j] = f_k(alpha_kj).  Used to

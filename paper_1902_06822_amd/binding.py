@@ -24,6 +24,7 @@ EXPORTS = (
     "mmse_workspace_bytes_dual_batched", "dual_quantize_alternating_batched",
     "mmse_workspace_bytes_dual_linesearch", "dual_line_search",
     "activation_residual_quantize", "mmse_scale_search_offset", "mmse_scale_alternating_kernelwise",
+    "mmse_workspace_bytes_activation_batched", "mmse_scale_search_activation_batched",
     "mmse_status_string",
 )
 
@@ -36,6 +37,11 @@ class MmseParams(C.Structure):
 class MmseTensorDesc(C.Structure):
     _fields_ = [("w_dev", C.c_void_p), ("K", C.c_int64), ("n", C.c_int64),
                 ("scale1_dev", C.c_void_p), ("scale_dev", C.c_void_p), ("idx_dev", C.c_void_p),
+                ("sse_dev", C.c_void_p), ("packed_dev", C.c_void_p)]
+
+
+class MmseActDesc(C.Structure):
+    _fields_ = [("x_dev", C.c_void_p), ("N", C.c_int64), ("scale_dev", C.c_void_p), ("idx_dev", C.c_void_p),
                 ("sse_dev", C.c_void_p), ("packed_dev", C.c_void_p)]
 
 
@@ -81,6 +87,9 @@ def load_library() -> C.CDLL:
                                                  C.c_size_t, vp]
     lib.mmse_scale_search_offset.argtypes = [vp, i64, C.POINTER(MmseParams), vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.mmse_scale_alternating_kernelwise.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    lib.mmse_workspace_bytes_activation_batched.argtypes = [C.POINTER(C.c_int64), i32, C.POINTER(MmseParams), szp]
+    lib.mmse_scale_search_activation_batched.argtypes = [C.POINTER(MmseActDesc), i32, C.POINTER(MmseParams), vp,
+                                                         C.c_size_t, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -436,3 +445,39 @@ def mmse_scale_alternating_kernelwise(w: torch.Tensor, qmin: int, qmax: int, max
         w.data_ptr(), K, n, qmin, qmax, max_iters, scale.data_ptr(), sse.data_ptr(), upd.data_ptr(), _stream()),
         "mmse_scale_alternating_kernelwise")
     return scale, sse, upd
+
+
+class ActBatchedPlan:
+    """Host-side descriptor table for ``mmse_scale_search_activation_batched`` (buffers allocated once)."""
+
+    def __init__(self, tensors: Sequence[torch.Tensor], p: MmseParams, want_packed: bool = True):
+        self.p = p
+        self.tensors = list(tensors)
+        self.results: List[SearchResult] = []
+        descs = (MmseActDesc * len(self.tensors))()
+        sizes = (C.c_int64 * len(self.tensors))()
+        for i, x in enumerate(self.tensors):
+            _dev(x, torch.float32)
+            N = x.numel()
+            r = _outputs(1, x.device)
+            if want_packed:
+                r.packed = torch.empty((N + 1) // 2, dtype=torch.uint8, device=x.device)
+            self.results.append(r)
+            descs[i] = MmseActDesc(x.data_ptr(), N, r.scale.data_ptr(), r.idx.data_ptr(), r.sse.data_ptr(), _ptr(r.packed))
+            sizes[i] = N
+        self.descs = descs
+        need = C.c_size_t(0)
+        _check(load_library().mmse_workspace_bytes_activation_batched(sizes, len(self.tensors), C.byref(p), C.byref(need)),
+               "mmse_workspace_bytes_activation_batched")
+        self.ws = alloc_workspace(need.value, self.tensors[0].device)
+
+    def run(self) -> List[SearchResult]:
+        _check(load_library().mmse_scale_search_activation_batched(self.descs, len(self.tensors), C.byref(self.p),
+                                                                   self.ws.data_ptr(), self.ws.numel(), _stream()),
+               "mmse_scale_search_activation_batched")
+        return self.results
+
+
+def mmse_scale_search_activation_batched(tensors: Sequence[torch.Tensor], p: MmseParams,
+                                         want_packed: bool = True) -> List[SearchResult]:
+    return ActBatchedPlan(tensors, p, want_packed).run()

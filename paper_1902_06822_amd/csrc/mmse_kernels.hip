@@ -1272,9 +1272,61 @@ __device__ __forceinline__ float order_unkey(unsigned k)
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-__global__ void k_act_init(ActState* S)
+// Several activation tensors searched by the same launches: the 4096-element blocks of all tensors
+// are numbered consecutively (start[t] = first block of tensor t); every tensor has its own state.
+constexpr int kMaxActBatch = 64;
+struct ActBatch {
+    const float* x[kMaxActBatch];
+    long long N[kMaxActBatch];
+    int start[kMaxActBatch + 1];
+    int count;
+    ActState* S;                 // [count]
+};
+struct ActOut {
+    float* scale[kMaxActBatch];
+    int32_t* idx[kMaxActBatch];
+    double* sse[kMaxActBatch];
+    uint8_t* packed[kMaxActBatch];
+};
+
+// tensor that owns block b: the largest t with start[t] <= b
+__device__ __forceinline__ int act_find(const ActBatch& B, int b)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
+    int lo = 0, hi = B.count - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (B.start[mid] <= b) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// rows a tensor of nb blocks has after l tree stages of 64
+__host__ __device__ inline int act_rows(int nb, int l)
+{
+    for (int i = 0; i < l; ++i) nb = (nb + 63) / 64;
+    return nb;
+}
+
+// At tree level l the rows of all tensors are again stored one tensor after the other.  Finds the
+// tensor that owns row r of that level; returns its first row there (first) and at the level below (below).
+__device__ __forceinline__ int act_find_level(const ActBatch& B, int l, int r, int& first, int& below)
+{
+    int acc = 0, accb = 0, t = 0;
+    for (; t < B.count; ++t) {
+        const int nb = B.start[t + 1] - B.start[t];
+        const int rows = act_rows(nb, l);
+        if (r < acc + rows || t == B.count - 1) break;
+        acc += rows;
+        accb += act_rows(nb, l - 1);
+    }
+    first = acc; below = accb;
+    return t;
+}
+
+__global__ void k_act_init(ActState* Sall, int count)
+{
+    if (blockIdx.x == 0 && (int)threadIdx.x < count) {
+        ActState* S = Sall + threadIdx.x;
         S->absmax_bits = 0; S->status = 0; S->j = 0; S->it = 0; S->done = 1;
         S->have_c = S->have_d = 0; S->nprobe = 0; S->absmax = 0.0f;
         S->lo_a = S->hi_a = S->pc = S->pd = S->best_a = 1.0f;
@@ -1371,9 +1423,12 @@ __device__ void act_advance(ActState* S, const double* vals, int iters)
 // MODE 0: max |x| (integer max of the bit patterns); 1: max |residual of the first tensor|;
 // 2: min and max of x as order-preserving keys (offset form).
 template <int U, int MODE>
-__global__ void __launch_bounds__(256) k_act_absmax(const float* __restrict__ x, long long N, ActState* S,
-                                                    const ActPre pre)
+__global__ void __launch_bounds__(256) k_act_absmax(const ActBatch B, const ActPre pre)
 {
+    const float* __restrict__ x = B.x[blockIdx.y];
+    const long long N = B.N[blockIdx.y];
+    ActState* S = B.S + blockIdx.y;
+    if ((long long)blockIdx.x * blockDim.x * 4 * U >= N) return;       // nothing of this tensor for this workgroup
     __shared__ unsigned s_amax[4];
     __shared__ unsigned s_amin[4];
     unsigned amax = 0, amin = 0xffffffffu;
@@ -1441,17 +1496,20 @@ __global__ void k_act_offset_setup(ActState* S, float* delta_out)
 
 // Grid sweep of one 4096-element block per workgroup; waves split the candidates.
 template <int C>
-__global__ void __launch_bounds__(512) k_act_sweep(const float* __restrict__ x, long long N, int G, int qmax,
-                                                    float lo, float hi, const ActState* S, double* part0,
-                                                    const ActPre pre)
+__global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int qmax,
+                                                    float lo, float hi, double* part0, const ActPre pre)
 {
     __shared__ float4 slice4[kBlockElems / 4];
     float* slice = reinterpret_cast<float*>(slice4);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const int t = act_find(B, blockIdx.x);
+    const float* __restrict__ x = B.x[t];
+    const long long N = B.N[t];
+    const ActState* S = B.S + t;
     const float a = __uint_as_float(S->absmax_bits);
     if (!(a <= kHuge)) return;                // rejected: k_act_argmin reports it
     const bool tiny = a < kTiny;
-    const long long base = (long long)blockIdx.x * kBlockElems;
+    const long long base = (long long)(blockIdx.x - B.start[t]) * kBlockElems;
     const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
     const int npad = (len + kChunk - 1) & ~(kChunk - 1);
     const ActPreV V = act_pre_load(pre);
@@ -1485,12 +1543,17 @@ __global__ void __launch_bounds__(512) k_act_sweep(const float* __restrict__ x, 
 
 // One tree stage over blocks: out[g][j] = pairwise sum of in[64g .. 64g+63][j].
 // When a stage leaves a single row and fin != nullptr the caller continues with it.
-__global__ void __launch_bounds__(256) k_act_reduce64(const double* __restrict__ in, int rows, int G,
+// Output row blockIdx.y of level `level` belongs to one tensor; its inputs are that tensor's rows of level - 1.
+__global__ void __launch_bounds__(256) k_act_reduce64(const ActBatch B, int level, const double* __restrict__ in, int G,
                                                       double* __restrict__ out)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    const int g = blockIdx.y;
+    int first, below;
+    const int t = act_find_level(B, level, blockIdx.y, first, below);
+    const int g = blockIdx.y - first;                                   // group of 64 input rows inside the tensor
+    const int rows = act_rows(B.start[t + 1] - B.start[t], level - 1);
     if (j >= G) return;
+    in += (size_t)below * G;
     double v[64];
 #pragma unroll
     for (int i = 0; i < 64; ++i) {
@@ -1501,16 +1564,21 @@ __global__ void __launch_bounds__(256) k_act_reduce64(const double* __restrict__
     for (int w = 1; w < 64; w <<= 1)
 #pragma unroll
         for (int i = 0; i < 64; i += 2 * w) v[i] = v[i] + v[i + w];
-    out[(size_t)g * G + j] = v[0];
+    out[(size_t)blockIdx.y * G + j] = v[0];
 }
 
 // Argmin over the G grid sums (one workgroup) and set-up of the refinement state.
-__global__ void __launch_bounds__(1024) k_act_argmin(const double* __restrict__ tot, int G, int qmax, int iters,
-                                                     ActState* S, float* scale, int32_t* idx, double* sse)
+__global__ void __launch_bounds__(1024) k_act_argmin(const ActBatch B, const double* __restrict__ tot, int G, int qmax,
+                                                     int iters, const ActOut O)
 {
     __shared__ double s_bestE[16];
     __shared__ int s_bestJ[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    ActState* S = B.S + blockIdx.x;
+    float* scale = O.scale[blockIdx.x];
+    int32_t* idx = O.idx[blockIdx.x];
+    double* sse = O.sse[blockIdx.x];
+    tot += (size_t)blockIdx.x * G;                 // the last level holds one row per tensor
     const float a = __uint_as_float(S->absmax_bits);
     if (!(a <= kHuge)) {
         if (tid == 0) {
@@ -1560,16 +1628,22 @@ __global__ void __launch_bounds__(1024) k_act_argmin(const double* __restrict__ 
 // lane = chunk, wave = block.  The wave reads its 16 KB with coalesced 16-byte loads and
 // turns them into one chunk per lane through a wave-private LDS tile (32 chunks at a time);
 // fp32 chunk sums per scale, then the first six tree levels by wave shuffles.
-__global__ void __launch_bounds__(256) k_act_probe(const float* __restrict__ x, long long N, float lo, float hi,
-                                                   const ActState* S, double* probe0, const ActPre pre)
+__global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, float hi, double* probe0, const ActPre pre)
 {
     __shared__ float4 tile4[4][32 * kTileStride / 4];
-    if (S->status != 0 || S->done) return;
-    const ActPreV V = act_pre_load(pre);
-    const int np = S->nprobe;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long blk = (long long)blockIdx.x * 4 + wave;
-    const long long base = blk * kBlockElems;                 // first element of this wave's block
+    const int blk = blockIdx.x * 4 + wave;                    // block in the concatenated numbering
+    const int total = B.start[B.count];
+    const int t = act_find(B, blk < total ? blk : total - 1);
+    const ActState* S = B.S + t;
+    // the four waves of a workgroup may belong to different tensors: a wave with nothing to do still
+    // takes part in the barriers below, with N = 0 so that it loads nothing
+    const bool active = blk < total && S->status == 0 && !S->done;
+    const float* __restrict__ x = B.x[t];
+    const long long N = active ? B.N[t] : 0;
+    const ActPreV V = act_pre_load(pre);
+    const int np = active ? S->nprobe : 0;
+    const long long base = (long long)(blk - B.start[t]) * kBlockElems;   // first element of this wave's block
     float* tile = reinterpret_cast<float*>(tile4[wave]);
 
     float xr[kChunk];
@@ -1618,16 +1692,23 @@ __global__ void __launch_bounds__(256) k_act_probe(const float* __restrict__ x, 
         double v = (double)s[0];
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) v = v + __shfl_xor(v, off, 64);   // pairwise tree, same in all lanes
-        if (lane == 0 && base < N) probe0[blk * kMaxProbes + pi] = v;
+        if (lane == 0) probe0[(size_t)blk * kMaxProbes + pi] = v;
     }
 }
 
 // Last tree level(s) over <= 64 rows of per-scale sums, then the golden-section bookkeeping.
-__global__ void __launch_bounds__(64) k_act_finish(const double* __restrict__ part, int rows, int iters,
-                                                   ActState* S, float* scale, double* sse)
+__global__ void __launch_bounds__(64) k_act_finish(const ActBatch B, int level, const double* __restrict__ part, int iters,
+                                                   const ActOut O)
 {
     __shared__ double vals[kMaxProbes];
+    ActState* S = B.S + blockIdx.x;
     if (S->status != 0 || S->done) return;
+    float* scale = O.scale[blockIdx.x];
+    double* sse = O.sse[blockIdx.x];
+    int first = 0;
+    for (int u = 0; u < (int)blockIdx.x; ++u) first += act_rows(B.start[u + 1] - B.start[u], level);
+    const int rows = act_rows(B.start[blockIdx.x + 1] - B.start[blockIdx.x], level);
+    part += (size_t)first * kMaxProbes;
     const int t = threadIdx.x;
     if (t < kMaxProbes) {
         double v[64];
@@ -1845,66 +1926,85 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
     return MMSE_OK;
 }
 
-// Codes of the searched tensor (residual or shifted input) for its final scale, 8 elements per
-// thread, two per byte; a rejected tensor (scale NaN) is coded as zeros.
-__global__ void __launch_bounds__(kPackThreads) k_act_pack(const float* __restrict__ x, long long N, const ActPre pre,
-                                                           const float* __restrict__ scale, float lo, float hi,
-                                                           uint8_t* __restrict__ packed)
+// Codes of the searched tensors (input, residual or shifted input) for their final scales: one
+// workgroup per 4096-element block, 8 elements -> one 32-bit store, two such groups per thread;
+// a rejected tensor (scale NaN) is coded as zeros.
+__global__ void __launch_bounds__(kPackThreads) k_act_pack(const ActBatch B, const ActPre pre, const ActOut O,
+                                                           float lo, float hi)
 {
-    const long long e0 = ((long long)blockIdx.x * kPackThreads + threadIdx.x) * kPackPerThread;
-    if (e0 >= N) return;
-    const int cnt = (N - e0) < kPackPerThread ? (int)(N - e0) : kPackPerThread;
+    const int t = act_find(B, blockIdx.x);
+    const float* __restrict__ x = B.x[t];
+    const long long N = B.N[t];
+    uint8_t* __restrict__ packed = O.packed[t];
+    if (!packed) return;
     const ActPreV V = act_pre_load(pre);
-    const float sc = *scale, inv = 1.0f / sc;
-    float v[kPackPerThread];
-    if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
-        const float4 p0 = reinterpret_cast<const float4*>(x + e0)[0];
-        const float4 p1 = reinterpret_cast<const float4*>(x + e0)[1];
-        v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w;
-        v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
-    } else {
+    const float sc = *O.scale[t], inv = 1.0f / sc;
+    const long long blk0 = (long long)(blockIdx.x - B.start[t]) * kBlockElems;
 #pragma unroll
-        for (int i = 0; i < kPackPerThread; ++i) v[i] = (i < cnt) ? x[e0 + i] : 0.0f;
-    }
-    unsigned word = 0;
+    for (int h = 0; h < kBlockElems / (kPackThreads * kPackPerThread); ++h) {
+        const long long e0 = blk0 + ((long long)h * kPackThreads + threadIdx.x) * kPackPerThread;
+        if (e0 >= N) continue;
+        const int cnt = (N - e0) < kPackPerThread ? (int)(N - e0) : kPackPerThread;
+        float v[kPackPerThread];
+        if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
+            const float4 p0 = reinterpret_cast<const float4*>(x + e0)[0];
+            const float4 p1 = reinterpret_cast<const float4*>(x + e0)[1];
+            v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w;
+            v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+        } else {
 #pragma unroll
-    for (int i = 0; i < kPackPerThread; ++i) {
-        if (i < cnt) {
-            const int q = (sc == sc) ? (int)code_of(act_pre(V, v[i]), inv, lo, hi) : 0;
-            word |= ((unsigned)q & 0xFu) << (4 * i);
+            for (int i = 0; i < kPackPerThread; ++i) v[i] = (i < cnt) ? x[e0 + i] : 0.0f;
         }
-    }
-    uint8_t* dst = packed + (e0 >> 1);
-    if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(packed) & 3u) == 0) {
-        *reinterpret_cast<unsigned*>(dst) = word;
-    } else {
-        const int nbytes = (cnt + 1) >> 1;
-        for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));
+        unsigned word = 0;
+#pragma unroll
+        for (int i = 0; i < kPackPerThread; ++i) {
+            if (i < cnt) {
+                const int q = (sc == sc) ? (int)code_of(act_pre(V, v[i]), inv, lo, hi) : 0;
+                word |= ((unsigned)q & 0xFu) << (4 * i);
+            }
+        }
+        uint8_t* dst = packed + (e0 >> 1);
+        if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(packed) & 3u) == 0) {
+            *reinterpret_cast<unsigned*>(dst) = word;
+        } else {
+            const int nbytes = (cnt + 1) >> 1;
+            for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));
+        }
     }
 }
 
 struct ActPlan {
-    int nb;                 // blocks of 4096 elements
-    int levels;             // reduce64 stages of the grid sums until one row is left
-    int rows[8];            // rows[0] = nb, rows[i+1] = ceil(rows[i]/64)
-    int plevels;            // reduce64 stages of the probe sums until <= 64 rows are left
+    int count;
+    int start[kMaxActBatch + 1];   // first block of each tensor in the concatenated numbering
+    int levels;             // reduce64 stages of the grid sums until every tensor has one row
+    int plevels;            // reduce64 stages of the probe sums until every tensor has <= 64 rows
+    int total_rows[8];      // rows of all tensors together at each level
     size_t off_part[8];     // byte offsets of the grid-sum levels ([rows][G] doubles)
     size_t off_probe[8];    // byte offsets of the probe levels ([rows][kMaxProbes] doubles)
     size_t bytes;
 };
 
-ActPlan plan_activation(long long N, int G)
+// Workspace of one launch group: the states, then the levels of the grid sums, then those of the probe sums.
+ActPlan plan_activation(const long long* N, int count, int G)
 {
     ActPlan P{};
-    P.nb = (int)((N + kBlockElems - 1) / kBlockElems);
-    P.rows[0] = P.nb;
-    P.levels = 0;
-    while (P.rows[P.levels] > 1) { P.rows[P.levels + 1] = (P.rows[P.levels] + 63) / 64; ++P.levels; }
-    P.plevels = 0;
-    while (P.rows[P.plevels] > 64) ++P.plevels;
-    size_t off = round256(sizeof(ActState));
-    for (int l = 0; l <= P.levels; ++l) { P.off_part[l] = off; off += round256((size_t)P.rows[l] * G * sizeof(double)); }
-    for (int l = 0; l <= P.plevels; ++l) { P.off_probe[l] = off; off += round256((size_t)P.rows[l] * kMaxProbes * sizeof(double)); }
+    P.count = count;
+    int maxnb = 1;
+    for (int t = 0; t < count; ++t) {
+        const int nb = (int)((N[t] + kBlockElems - 1) / kBlockElems);
+        P.start[t + 1] = P.start[t] + nb;
+        maxnb = nb > maxnb ? nb : maxnb;
+    }
+    while (act_rows(maxnb, P.levels) > 1) ++P.levels;
+    while (act_rows(maxnb, P.plevels) > 64) ++P.plevels;
+    for (int l = 0; l <= P.levels; ++l) {
+        int r = 0;
+        for (int t = 0; t < count; ++t) r += act_rows(P.start[t + 1] - P.start[t], l);
+        P.total_rows[l] = r;
+    }
+    size_t off = round256(sizeof(ActState) * (size_t)count);
+    for (int l = 0; l <= P.levels; ++l) { P.off_part[l] = off; off += round256((size_t)P.total_rows[l] * G * sizeof(double)); }
+    for (int l = 0; l <= P.plevels; ++l) { P.off_probe[l] = off; off += round256((size_t)P.total_rows[l] * kMaxProbes * sizeof(double)); }
     P.bytes = off;
     return P;
 }
@@ -1976,7 +2076,28 @@ int mmse_workspace_bytes_activation(int64_t N, const mmse_params_t* p, size_t* b
     const int rc = check_params(p);
     if (rc) return rc;
     if (N <= 0 || N > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
-    *bytes_out = plan_activation(N, p->grid_points).bytes;
+    const long long n1 = N;
+    *bytes_out = plan_activation(&n1, 1, p->grid_points).bytes;
+    return MMSE_OK;
+}
+
+int mmse_workspace_bytes_activation_batched(const int64_t* N_host, int32_t count, const mmse_params_t* p, size_t* bytes_out)
+{
+    if (!bytes_out || !N_host) return MMSE_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc) return rc;
+    if (count <= 0 || count > MMSE_MAX_BATCH_TENSORS) return MMSE_ERR_SIZE;
+    size_t total = 0;
+    for (int g0 = 0; g0 < count; g0 += kMaxActBatch) {
+        long long n[kMaxActBatch];
+        const int m = (count - g0) < kMaxActBatch ? (count - g0) : kMaxActBatch;
+        for (int i = 0; i < m; ++i) {
+            if (N_host[g0 + i] <= 0 || N_host[g0 + i] > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
+            n[i] = N_host[g0 + i];
+        }
+        total += plan_activation(n, m, p->grid_points).bytes;
+    }
+    *bytes_out = total;
     return MMSE_OK;
 }
 
@@ -2299,8 +2420,100 @@ int dual_line_search(const float* w_dev, int64_t K, int64_t n, int32_t qmin, int
     return MMSE_OK;
 }
 
-// The per-layer search; pre_mode selects what is searched (the tensor, the residual of a first
-// tensor, the tensor shifted by its minimum); packed_dev != nullptr also writes the codes.
+// The per-layer search for a group of at most kMaxActBatch tensors in one set of launches (arguments already
+// validated).  pre_mode selects what is searched (the tensor, the residual of a first tensor, the tensor
+// shifted by its minimum; the last two for a single tensor only); packed != nullptr also writes the codes.
+struct ActItem { const float* x; long long N; float* scale; int32_t* idx; double* sse; uint8_t* packed; };
+
+static int run_activation_group(const ActItem* items, int count, const mmse_params_t* p, int pre_mode,
+                                const float* scale1_dev, int qmin1, int qmax1, float* delta_dev,
+                                char* ws, const ActPlan& P, hipStream_t s)
+{
+    const int G = p->grid_points;
+    ActBatch B{};
+    ActOut O{};
+    bool any_packed = false;
+    long long maxN = 0;
+    for (int t = 0; t < count; ++t) {
+        B.x[t] = items[t].x; B.N[t] = items[t].N; B.start[t] = P.start[t];
+        O.scale[t] = items[t].scale; O.idx[t] = items[t].idx; O.sse[t] = items[t].sse; O.packed[t] = items[t].packed;
+        any_packed = any_packed || items[t].packed != nullptr;
+        maxN = items[t].N > maxN ? items[t].N : maxN;
+    }
+    B.start[count] = P.start[count];
+    B.count = count;
+    B.S = reinterpret_cast<ActState*>(ws);
+    ActState* S = B.S;
+    const int total = P.start[count];
+    const float lo = (float)p->qmin, hi = (float)p->qmax;
+    ActPre pre{};
+    pre.mode = pre_mode;
+    pre.s = pre_mode == 1 ? scale1_dev : (pre_mode == 2 ? &S->delta : nullptr);
+    pre.lo1 = (float)qmin1; pre.hi1 = (float)qmax1;
+#define MMSE_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH; } while (0)
+
+    hipLaunchKernelGGL(k_act_init, dim3(1), dim3(64), 0, s, S, count);
+    MMSE_CHECK_LAUNCH();
+    {
+        // per tensor at most one workgroup per CU, eight 16-byte loads in flight per thread: measured fastest
+        // on MI355X (6.9 TB/s on a 205 MB tensor; more, smaller workgroups lose up to 2x)
+        constexpr int U = 8;
+        long long want = (maxN + 1024 * U - 1) / (1024 * U);
+        const int grid = (int)(want < 256 ? (want < 1 ? 1 : want) : 256);
+        const dim3 g(grid, count);
+        if (pre_mode == 0) hipLaunchKernelGGL((k_act_absmax<U, 0>), g, dim3(256), 0, s, B, pre);
+        else if (pre_mode == 1) hipLaunchKernelGGL((k_act_absmax<U, 1>), g, dim3(256), 0, s, B, pre);
+        else hipLaunchKernelGGL((k_act_absmax<U, 2>), g, dim3(256), 0, s, B, pre);
+        MMSE_CHECK_LAUNCH();
+        if (pre_mode == 2) {
+            hipLaunchKernelGGL(k_act_offset_setup, dim3(1), dim3(64), 0, s, S, delta_dev);
+            MMSE_CHECK_LAUNCH();
+        }
+    }
+    {
+        const int C = pick_cands(p);
+        const int waves = (G + 64 * C - 1) / (64 * C);
+        double* part0 = reinterpret_cast<double*>(ws + P.off_part[0]);
+        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre);
+        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre);
+        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre);
+        MMSE_CHECK_LAUNCH();
+    }
+    for (int l = 0; l < P.levels; ++l) {
+        hipLaunchKernelGGL(k_act_reduce64, dim3((G + 255) / 256, P.total_rows[l + 1]), dim3(256), 0, s, B, l + 1,
+                           reinterpret_cast<const double*>(ws + P.off_part[l]), G,
+                           reinterpret_cast<double*>(ws + P.off_part[l + 1]));
+        MMSE_CHECK_LAUNCH();
+    }
+    {
+        int threads = ((G + 63) / 64) * 64;
+        if (threads > 1024) threads = 1024;
+        hipLaunchKernelGGL(k_act_argmin, dim3(count), dim3(threads), 0, s, B,
+                           reinterpret_cast<const double*>(ws + P.off_part[P.levels]), G, p->qmax, p->refine_iters, O);
+        MMSE_CHECK_LAUNCH();
+    }
+    for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
+        hipLaunchKernelGGL(k_act_probe, dim3((total + 3) / 4), dim3(256), 0, s, B, lo, hi,
+                           reinterpret_cast<double*>(ws + P.off_probe[0]), pre);
+        MMSE_CHECK_LAUNCH();
+        for (int l = 0; l < P.plevels; ++l) {
+            hipLaunchKernelGGL(k_act_reduce64, dim3(1, P.total_rows[l + 1]), dim3(64), 0, s, B, l + 1,
+                               reinterpret_cast<const double*>(ws + P.off_probe[l]), kMaxProbes,
+                               reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
+            MMSE_CHECK_LAUNCH();
+        }
+        hipLaunchKernelGGL(k_act_finish, dim3(count), dim3(64), 0, s, B, P.plevels,
+                           reinterpret_cast<const double*>(ws + P.off_probe[P.plevels]), p->refine_iters, O);
+        MMSE_CHECK_LAUNCH();
+    }
+    if (any_packed) {
+        hipLaunchKernelGGL(k_act_pack, dim3(total), dim3(kPackThreads), 0, s, B, pre, O, lo, hi);
+        MMSE_CHECK_LAUNCH();
+    }
+#undef MMSE_CHECK_LAUNCH
+    return MMSE_OK;
+}
+
 static int run_activation(const float* x_dev, int64_t N, const mmse_params_t* p, int pre_mode,
                           const float* scale1_dev, int qmin1, int qmax1, float* delta_dev,
                           float* scale_dev, int32_t* idx_dev, double* sse_dev, uint8_t* packed_dev,
@@ -2312,81 +2525,53 @@ static int run_activation(const float* x_dev, int64_t N, const mmse_params_t* p,
     if (N <= 0 || N > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
     if (!aligned_to(x_dev, 4) || !aligned_to(scale_dev, 4) || !aligned_to(idx_dev, 4) || !aligned_to(sse_dev, 8))
         return MMSE_ERR_ALIGN;
-    const int G = p->grid_points;
-    const ActPlan P = plan_activation(N, G);
+    const long long n1 = N;
+    const ActPlan P = plan_activation(&n1, 1, p->grid_points);
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < P.bytes) return MMSE_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    char* ws = static_cast<char*>(ws_dev);
-    ActState* S = reinterpret_cast<ActState*>(ws);
-    const float lo = (float)p->qmin, hi = (float)p->qmax;
-    ActPre pre{};
-    pre.mode = pre_mode;
-    pre.s = pre_mode == 1 ? scale1_dev : (pre_mode == 2 ? &S->delta : nullptr);
-    pre.lo1 = (float)qmin1; pre.hi1 = (float)qmax1;
-#define MMSE_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH; } while (0)
+    const ActItem item{x_dev, n1, scale_dev, idx_dev, sse_dev, packed_dev};
+    return run_activation_group(&item, 1, p, pre_mode, scale1_dev, qmin1, qmax1, delta_dev,
+                                static_cast<char*>(ws_dev), P, static_cast<hipStream_t>(stream));
+}
 
-    hipLaunchKernelGGL(k_act_init, dim3(1), dim3(64), 0, s, S);
-    MMSE_CHECK_LAUNCH();
-    {
-        // one workgroup per CU, eight 16-byte loads in flight per thread: measured fastest on MI355X
-        // (6.9 TB/s on a 205 MB tensor; more, smaller workgroups lose up to 2x)
-        constexpr int U = 8;
-        long long want = (N + 1024 * U - 1) / (1024 * U);
-        const int grid = (int)(want < 256 ? (want < 1 ? 1 : want) : 256);
-        if (pre_mode == 0) hipLaunchKernelGGL((k_act_absmax<U, 0>), dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S, pre);
-        else if (pre_mode == 1) hipLaunchKernelGGL((k_act_absmax<U, 1>), dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S, pre);
-        else hipLaunchKernelGGL((k_act_absmax<U, 2>), dim3(grid), dim3(256), 0, s, x_dev, (long long)N, S, pre);
-        MMSE_CHECK_LAUNCH();
-        if (pre_mode == 2) {
-            hipLaunchKernelGGL(k_act_offset_setup, dim3(1), dim3(64), 0, s, S, delta_dev);
-            MMSE_CHECK_LAUNCH();
+int mmse_scale_search_activation_batched(const mmse_act_desc_t* descs_host, int32_t count, const mmse_params_t* p,
+                                         void* ws_dev, size_t ws_bytes, void* stream)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (!descs_host) return MMSE_ERR_NULL;
+    if (count <= 0 || count > MMSE_MAX_BATCH_TENSORS) return MMSE_ERR_SIZE;
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) {
+        const mmse_act_desc_t& d = descs_host[i];
+        if (!d.x_dev || !d.scale_dev || !d.idx_dev || !d.sse_dev) return MMSE_ERR_NULL;
+        if (d.N <= 0 || d.N > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
+        if (!aligned_to(d.x_dev, 4) || !aligned_to(d.scale_dev, 4) || !aligned_to(d.idx_dev, 4) || !aligned_to(d.sse_dev, 8))
+            return MMSE_ERR_ALIGN;
+    }
+    // groups of at most kMaxActBatch tensors, each with its own slice of the workspace
+    ActPlan plans[(MMSE_MAX_BATCH_TENSORS + kMaxActBatch - 1) / kMaxActBatch];
+    int ngroups = 0;
+    for (int g0 = 0; g0 < count; g0 += kMaxActBatch, ++ngroups) {
+        long long n[kMaxActBatch];
+        const int m = (count - g0) < kMaxActBatch ? (count - g0) : kMaxActBatch;
+        for (int i = 0; i < m; ++i) n[i] = descs_host[g0 + i].N;
+        plans[ngroups] = plan_activation(n, m, p->grid_points);
+        need += plans[ngroups].bytes;
+    }
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < need) return MMSE_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(ws_dev);
+    for (int g = 0; g < ngroups; ++g) {
+        ActItem items[kMaxActBatch];
+        const int g0 = g * kMaxActBatch;
+        const int m = plans[g].count;
+        for (int i = 0; i < m; ++i) {
+            const mmse_act_desc_t& d = descs_host[g0 + i];
+            items[i] = ActItem{d.x_dev, (long long)d.N, d.scale_dev, d.idx_dev, d.sse_dev, d.packed_dev};
         }
+        rc = run_activation_group(items, m, p, 0, nullptr, 0, 0, nullptr, ws, plans[g], static_cast<hipStream_t>(stream));
+        if (rc) return rc;
+        ws += plans[g].bytes;
     }
-    {
-        const int C = pick_cands(p);
-        const int waves = (G + 64 * C - 1) / (64 * C);
-        double* part0 = reinterpret_cast<double*>(ws + P.off_part[0]);
-        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0, pre);
-        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0, pre);
-        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(P.nb), dim3(64 * waves), 0, s, x_dev, (long long)N, G, p->qmax, lo, hi, S, part0, pre);
-        MMSE_CHECK_LAUNCH();
-    }
-    for (int l = 0; l < P.levels; ++l) {
-        hipLaunchKernelGGL(k_act_reduce64, dim3((G + 255) / 256, P.rows[l + 1]), dim3(256), 0, s,
-                           reinterpret_cast<const double*>(ws + P.off_part[l]), P.rows[l], G,
-                           reinterpret_cast<double*>(ws + P.off_part[l + 1]));
-        MMSE_CHECK_LAUNCH();
-    }
-    {
-        int threads = ((G + 63) / 64) * 64;
-        if (threads > 1024) threads = 1024;
-        hipLaunchKernelGGL(k_act_argmin, dim3(1), dim3(threads), 0, s,
-                           reinterpret_cast<const double*>(ws + P.off_part[P.levels]), G, p->qmax, p->refine_iters,
-                           S, scale_dev, idx_dev, sse_dev);
-        MMSE_CHECK_LAUNCH();
-    }
-    for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
-        hipLaunchKernelGGL(k_act_probe, dim3((P.nb + 3) / 4), dim3(256), 0, s, x_dev, (long long)N, lo, hi, S,
-                           reinterpret_cast<double*>(ws + P.off_probe[0]), pre);
-        MMSE_CHECK_LAUNCH();
-        for (int l = 0; l < P.plevels; ++l) {
-            hipLaunchKernelGGL(k_act_reduce64, dim3(1, P.rows[l + 1]), dim3(64), 0, s,
-                               reinterpret_cast<const double*>(ws + P.off_probe[l]), P.rows[l], kMaxProbes,
-                               reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
-            MMSE_CHECK_LAUNCH();
-        }
-        hipLaunchKernelGGL(k_act_finish, dim3(1), dim3(64), 0, s,
-                           reinterpret_cast<const double*>(ws + P.off_probe[P.plevels]), P.rows[P.plevels],
-                           p->refine_iters, S, scale_dev, sse_dev);
-        MMSE_CHECK_LAUNCH();
-    }
-    if (packed_dev) {
-        const long long per_wg = (long long)kPackThreads * kPackPerThread;
-        hipLaunchKernelGGL(k_act_pack, dim3((unsigned)((N + per_wg - 1) / per_wg)), dim3(kPackThreads), 0, s,
-                           x_dev, (long long)N, pre, scale_dev, lo, hi, packed_dev);
-        MMSE_CHECK_LAUNCH();
-    }
-#undef MMSE_CHECK_LAUNCH
     return MMSE_OK;
 }
 

@@ -1,0 +1,110 @@
+"""GPU parity of the batched per-layer activation search (Section 3.7, Eq. 15 for many layers in one set of
+launches) against the oracle, tensor by tensor and bit for bit."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1902_06822_amd import synth
+
+pytestmark = pytest.mark.gpu
+UNSIGNED = (0, 15)
+SIGNED = (-8, 7)
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1902_06822_amd import binding
+    binding.load_library()
+    return binding
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_all(B, xs, q, G, iters, tag):
+    import torch
+    res = B.mmse_scale_search_activation_batched([dev(x) for x in xs], B.params(*q, G, iters))
+    torch.cuda.synchronize()
+    for i, (x, r) in enumerate(zip(xs, res)):
+        o = oracle.can_search(x, *q, G, iters)
+        assert int(r.idx[0]) == o["idx"], f"idx {tag} tensor {i}"
+        np.testing.assert_allclose(r.scale.cpu().numpy(), [o["scale"]], rtol=1e-6, atol=0, err_msg=f"scale {tag} {i}")
+        np.testing.assert_allclose(r.sse.cpu().numpy(), [o["sse"]], rtol=1e-4, atol=0, err_msg=f"sse {tag} {i}")
+        np.testing.assert_array_equal(r.scale.cpu().numpy(), np.array([o["scale"]], np.float32), err_msg=f"scale bits {tag} {i}")
+        np.testing.assert_array_equal(r.sse.cpu().numpy(), np.array([o["sse"]]), err_msg=f"sse bits {tag} {i}")
+        np.testing.assert_array_equal(r.packed.cpu().numpy(), oracle.can_quantize_pack_int4(x, [o["scale"]], *q),
+                                      err_msg=f"codes {tag} {i}")
+    return res
+
+
+@pytest.mark.parametrize("G,iters", [(128, 20), (512, 3), (50, 0), (1024, 20)])
+def test_batched_activations_of_many_sizes(B, G, iters):
+    say(f"batched activations G={G} iters={iters}")
+    sizes = [1, 63, 4096, 4097, 100001, 300000, 5, 3 * 8192 + 1, 262144, 64, 1000003, 4095]
+    xs = [synth.acts_relu_normal(n, 800 + i) if i % 2 == 0 else synth.acts_relu_student_t(n, 800 + i)
+          for i, n in enumerate(sizes)]
+    check_all(B, xs, UNSIGNED, G, iters, f"G={G}")
+
+
+def test_batched_activations_signed_range_and_degenerate_members(B):
+    say("batched activations: signed range; zero, tiny, NaN and infinite members among ordinary ones")
+    rng = np.random.default_rng(12)
+    xs = [rng.normal(0, 1, n).astype(np.float32) for n in (5000, 70001, 12, 4096 * 65, 9000)]
+    xs[1][:] = 0.0
+    xs[2][:] = np.float32(2.0 ** -70)
+    bad = rng.normal(0, 1, 20000).astype(np.float32)
+    bad[19999] = np.nan
+    inf = rng.normal(0, 1, 4097).astype(np.float32)
+    inf[0] = -np.inf
+    xs += [bad, inf]
+    res = check_all(B, xs, SIGNED, 96, 20, "degenerate")
+    assert float(res[1].scale[0]) == 1.0 and float(res[1].sse[0]) == 0.0
+    assert np.isnan(float(res[5].scale[0])) and int(res[5].idx[0]) == -1
+    assert np.isnan(float(res[6].scale[0])) and not res[6].packed.cpu().numpy().any()
+
+
+def test_batched_activations_more_tensors_than_one_launch_group(B):
+    say("batched activations: 70 tensors (two launch groups)")
+    xs = [synth.acts_relu_normal(1000 + 997 * i, 300 + i) for i in range(70)]
+    check_all(B, xs, UNSIGNED, 64, 20, "70 tensors")
+
+
+def test_batched_equals_one_by_one_and_is_repeatable(B):
+    import torch
+    say("batched activations: same as the per-tensor entry point, twice")
+    xs = [dev(synth.acts_relu_student_t(n, 50 + i)) for i, n in enumerate((123457, 4096, 999, 2 ** 20))]
+    p = B.params(*UNSIGNED, 256, 20)
+    plan = B.ActBatchedPlan(xs, p)
+    for rep in range(2):
+        for r in plan.results:
+            r.scale.fill_(-1); r.idx.fill_(-5); r.sse.fill_(-1); r.packed.fill_(0xEE)
+        plan.ws.fill_(0xCD)
+        res = plan.run()
+        torch.cuda.synchronize()
+        for x, r in zip(xs, res):
+            one = B.mmse_scale_search_activation(x, p)
+            pk = B.quantize_pack_int4(x, one.scale, *UNSIGNED)
+            torch.cuda.synchronize()
+            assert (float(one.scale[0]), int(one.idx[0]), float(one.sse[0])) == \
+                (float(r.scale[0]), int(r.idx[0]), float(r.sse[0]))
+            np.testing.assert_array_equal(pk.cpu().numpy(), r.packed.cpu().numpy())
+
+
+def test_batched_activations_reject_bad_arguments(B):
+    x = dev(np.ones(16, np.float32))
+    with pytest.raises(RuntimeError):
+        B.ActBatchedPlan([x] * 1025, B.params(*UNSIGNED, 16, 4))
+    with pytest.raises(ValueError):
+        B.ActBatchedPlan([x.cpu()], B.params(*UNSIGNED, 16, 4))
