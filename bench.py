@@ -351,22 +351,32 @@ def bench_whole(args, cfg, torch, B) -> int:
     res_plans = [B.BatchedPlan([dev_w[i]], pw, want_packed=True, scale1=[plan_w.results[i].scale]) for i in range(nlayers)] \
         if nkey else []
     res_all = B.BatchedPlan(dev_w, pw, want_packed=True, scale1=[r.scale for r in plan_w.results]) if fixed_key else None
-    nstreams = max(1, args.streams)
-    streams = [torch.cuda.Stream() for _ in range(nstreams)]
-    act_ws = [B.alloc_workspace(B.mmse_workspace_bytes_activation(x.numel(), pa)) for x in dev_x]
-    act_out = [B.SearchResult(torch.empty(1, dtype=torch.float32, device="cuda"),
-                              torch.empty(1, dtype=torch.int32, device="cuda"),
-                              torch.empty(1, dtype=torch.float64, device="cuda"),
-                              torch.empty((x.numel() + 1) // 2, dtype=torch.uint8, device="cuda")) for x in dev_x]
+    nstreams = max(0, args.streams)              # 0: the batched entry point on one side stream
+    streams = [torch.cuda.Stream() for _ in range(max(1, nstreams))]
     order = sorted(range(len(dev_x)), key=lambda i: -dev_x[i].numel())            # large tensors first
+    if nstreams == 0:
+        plan_a = B.ActBatchedPlan([dev_x[i] for i in order], pa, want_packed=True)
+        act_out = [None] * len(dev_x)
+        for n_, i in enumerate(order):
+            act_out[i] = plan_a.results[n_]
+    else:
+        act_ws = [B.alloc_workspace(B.mmse_workspace_bytes_activation(x.numel(), pa)) for x in dev_x]
+        act_out = [B.SearchResult(torch.empty(1, dtype=torch.float32, device="cuda"),
+                                  torch.empty(1, dtype=torch.int32, device="cuda"),
+                                  torch.empty(1, dtype=torch.float64, device="cuda"),
+                                  torch.empty((x.numel() + 1) // 2, dtype=torch.uint8, device="cuda")) for x in dev_x]
     key_used = []
 
     def step():
         main = torch.cuda.current_stream()
         start = torch.cuda.Event()
         start.record(main)
-        # activations on side streams, largest first, while the weight path runs on the main stream
-        for n_, i in enumerate(order):
+        # activations on side streams while the weight path runs on the main stream
+        if nstreams == 0:
+            streams[0].wait_event(start)
+            with torch.cuda.stream(streams[0]):
+                plan_a.run()
+        for n_, i in enumerate(order if nstreams else []):
             st = streams[n_ % nstreams]
             if n_ < nstreams:
                 st.wait_event(start)
@@ -427,7 +437,9 @@ def bench_whole(args, cfg, torch, B) -> int:
                                f"({cfg.residual}), all calibration activations",
                    "weight_tensors": nlayers, "weights": w_elems, "second_tensor_layers": (nlayers if fixed_key else key_used),
                    "activation_tensors": len(dev_x), "activation_elements": a_elems, "grid_points": G,
-                   "refine_iters": iters, "streams_for_activations": nstreams, "evals_per_step": evals},
+                   "refine_iters": iters,
+                   "activations": "batched entry point" if nstreams == 0 else f"per tensor on {nstreams} streams",
+                   "evals_per_step": evals},
         "roofline": None, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
     return 0
 
@@ -448,7 +460,9 @@ def main() -> int:
                     help="also run plain device copies of this many MiB (for scaling FETCH_SIZE/WRITE_SIZE "
                          "counters under rocprofv3 --pmc); not part of any timed region")
     ap.add_argument("--pair-grid", type=int, default=32, help="G1 = G2 of --part dual-ls")
-    ap.add_argument("--streams", type=int, default=4, help="--part whole: side streams the activation tensors are spread over")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="--part whole: 0 = all activation tensors through the batched entry point (default); "
+                         "N > 0 = one call per tensor, spread over N side streams")
     ap.add_argument("--act-variant", choices=("plain", "residual", "offset"), default="plain",
                     help="--part activation: the per-layer search alone, with the second tensor, or in offset form")
     ap.add_argument("--grid-points", type=int, default=0, help="override G of the configuration")

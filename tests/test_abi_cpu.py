@@ -39,6 +39,7 @@ def test_struct_layouts_match_header(B):
     assert C.sizeof(B.MmseTensorDesc) == 64
     assert B.MmseTensorDesc.K.offset == 8 and B.MmseTensorDesc.packed_dev.offset == 56
     assert C.sizeof(B.MmseDualDesc) == 72 and B.MmseDualDesc.sweeps_dev.offset == 64
+    assert C.sizeof(B.MmseActDesc) == 48 and B.MmseActDesc.N.offset == 8 and B.MmseActDesc.packed_dev.offset == 40
 
 
 def test_status_strings(B):
@@ -113,6 +114,21 @@ def test_entry_points_validate_before_enqueue(B):
     assert lib.mmse_scale_alternating_kernelwise(a, 4, 65537, -8, 7, 10, a, a, a, None) == -2
     assert lib.mmse_scale_alternating_kernelwise(a, 4, 4, -8, 7, 1001, a, a, a, None) == -3
     assert lib.mmse_scale_alternating_kernelwise(a, 4, 4, -8, 7, 10, a, a + 4, a, None) == -6
+    d1 = (B.MmseActDesc * 2)(B.MmseActDesc(a, 64, a, a, a, None), B.MmseActDesc(a, 4097, a, a, a, a))
+    assert lib.mmse_scale_search_activation_batched(d1, 2, C.byref(pu), a, 16, None) == -4
+    assert lib.mmse_scale_search_activation_batched(None, 2, C.byref(pu), a, 1 << 24, None) == -1
+    assert lib.mmse_scale_search_activation_batched(d1, 0, C.byref(pu), a, 1 << 24, None) == -2
+    assert lib.mmse_scale_search_activation_batched(d1, 1025, C.byref(pu), a, 1 << 24, None) == -2
+    d2 = (B.MmseActDesc * 1)(B.MmseActDesc(a, 0, a, a, a, None))
+    assert lib.mmse_scale_search_activation_batched(d2, 1, C.byref(pu), a, 1 << 24, None) == -2
+    d3 = (B.MmseActDesc * 1)(B.MmseActDesc(a, 8, None, a, a, None))
+    assert lib.mmse_scale_search_activation_batched(d3, 1, C.byref(pu), a, 1 << 24, None) == -1
+    sizes = (C.c_int64 * 2)(64, 4097)
+    need2, need1a, need1b = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    assert lib.mmse_workspace_bytes_activation_batched(sizes, 2, C.byref(pu), C.byref(need2)) == 0
+    assert lib.mmse_workspace_bytes_activation(64, C.byref(pu), C.byref(need1a)) == 0
+    assert lib.mmse_workspace_bytes_activation(4097, C.byref(pu), C.byref(need1b)) == 0
+    assert max(need1a.value, need1b.value) <= need2.value <= 2 * (need1a.value + need1b.value)
     # sizes
     assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
     assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2

@@ -137,6 +137,30 @@ def test_full_size_activation_second_tensor_and_offset_form(B, cfg):
     np.testing.assert_array_equal(ro.packed.cpu().numpy(), oo["packed"])
 
 
+def test_config4_all_activation_tensors_batched(B):
+    """Every calibration tensor of configuration 4 (54 tensors, 341 M elements) through the batched entry
+    point, in the launch configuration `bench.py --part whole` times, against the oracle tensor by tensor."""
+    import torch
+    c = synth.config(4)
+    G, it = c.grid_points, c.refine_iters
+    say(f"config 4: {len(c.act_shapes)} activation tensors, batched")
+    order = sorted(range(len(c.act_shapes)), key=lambda i: -c.act_shapes[i].per_image)
+    dev = [to_dev(c.act_tensor(i)) for i in order]
+    res = B.mmse_scale_search_activation_batched(dev, B.params(*UNSIGNED, G, it))
+    torch.cuda.synchronize()
+    got = [(float(r.scale[0]), int(r.idx[0]), float(r.sse[0])) for r in res]
+    del dev
+    for n_, i in enumerate(order):
+        x = c.act_tensor(i)
+        o = oracle.can_search(x, *UNSIGNED, G, it)
+        assert got[n_] == (float(o["scale"]), o["idx"], o["sse"]), f"cfg4 activation tensor {i} ({c.act_shapes[i].name})"
+        if n_ % 9 == 0 or n_ == len(order) - 1:          # codes of every ninth tensor, the largest included
+            np.testing.assert_array_equal(res[n_].packed.cpu().numpy(),
+                                          oracle.can_quantize_pack_int4(x, [o["scale"]], *UNSIGNED),
+                                          err_msg=f"cfg4 activation codes {i}")
+        res[n_].packed = None
+
+
 def test_config5_weights_and_residual_on_sampled_kernels(B):
     import torch
     c = synth.config(5)
