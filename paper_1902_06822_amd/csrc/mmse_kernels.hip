@@ -133,6 +133,33 @@ __device__ __forceinline__ float xform_apply(const Xform& X, float v, long long 
     return v;
 }
 
+// Ordering point for an LDS tile that only one wave touches: the LDS unit executes a wave's
+// instructions in order, so a read issued after a write of the same wave sees it; the fences keep the
+// compiler from moving LDS accesses across this point.  No workgroup barrier: the waves stay independent.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Lane i receives lane i + N of its row of 16 lanes (zero beyond the row).
+template <int N>
+__device__ __forceinline__ double dpp_row_shl(double v)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0x100 + N, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0x100 + N, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int l)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v)
@@ -1625,74 +1652,125 @@ __global__ void __launch_bounds__(1024) k_act_argmin(const ActBatch B, const dou
 }
 
 // One refinement pass: f at up to kMaxProbes scales for every block of 64 chunks.
-// lane = chunk, wave = block.  The wave reads its 16 KB with coalesced 16-byte loads and
-// turns them into one chunk per lane through a wave-private LDS tile (32 chunks at a time);
-// fp32 chunk sums per scale, then the first six tree levels by wave shuffles.
+// lane = chunk, wave = block.  A block is handled as two halves by element: elements 0..31 of every
+// chunk, then elements 32..63 (the fp32 chunk sums simply continue, so the order of additions is
+// unchanged).  All 16 coalesced 16-byte loads of the wave are issued up front; the first half goes
+// through a wave-private LDS tile to become half a chunk per lane and is evaluated for all scales
+// while the loads of the second half are still in flight.  Tree over the 64 chunk sums by DPP.
+constexpr int kHalfStride = 36;        // floats between chunks in the half-chunk tile (32 + 4: keeps 16-byte alignment)
+
+__device__ __forceinline__ void probe_fetch(const float* __restrict__ x, long long N, long long base, int h, int lane,
+                                            bool aligned, float4 (&stg)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int f = r * 64 + lane;                         // float4 number inside the half: chunk f / 8, position f % 8
+        const long long e = base + (long long)(f >> 3) * kChunk + h * 32 + (f & 7) * 4;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (aligned && e + 4 <= N) {
+            v = *reinterpret_cast<const float4*>(x + e);
+        } else if (e < N) {
+            v.x = x[e];
+            if (e + 1 < N) v.y = x[e + 1];
+            if (e + 2 < N) v.z = x[e + 2];
+            if (e + 3 < N) v.w = x[e + 3];
+        }
+        stg[r] = v;
+    }
+}
+
+__device__ __forceinline__ void probe_stage(float* tile, const ActPreV& V, long long N, long long base, int h, int lane,
+                                            const float4 (&stg)[8], float (&xr)[32])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int f = r * 64 + lane;
+        float4 v = stg[r];
+        if (V.mode != 0) {                                   // padding stays exactly zero
+            const long long e = base + (long long)(f >> 3) * kChunk + h * 32 + (f & 7) * 4;
+            if (e < N) v.x = act_pre(V, v.x);
+            if (e + 1 < N) v.y = act_pre(V, v.y);
+            if (e + 2 < N) v.z = act_pre(V, v.z);
+            if (e + 3 < N) v.w = act_pre(V, v.w);
+        }
+        *reinterpret_cast<float4*>(tile + (f >> 3) * kHalfStride + (f & 7) * 4) = v;
+    }
+    wave_lds_sync();
+    const float4* t4 = reinterpret_cast<const float4*>(tile + lane * kHalfStride);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float4 v = t4[i];
+        xr[4 * i + 0] = v.x; xr[4 * i + 1] = v.y; xr[4 * i + 2] = v.z; xr[4 * i + 3] = v.w;
+    }
+    wave_lds_sync();
+}
+
+__device__ __forceinline__ void probe_eval(const float (&xr)[32], int np, const float (&pr)[kMaxProbes],
+                                           const float (&pinv)[kMaxProbes], float lo, float hi, float (&s)[kMaxProbes])
+{
+#pragma unroll
+    for (int pi = 0; pi < kMaxProbes; ++pi) {
+        if (pi < np) {
+            float sp[1] = {s[pi]};
+            const float al[1] = {pr[pi]}, iv[1] = {pinv[pi]};
+#pragma unroll
+            for (int i = 0; i < 32; i += 8) {
+                const float xs[8] = {xr[i], xr[i + 1], xr[i + 2], xr[i + 3], xr[i + 4], xr[i + 5], xr[i + 6], xr[i + 7]};
+                eval_stage<8, 1>(xs, al, iv, lo, hi, sp);
+            }
+            s[pi] = sp[0];
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, float hi, double* probe0, const ActPre pre)
 {
-    __shared__ float4 tile4[4][32 * kTileStride / 4];
+    __shared__ float4 tile4[4][64 * kHalfStride / 4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int blk = blockIdx.x * 4 + wave;                    // block in the concatenated numbering
     const int total = B.start[B.count];
-    const int t = act_find(B, blk < total ? blk : total - 1);
+    if (blk >= total) return;                                 // the waves of a workgroup are independent: no barriers below
+    const int t = act_find(B, blk);
     const ActState* S = B.S + t;
-    // the four waves of a workgroup may belong to different tensors: a wave with nothing to do still
-    // takes part in the barriers below, with N = 0 so that it loads nothing
-    const bool active = blk < total && S->status == 0 && !S->done;
+    if (S->status != 0 || S->done) return;
     const float* __restrict__ x = B.x[t];
-    const long long N = active ? B.N[t] : 0;
+    const long long N = B.N[t];
     const ActPreV V = act_pre_load(pre);
-    const int np = active ? S->nprobe : 0;
+    const int np = S->nprobe;
     const long long base = (long long)(blk - B.start[t]) * kBlockElems;   // first element of this wave's block
     float* tile = reinterpret_cast<float*>(tile4[wave]);
-
-    float xr[kChunk];
-#pragma unroll
-    for (int i = 0; i < kChunk; ++i) xr[i] = 0.0f;
     const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
-    for (int p0 = 0; p0 < 64; p0 += 32) {
-        // 32 chunks = 2048 floats = 512 float4: 8 per lane
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int f = r * 64 + lane;
-            const long long e = base + (long long)p0 * kChunk + 4LL * f;
-            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (aligned && e + 4 <= N) {
-                v = *reinterpret_cast<const float4*>(x + e);
-                if (V.mode != 0) { v.x = act_pre(V, v.x); v.y = act_pre(V, v.y); v.z = act_pre(V, v.z); v.w = act_pre(V, v.w); }
-            } else if (e < N) {                                    // padding stays exactly zero
-                v.x = act_pre(V, x[e]);
-                if (e + 1 < N) v.y = act_pre(V, x[e + 1]);
-                if (e + 2 < N) v.z = act_pre(V, x[e + 2]);
-                if (e + 3 < N) v.w = act_pre(V, x[e + 3]);
-            }
-            *reinterpret_cast<float4*>(tile + (f >> 4) * kTileStride + (f & 15) * 4) = v;
-        }
-        __syncthreads();
-        if (lane >= p0 && lane < p0 + 32) {
-            const float4* t4 = reinterpret_cast<const float4*>(tile + (lane - p0) * kTileStride);
-#pragma unroll
-            for (int i = 0; i < kChunk / 4; ++i) {
-                const float4 v = t4[i];
-                xr[4 * i + 0] = v.x; xr[4 * i + 1] = v.y; xr[4 * i + 2] = v.z; xr[4 * i + 3] = v.w;
-            }
-        }
-        __syncthreads();
-    }
 
-    for (int pi = 0; pi < np; ++pi) {
-        const float alpha = S->probes[pi];
-        float s[1] = {0.0f};
-        const float al[1] = {alpha}, iv[1] = {1.0f / alpha};
+    float4 stg0[8], stg1[8];
+    probe_fetch(x, N, base, 0, lane, aligned, stg0);
+    probe_fetch(x, N, base, 1, lane, aligned, stg1);
+    // the scales of this pass (unused slots hold 1.0)
+    float pr[kMaxProbes], pinv[kMaxProbes], s[kMaxProbes];
 #pragma unroll
-        for (int i = 0; i < kChunk; i += 8) {
-            const float xs[8] = {xr[i], xr[i + 1], xr[i + 2], xr[i + 3], xr[i + 4], xr[i + 5], xr[i + 6], xr[i + 7]};
-            eval_stage<8, 1>(xs, al, iv, lo, hi, s);
+    for (int i = 0; i < kMaxProbes; ++i) pr[i] = S->probes[i];
+#pragma unroll
+    for (int i = 0; i < kMaxProbes; ++i) { pinv[i] = 1.0f / pr[i]; s[i] = 0.0f; }
+
+    float xr[32];
+    probe_stage(tile, V, N, base, 0, lane, stg0, xr);
+    probe_eval(xr, np, pr, pinv, lo, hi, s);
+    probe_stage(tile, V, N, base, 1, lane, stg1, xr);
+    probe_eval(xr, np, pr, pinv, lo, hi, s);
+
+    // pairwise tree over the 64 chunk sums: lane i (a multiple of 2w) adds lane i + w; four levels inside
+    // rows of 16 lanes by DPP shifts, the last two on the four row heads as scalar operands
+#pragma unroll
+    for (int pi = 0; pi < kMaxProbes; ++pi) {
+        if (pi < np) {
+            double v = (double)s[pi];
+            v = v + dpp_row_shl<1>(v);
+            v = v + dpp_row_shl<2>(v);
+            v = v + dpp_row_shl<4>(v);
+            v = v + dpp_row_shl<8>(v);
+            const double r0 = readlane_f64(v, 0), r1 = readlane_f64(v, 16), r2 = readlane_f64(v, 32), r3 = readlane_f64(v, 48);
+            const double tot = (r0 + r1) + (r2 + r3);
+            if (lane == 0) probe0[(size_t)blk * kMaxProbes + pi] = tot;
         }
-        double v = (double)s[0];
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) v = v + __shfl_xor(v, off, 64);   // pairwise tree, same in all lanes
-        if (lane == 0) probe0[(size_t)blk * kMaxProbes + pi] = v;
     }
 }
 
