@@ -24,7 +24,7 @@
  *     2^60 or holds inf/NaN is rejected on the device: scale = NaN, idx = -1,
  *     sse = NaN for that problem, codes unspecified.
  *   - "sse" is the SUM of squared errors (the paper omits the mean factor,
- *     Section 3.2), accumulated as documented in mmse_kernels.hip.
+ *     Section 3.2), accumulated as documented in csrc/mmse_kernels.hip.
  */
 #ifndef MMSE_H_
 #define MMSE_H_

@@ -1,0 +1,629 @@
+// mmse_activation.h -- per-layer activation path: one or many tensors spread over the whole GPU (Section 3.7), with the residual and offset variants.
+#ifndef MMSE_ACTIVATION_H_
+#define MMSE_ACTIVATION_H_
+#include "mmse_common.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------------
+// activation tensor: one problem of N elements over the whole GPU
+// ---------------------------------------------------------------------------------
+// Workspace layout (all offsets multiples of 256 bytes):
+//   ActState                              scalars of the search
+//   part0[nb][G] doubles                  per-block tree sums of the grid sweep
+//   part1[ceil(nb/64)][G], part2, ...     upper tree levels, 64 blocks at a time
+//   probe0[nb], probe1[...], ...          same hierarchy for one refinement probe
+constexpr int kMaxProbes = 8;          // scales evaluated in one pass over an activation tensor
+
+struct ActState {
+    unsigned absmax_bits;
+    int status;              // 0 normal, 1 all-zero (scale 1), 2 rejected
+    int j;                   // grid argmin
+    int it;                  // golden-section iterations decided so far
+    int done;                // refinement finished
+    int have_c, have_d;      // f(pc), f(pd) known
+    int nprobe;              // scales to evaluate in the next pass
+    float absmax;
+    float lo_a, hi_a, pc, pd, best_a;
+    float probes[kMaxProbes];
+    double ec, ed, best;
+    unsigned min_key, max_key;   // offset form: order-preserving keys of min and max
+    float delta;                 // offset form: min of the tensor
+};
+
+// What the activation kernels search instead of the stored tensor (never written to memory):
+//   mode 1: the residual of a first tensor, x - s*[x/s] saturated to [lo1, hi1]   (Section 3.7, Eq. 16)
+//   mode 2: the shifted tensor x - delta, delta = min x                            (Section 3.1, Eq. 2)
+struct ActPre {
+    int mode;
+    const float* s;              // device: the first scale (mode 1) or delta (mode 2)
+    float lo1, hi1;
+};
+struct ActPreV { int mode; float s, inv, lo1, hi1; };
+
+__device__ __forceinline__ ActPreV act_pre_load(const ActPre& P)
+{
+    ActPreV V;
+    V.mode = P.mode; V.lo1 = P.lo1; V.hi1 = P.hi1;
+    V.s = P.mode != 0 ? *P.s : 0.0f;
+    V.inv = P.mode == 1 ? 1.0f / V.s : 0.0f;
+    return V;
+}
+
+__device__ __forceinline__ float act_pre(const ActPreV& V, float v)
+{
+    if (V.mode == 1) return __builtin_fmaf(-V.s, code_of(v, V.inv, V.lo1, V.hi1), v);
+    if (V.mode == 2) return v - V.s;
+    return v;
+}
+
+// Order-preserving map of fp32 bit patterns to unsigned integers (-NaN < -inf < ... < +inf < +NaN).
+__device__ __forceinline__ unsigned order_key(float v)
+{
+    const unsigned b = __float_as_uint(v);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float order_unkey(unsigned k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// Several activation tensors searched by the same launches: the 4096-element blocks of all tensors
+// are numbered consecutively (start[t] = first block of tensor t); every tensor has its own state.
+constexpr int kMaxActBatch = 64;
+struct ActBatch {
+    const float* x[kMaxActBatch];
+    long long N[kMaxActBatch];
+    int start[kMaxActBatch + 1];
+    int count;
+    ActState* S;                 // [count]
+};
+struct ActOut {
+    float* scale[kMaxActBatch];
+    int32_t* idx[kMaxActBatch];
+    double* sse[kMaxActBatch];
+    uint8_t* packed[kMaxActBatch];
+};
+
+// tensor that owns block b: the largest t with start[t] <= b
+__device__ __forceinline__ int act_find(const ActBatch& B, int b)
+{
+    int lo = 0, hi = B.count - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (B.start[mid] <= b) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// rows a tensor of nb blocks has after l tree stages of 64
+__host__ __device__ inline int act_rows(int nb, int l)
+{
+    for (int i = 0; i < l; ++i) nb = (nb + 63) / 64;
+    return nb;
+}
+
+// At tree level l the rows of all tensors are again stored one tensor after the other.  Finds the
+// tensor that owns row r of that level; returns its first row there (first) and at the level below (below).
+__device__ __forceinline__ int act_find_level(const ActBatch& B, int l, int r, int& first, int& below)
+{
+    int acc = 0, accb = 0, t = 0;
+    for (; t < B.count; ++t) {
+        const int nb = B.start[t + 1] - B.start[t];
+        const int rows = act_rows(nb, l);
+        if (r < acc + rows || t == B.count - 1) break;
+        acc += rows;
+        accb += act_rows(nb, l - 1);
+    }
+    first = acc; below = accb;
+    return t;
+}
+
+__global__ void k_act_init(ActState* Sall, int count)
+{
+    if (blockIdx.x == 0 && (int)threadIdx.x < count) {
+        ActState* S = Sall + threadIdx.x;
+        S->absmax_bits = 0; S->status = 0; S->j = 0; S->it = 0; S->done = 1;
+        S->have_c = S->have_d = 0; S->nprobe = 0; S->absmax = 0.0f;
+        S->lo_a = S->hi_a = S->pc = S->pd = S->best_a = 1.0f;
+        for (int i = 0; i < kMaxProbes; ++i) S->probes[i] = 1.0f;
+        S->ec = S->ed = S->best = 0.0;
+        S->min_key = 0xffffffffu; S->max_key = 0u; S->delta = 0.0f;
+    }
+}
+
+// ---- golden-section bookkeeping (one thread) ---------------------------------------
+// The search is sequential: each iteration needs f at one new scale.  One pass over a big
+// tensor costs a full read of it, so a pass evaluates the scale(s) the search is waiting
+// for *and* every scale the next two iterations could ask for (both outcomes of each
+// comparison: 1 + 2 + 4, or 2 + 2 + 4 at the start).  act_advance then replays the plain
+// sequential algorithm, looking values up by scale; it stops when a value is missing.
+// The probes are produced by the same fp32 expressions on both paths, so a lookup is an
+// exact match.  Nothing about the result depends on how much was evaluated ahead.
+template <int DEPTH>
+__device__ void act_enumerate(float lo_a, float hi_a, float pc, float pd, int depth, float* list, int& n)
+{
+    if constexpr (DEPTH > 0) {
+        if (depth == 0) return;
+        {   // f(pc) <= f(pd): keep [lo, pd]
+            const float nh = pd, npd = pc;
+            const float npc = __builtin_fmaf(-kPhi, nh - lo_a, nh);
+            if (n < kMaxProbes) list[n++] = npc;
+            act_enumerate<DEPTH - 1>(lo_a, nh, npc, npd, depth - 1, list, n);
+        }
+        {   // otherwise: keep [pc, hi]
+            const float nl = pc, npc = pd;
+            const float npd = __builtin_fmaf(kPhi, hi_a - nl, nl);
+            if (n < kMaxProbes) list[n++] = npd;
+            act_enumerate<DEPTH - 1>(nl, hi_a, npc, npd, depth - 1, list, n);
+        }
+    }
+}
+
+__device__ void act_plan(ActState* S, int iters)
+{
+    int n = 0;
+    float list[kMaxProbes];
+    if (!S->done) {
+        if (!S->have_c) list[n++] = S->pc;
+        if (!S->have_d) list[n++] = S->pd;
+        int depth = iters - S->it;
+        if (depth > 2) depth = 2;
+        act_enumerate<2>(S->lo_a, S->hi_a, S->pc, S->pd, depth, list, n);
+    }
+    S->nprobe = n;
+    for (int i = 0; i < kMaxProbes; ++i) S->probes[i] = i < n ? list[i] : 1.0f;
+}
+
+__device__ bool act_lookup(const float* probes, const double* vals, int n, float a, double& out)
+{
+    for (int i = 0; i < n; ++i)
+        if (probes[i] == a) { out = vals[i]; return true; }
+    return false;
+}
+
+__device__ void act_advance(ActState* S, const double* vals, int iters)
+{
+    float lo_a = S->lo_a, hi_a = S->hi_a, pc = S->pc, pd = S->pd, best_a = S->best_a;
+    double ec = S->ec, ed = S->ed, best = S->best;
+    int have_c = S->have_c, have_d = S->have_d, it = S->it, done = S->done;
+    const int n = S->nprobe;
+    while (!done) {
+        if (!have_c) {
+            if (!act_lookup(S->probes, vals, n, pc, ec)) break;
+            have_c = 1;
+            if (ec < best) { best = ec; best_a = pc; }
+        }
+        if (!have_d) {
+            if (!act_lookup(S->probes, vals, n, pd, ed)) break;
+            have_d = 1;
+            if (ed < best) { best = ed; best_a = pd; }
+        }
+        if (it == iters) { done = 1; break; }
+        if (ec <= ed) {
+            hi_a = pd; pd = pc; ed = ec;
+            pc = __builtin_fmaf(-kPhi, hi_a - lo_a, hi_a);
+            have_c = 0;
+        } else {
+            lo_a = pc; pc = pd; ec = ed;
+            pd = __builtin_fmaf(kPhi, hi_a - lo_a, lo_a);
+            have_d = 0;
+        }
+        ++it;
+    }
+    S->lo_a = lo_a; S->hi_a = hi_a; S->pc = pc; S->pd = pd; S->best_a = best_a;
+    S->ec = ec; S->ed = ed; S->best = best;
+    S->have_c = have_c; S->have_d = have_d; S->it = it; S->done = done;
+}
+
+// MODE 0: max |x| (integer max of the bit patterns); 1: max |residual of the first tensor|;
+// 2: min and max of x as order-preserving keys (offset form).
+template <int U, int MODE>
+__global__ void __launch_bounds__(256) k_act_absmax(const ActBatch B, const ActPre pre)
+{
+    const float* __restrict__ x = B.x[blockIdx.y];
+    const long long N = B.N[blockIdx.y];
+    ActState* S = B.S + blockIdx.y;
+    if ((long long)blockIdx.x * blockDim.x * 4 * U >= N) return;       // nothing of this tensor for this workgroup
+    __shared__ unsigned s_amax[4];
+    __shared__ unsigned s_amin[4];
+    unsigned amax = 0, amin = 0xffffffffu;
+    ActPreV V{};
+    if constexpr (MODE == 1) V = act_pre_load(pre);
+    auto take = [&](float v) {
+        if constexpr (MODE == 2) {
+            const unsigned k = order_key(v);
+            amax = k > amax ? k : amax;
+            amin = k < amin ? k : amin;
+        } else {
+            if constexpr (MODE == 1) v = act_pre(V, v);
+            const unsigned b = abs_bits(v);
+            amax = b > amax ? b : amax;
+        }
+    };
+    const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+    // U independent 16-byte loads per thread and trip: enough bytes in flight to fill HBM
+    const long long tile = (long long)blockDim.x * 4 * U;                 // elements per workgroup and trip
+    const long long stride = (long long)gridDim.x * tile;
+    for (long long base = (long long)blockIdx.x * tile; base < N; base += stride) {
+        if (aligned && base + tile <= N) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                v[u] = *reinterpret_cast<const float4*>(x + base + ((long long)u * blockDim.x + threadIdx.x) * 4);
+#pragma unroll
+            for (int u = 0; u < U; ++u) { take(v[u].x); take(v[u].y); take(v[u].z); take(v[u].w); }
+        } else {
+            for (long long i = base + threadIdx.x; i < base + tile && i < N; i += blockDim.x) take(x[i]);
+        }
+    }
+    amax = wave_max_u32(amax);
+    if constexpr (MODE == 2) amin = ~wave_max_u32(~amin);
+    if ((threadIdx.x & 63) == 0) { s_amax[threadIdx.x >> 6] = amax; s_amin[threadIdx.x >> 6] = amin; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned am = s_amax[0], an = s_amin[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) {
+            am = s_amax[w] > am ? s_amax[w] : am;
+            an = s_amin[w] < an ? s_amin[w] : an;
+        }
+        if constexpr (MODE == 2) {
+            atomicMax(&S->max_key, am);
+            atomicMin(&S->min_key, an);
+        } else {
+            atomicMax(&S->absmax_bits, am);       // integer max: exact and order-free
+        }
+    }
+}
+
+// Offset form: delta = min x; the search range is that of x - delta, whose largest element is
+// fl(max - delta) because rounding is monotonic.  Anything not finite rejects the tensor.
+__global__ void k_act_offset_setup(ActState* S, float* delta_out)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const float mn = order_unkey(S->min_key), mx = order_unkey(S->max_key);
+    const float nanf_ = __uint_as_float(0x7fc00000u);
+    const bool finite = (abs_bits(mn) < 0x7f800000u) && (abs_bits(mx) < 0x7f800000u);
+    const float range = finite ? mx - mn : nanf_;
+    S->delta = mn;
+    S->absmax_bits = abs_bits(range);
+    *delta_out = (range <= kHuge) ? mn : nanf_;
+}
+
+// Grid sweep of one 4096-element block per workgroup; waves split the candidates.
+template <int C>
+__global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int qmax,
+                                                    float lo, float hi, double* part0, const ActPre pre)
+{
+    __shared__ float4 slice4[kBlockElems / 4];
+    float* slice = reinterpret_cast<float*>(slice4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const int t = act_find(B, blockIdx.x);
+    const float* __restrict__ x = B.x[t];
+    const long long N = B.N[t];
+    const ActState* S = B.S + t;
+    const float a = __uint_as_float(S->absmax_bits);
+    if (!(a <= kHuge)) return;                // rejected: k_act_argmin reports it
+    const bool tiny = a < kTiny;
+    const long long base = (long long)(blockIdx.x - B.start[t]) * kBlockElems;
+    const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
+    const int npad = (len + kChunk - 1) & ~(kChunk - 1);
+    const ActPreV V = act_pre_load(pre);
+    for (int i = tid; i < npad; i += nthreads) slice[i] = i < len ? act_pre(V, x[base + i]) : 0.0f;
+    __syncthreads();
+
+    const float qmaxf = (float)qmax, Gf = (float)G;
+    float alpha[C], inv[C];
+    int jcand[C];
+#pragma unroll
+    for (int u = 0; u < C; ++u) {
+        const int j = (wave * C + u) * 64 + lane;
+        jcand[u] = j;
+        const int jj = j < G ? j : G - 1;
+        alpha[u] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, jj);
+        inv[u] = 1.0f / alpha[u];
+    }
+    double st[C][kLevelsBlk];
+#pragma unroll
+    for (int u = 0; u < C; ++u)
+#pragma unroll
+        for (int l = 0; l < kLevelsBlk; ++l) st[u][l] = 0.0;
+    unsigned ci = 0;
+    sweep_slice<C, kLevelsBlk>(slice, (len + 7) & ~7, ci, alpha, inv, lo, hi, st);
+    double E[C];
+    tree_fold<C, kLevelsBlk>(st, ci, E);
+#pragma unroll
+    for (int u = 0; u < C; ++u)
+        if (jcand[u] < G) part0[(size_t)blockIdx.x * G + jcand[u]] = E[u];
+}
+
+// One tree stage over blocks: out[g][j] = pairwise sum of in[64g .. 64g+63][j].
+// When a stage leaves a single row and fin != nullptr the caller continues with it.
+// Output row blockIdx.y of level `level` belongs to one tensor; its inputs are that tensor's rows of level - 1.
+__global__ void __launch_bounds__(256) k_act_reduce64(const ActBatch B, int level, const double* __restrict__ in, int G,
+                                                      double* __restrict__ out)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    int first, below;
+    const int t = act_find_level(B, level, blockIdx.y, first, below);
+    const int g = blockIdx.y - first;                                   // group of 64 input rows inside the tensor
+    const int rows = act_rows(B.start[t + 1] - B.start[t], level - 1);
+    if (j >= G) return;
+    in += (size_t)below * G;
+    double v[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+        const int r = g * 64 + i;
+        v[i] = r < rows ? in[(size_t)r * G + j] : 0.0;
+    }
+#pragma unroll
+    for (int w = 1; w < 64; w <<= 1)
+#pragma unroll
+        for (int i = 0; i < 64; i += 2 * w) v[i] = v[i] + v[i + w];
+    out[(size_t)blockIdx.y * G + j] = v[0];
+}
+
+// Argmin over the G grid sums (one workgroup) and set-up of the refinement state.
+__global__ void __launch_bounds__(1024) k_act_argmin(const ActBatch B, const double* __restrict__ tot, int G, int qmax,
+                                                     int iters, const ActOut O)
+{
+    __shared__ double s_bestE[16];
+    __shared__ int s_bestJ[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    ActState* S = B.S + blockIdx.x;
+    float* scale = O.scale[blockIdx.x];
+    int32_t* idx = O.idx[blockIdx.x];
+    double* sse = O.sse[blockIdx.x];
+    tot += (size_t)blockIdx.x * G;                 // the last level holds one row per tensor
+    const float a = __uint_as_float(S->absmax_bits);
+    if (!(a <= kHuge)) {
+        if (tid == 0) {
+            const float nanf_ = __uint_as_float(0x7fc00000u);
+            S->status = 2; S->absmax = a;
+            *scale = nanf_; *idx = -1; *sse = (double)nanf_;
+        }
+        return;
+    }
+    double bE = __longlong_as_double(0x7ff0000000000000LL);
+    int bJ = INT_MAX;
+    for (int j = tid; j < G; j += blockDim.x) {
+        const double e = tot[j];
+        if (e < bE) { bE = e; bJ = j; }       // ascending j per thread: strict < keeps the lowest
+    }
+    wave_argmin(bE, bJ);
+    if (lane == 0) { s_bestE[wave] = bE; s_bestJ[wave] = bJ; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < nwaves; ++w) {
+            const double oe = s_bestE[w];
+            const int oj = s_bestJ[w];
+            if (oe < bE || (oe == bE && oj < bJ)) { bE = oe; bJ = oj; }
+        }
+        if (bJ == INT_MAX) bJ = 0;
+        const bool tiny = a < kTiny;
+        const float qmaxf = (float)qmax, Gf = (float)G;
+        const float aj = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, bJ);
+        S->absmax = a; S->j = bJ; S->status = tiny ? 1 : 0; S->it = 0;
+        S->best = bE; S->best_a = aj;
+        S->done = 1; S->have_c = S->have_d = 0;
+        *idx = bJ; *scale = aj; *sse = bE;
+        if (!tiny && iters > 0) {
+            const float lo_a = bJ == 0 ? 0.0f : grid_alpha(a, qmaxf, Gf, bJ - 1);
+            const float hi_a = bJ == G - 1 ? aj : grid_alpha(a, qmaxf, Gf, bJ + 1);
+            const float w = hi_a - lo_a;
+            S->lo_a = lo_a; S->hi_a = hi_a;
+            S->pc = __builtin_fmaf(-kPhi, w, hi_a);
+            S->pd = __builtin_fmaf(kPhi, w, lo_a);
+            S->done = 0;
+        }
+        act_plan(S, iters);
+    }
+}
+
+// One refinement pass: f at up to kMaxProbes scales for every block of 64 chunks.
+// lane = chunk, wave = block.  A block is handled as two halves by element: elements 0..31 of every
+// chunk, then elements 32..63 (the fp32 chunk sums simply continue, so the order of additions is
+// unchanged).  All 16 coalesced 16-byte loads of the wave are issued up front; the first half goes
+// through a wave-private LDS tile to become half a chunk per lane and is evaluated for all scales
+// while the loads of the second half are still in flight.  Tree over the 64 chunk sums by DPP.
+constexpr int kHalfStride = 36;        // floats between chunks in the half-chunk tile (32 + 4: keeps 16-byte alignment)
+
+__device__ __forceinline__ void probe_fetch(const float* __restrict__ x, long long N, long long base, int h, int lane,
+                                            bool aligned, float4 (&stg)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int f = r * 64 + lane;                         // float4 number inside the half: chunk f / 8, position f % 8
+        const long long e = base + (long long)(f >> 3) * kChunk + h * 32 + (f & 7) * 4;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (aligned && e + 4 <= N) {
+            v = *reinterpret_cast<const float4*>(x + e);
+        } else if (e < N) {
+            v.x = x[e];
+            if (e + 1 < N) v.y = x[e + 1];
+            if (e + 2 < N) v.z = x[e + 2];
+            if (e + 3 < N) v.w = x[e + 3];
+        }
+        stg[r] = v;
+    }
+}
+
+__device__ __forceinline__ void probe_stage(float* tile, const ActPreV& V, long long N, long long base, int h, int lane,
+                                            const float4 (&stg)[8], float (&xr)[32])
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int f = r * 64 + lane;
+        float4 v = stg[r];
+        if (V.mode != 0) {                                   // padding stays exactly zero
+            const long long e = base + (long long)(f >> 3) * kChunk + h * 32 + (f & 7) * 4;
+            if (e < N) v.x = act_pre(V, v.x);
+            if (e + 1 < N) v.y = act_pre(V, v.y);
+            if (e + 2 < N) v.z = act_pre(V, v.z);
+            if (e + 3 < N) v.w = act_pre(V, v.w);
+        }
+        *reinterpret_cast<float4*>(tile + (f >> 3) * kHalfStride + (f & 7) * 4) = v;
+    }
+    wave_lds_sync();
+    const float4* t4 = reinterpret_cast<const float4*>(tile + lane * kHalfStride);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float4 v = t4[i];
+        xr[4 * i + 0] = v.x; xr[4 * i + 1] = v.y; xr[4 * i + 2] = v.z; xr[4 * i + 3] = v.w;
+    }
+    wave_lds_sync();
+}
+
+__device__ __forceinline__ void probe_eval(const float (&xr)[32], int np, const float (&pr)[kMaxProbes],
+                                           const float (&pinv)[kMaxProbes], float lo, float hi, float (&s)[kMaxProbes])
+{
+#pragma unroll
+    for (int pi = 0; pi < kMaxProbes; ++pi) {
+        if (pi < np) {
+            float sp[1] = {s[pi]};
+            const float al[1] = {pr[pi]}, iv[1] = {pinv[pi]};
+#pragma unroll
+            for (int i = 0; i < 32; i += 8) {
+                const float xs[8] = {xr[i], xr[i + 1], xr[i + 2], xr[i + 3], xr[i + 4], xr[i + 5], xr[i + 6], xr[i + 7]};
+                eval_stage<8, 1>(xs, al, iv, lo, hi, sp);
+            }
+            s[pi] = sp[0];
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, float hi, double* probe0, const ActPre pre)
+{
+    __shared__ float4 tile4[4][64 * kHalfStride / 4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int blk = blockIdx.x * 4 + wave;                    // block in the concatenated numbering
+    const int total = B.start[B.count];
+    if (blk >= total) return;                                 // the waves of a workgroup are independent: no barriers below
+    const int t = act_find(B, blk);
+    const ActState* S = B.S + t;
+    if (S->status != 0 || S->done) return;
+    const float* __restrict__ x = B.x[t];
+    const long long N = B.N[t];
+    const ActPreV V = act_pre_load(pre);
+    const int np = S->nprobe;
+    const long long base = (long long)(blk - B.start[t]) * kBlockElems;   // first element of this wave's block
+    float* tile = reinterpret_cast<float*>(tile4[wave]);
+    const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+
+    float4 stg0[8], stg1[8];
+    probe_fetch(x, N, base, 0, lane, aligned, stg0);
+    probe_fetch(x, N, base, 1, lane, aligned, stg1);
+    // the scales of this pass (unused slots hold 1.0)
+    float pr[kMaxProbes], pinv[kMaxProbes], s[kMaxProbes];
+#pragma unroll
+    for (int i = 0; i < kMaxProbes; ++i) pr[i] = S->probes[i];
+#pragma unroll
+    for (int i = 0; i < kMaxProbes; ++i) { pinv[i] = 1.0f / pr[i]; s[i] = 0.0f; }
+
+    float xr[32];
+    probe_stage(tile, V, N, base, 0, lane, stg0, xr);
+    probe_eval(xr, np, pr, pinv, lo, hi, s);
+    probe_stage(tile, V, N, base, 1, lane, stg1, xr);
+    probe_eval(xr, np, pr, pinv, lo, hi, s);
+
+    // pairwise tree over the 64 chunk sums: lane i (a multiple of 2w) adds lane i + w; four levels inside
+    // rows of 16 lanes by DPP shifts, the last two on the four row heads as scalar operands
+#pragma unroll
+    for (int pi = 0; pi < kMaxProbes; ++pi) {
+        if (pi < np) {
+            double v = (double)s[pi];
+            v = v + dpp_row_shl<1>(v);
+            v = v + dpp_row_shl<2>(v);
+            v = v + dpp_row_shl<4>(v);
+            v = v + dpp_row_shl<8>(v);
+            const double r0 = readlane_f64(v, 0), r1 = readlane_f64(v, 16), r2 = readlane_f64(v, 32), r3 = readlane_f64(v, 48);
+            const double tot = (r0 + r1) + (r2 + r3);
+            if (lane == 0) probe0[(size_t)blk * kMaxProbes + pi] = tot;
+        }
+    }
+}
+
+// Last tree level(s) over <= 64 rows of per-scale sums, then the golden-section bookkeeping.
+__global__ void __launch_bounds__(64) k_act_finish(const ActBatch B, int level, const double* __restrict__ part, int iters,
+                                                   const ActOut O)
+{
+    __shared__ double vals[kMaxProbes];
+    ActState* S = B.S + blockIdx.x;
+    if (S->status != 0 || S->done) return;
+    float* scale = O.scale[blockIdx.x];
+    double* sse = O.sse[blockIdx.x];
+    int first = 0;
+    for (int u = 0; u < (int)blockIdx.x; ++u) first += act_rows(B.start[u + 1] - B.start[u], level);
+    const int rows = act_rows(B.start[blockIdx.x + 1] - B.start[blockIdx.x], level);
+    part += (size_t)first * kMaxProbes;
+    const int t = threadIdx.x;
+    if (t < kMaxProbes) {
+        double v[64];
+#pragma unroll
+        for (int i = 0; i < 64; ++i) v[i] = (i < rows && t < S->nprobe) ? part[(size_t)i * kMaxProbes + t] : 0.0;
+#pragma unroll
+        for (int w = 1; w < 64; w <<= 1)
+#pragma unroll
+            for (int i = 0; i < 64; i += 2 * w) v[i] = v[i] + v[i + w];
+        vals[t] = v[0];
+    }
+    __syncthreads();
+    if (t == 0) {
+        act_advance(S, vals, iters);
+        act_plan(S, iters);
+        *scale = S->best_a;
+        *sse = S->best;
+    }
+}
+
+
+// Codes of the searched tensors (input, residual or shifted input) for their final scales: one
+// workgroup per 4096-element block, 8 elements -> one 32-bit store, two such groups per thread;
+// a rejected tensor (scale NaN) is coded as zeros.
+__global__ void __launch_bounds__(kPackThreads) k_act_pack(const ActBatch B, const ActPre pre, const ActOut O,
+                                                           float lo, float hi)
+{
+    const int t = act_find(B, blockIdx.x);
+    const float* __restrict__ x = B.x[t];
+    const long long N = B.N[t];
+    uint8_t* __restrict__ packed = O.packed[t];
+    if (!packed) return;
+    const ActPreV V = act_pre_load(pre);
+    const float sc = *O.scale[t], inv = 1.0f / sc;
+    const long long blk0 = (long long)(blockIdx.x - B.start[t]) * kBlockElems;
+#pragma unroll
+    for (int h = 0; h < kBlockElems / (kPackThreads * kPackPerThread); ++h) {
+        const long long e0 = blk0 + ((long long)h * kPackThreads + threadIdx.x) * kPackPerThread;
+        if (e0 >= N) continue;
+        const int cnt = (N - e0) < kPackPerThread ? (int)(N - e0) : kPackPerThread;
+        float v[kPackPerThread];
+        if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
+            const float4 p0 = reinterpret_cast<const float4*>(x + e0)[0];
+            const float4 p1 = reinterpret_cast<const float4*>(x + e0)[1];
+            v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w;
+            v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < kPackPerThread; ++i) v[i] = (i < cnt) ? x[e0 + i] : 0.0f;
+        }
+        unsigned word = 0;
+#pragma unroll
+        for (int i = 0; i < kPackPerThread; ++i) {
+            if (i < cnt) {
+                const int q = (sc == sc) ? (int)code_of(act_pre(V, v[i]), inv, lo, hi) : 0;
+                word |= ((unsigned)q & 0xFu) << (4 * i);
+            }
+        }
+        uint8_t* dst = packed + (e0 >> 1);
+        if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(packed) & 3u) == 0) {
+            *reinterpret_cast<unsigned*>(dst) = word;
+        } else {
+            const int nbytes = (cnt + 1) >> 1;
+            for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));
+        }
+    }
+}
+
+}  // namespace
+
+#endif  // MMSE_ACTIVATION_H_

@@ -1,0 +1,302 @@
+// mmse_common.h -- constants, element arithmetic, the canonical summation tree and the LDS-fed sweep core shared by all kernels (gfx950).
+#ifndef MMSE_COMMON_H_
+#define MMSE_COMMON_H_
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <limits.h>
+
+namespace {
+
+
+constexpr int kChunk = 64;             // elements per sequential fp32 chunk
+constexpr int kMaxBatch = 32;          // tensors per launch (descriptor table lives in kernarg)
+constexpr int kTile = 8192;            // floats of one kernel staged in LDS at a time
+constexpr int kLevelsKW = 11;          // binary-counter levels for <= 1024 chunks (65536 elements)
+constexpr int kLevelsKWSmall = 8;      // ... for <= 128 chunks (8192 elements: one LDS tile)
+constexpr int kBlockChunks = 64;       // activation block = 64 chunks = 4096 elements
+constexpr int kBlockElems = kBlockChunks * kChunk;
+constexpr int kLevelsBlk = 7;          // levels for 64 chunks
+constexpr float kTiny = 0x1p-60f;
+constexpr float kHuge = 0x1p+60f;
+constexpr float kPhi = 0.6180339887f;
+constexpr int kPackPerThread = 8;
+constexpr int kPackThreads = 256;
+
+struct TensorArgs {
+    const float* w;
+    const float* scale1;     // nullptr, or first-tensor scales (search/pack the residual)
+    float* scale;
+    int32_t* idx;
+    double* sse;
+    float* absmax;           // workspace [K]
+    double* grid_sse;        // optional [K][G]
+    uint8_t* packed;
+    const uint8_t* sub_packed;   // nullptr, or stored codes Q of another tensor: search/pack w - sub_scale*Q
+    const float* sub_scale;      // [K], with sub_packed
+    const uint8_t* active;       // nullptr, or [K]: kernels with 0 are skipped by the search
+    int K;
+    int n;
+};
+
+struct Batch {
+    TensorArgs t[kMaxBatch];
+    int start[kMaxBatch + 1];   // prefix sum of workgroups per tensor
+    int count;
+    int G;
+    int qmax;
+    int iters;
+    float lo, hi;               // (float)qmin, (float)qmax
+};
+
+// ---------------------------------------------------------------------------------
+// element arithmetic
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float code_of(float x, float inv, float lo, float hi)
+{
+    return __builtin_amdgcn_fmed3f(__builtin_rintf(x * inv), lo, hi);
+}
+
+__device__ __forceinline__ float sq_err_acc(float x, float alpha, float inv, float lo, float hi, float s)
+{
+    const float q = code_of(x, inv, lo, hi);
+    const float r = __builtin_fmaf(-alpha, q, x);
+    return __builtin_fmaf(r, r, s);
+}
+
+// Grid candidate j: (absmax/qmax) * ((j+1)/G), three correctly rounded fp32 operations.
+__device__ __forceinline__ float grid_alpha(float absmax, float qmaxf, float Gf, int j)
+{
+    const float smax = absmax / qmaxf;
+    const float frac = (float)(j + 1) / Gf;
+    return smax * frac;
+}
+
+// What a search reads: the weights themselves, or what another INT4 tensor leaves of them
+// (Section 3.5: T - sum_{i != j} alpha_i*Q_i), formed with one fused multiply-add per element and
+// never stored.  mode 1 recomputes Q = [w/alpha] from alpha; mode 2 reads Q from packed codes.
+struct Xform {
+    int mode;                // 0 none, 1 subtract alpha*[w/alpha], 2 subtract alpha*stored code
+    float s1, inv1;
+    const uint8_t* sub;
+    bool sub_signed;
+};
+
+__device__ __forceinline__ Xform make_xform(const TensorArgs& A, int k, float lo, bool valid)
+{
+    Xform X;
+    X.mode = A.sub_packed != nullptr ? 2 : (A.scale1 != nullptr ? 1 : 0);
+    X.s1 = 1.0f; X.inv1 = 1.0f; X.sub = A.sub_packed; X.sub_signed = lo < 0.0f;
+    if (valid) {
+        if (X.mode == 1) { X.s1 = A.scale1[k]; X.inv1 = 1.0f / X.s1; }
+        if (X.mode == 2) X.s1 = A.sub_scale[k];
+    }
+    return X;
+}
+
+// v: element number `flat` of the tensor (row-major over [K][n]).
+__device__ __forceinline__ float xform_apply(const Xform& X, float v, long long flat, float lo, float hi)
+{
+    if (X.mode == 1) {
+        v = __builtin_fmaf(-X.s1, code_of(v, X.inv1, lo, hi), v);
+    } else if (X.mode == 2) {
+        int q = (X.sub[flat >> 1] >> ((flat & 1) * 4)) & 0xF;
+        if (X.sub_signed && q >= 8) q -= 16;
+        v = __builtin_fmaf(-X.s1, (float)q, v);
+    }
+    return v;
+}
+
+// Ordering point for an LDS tile that only one wave touches: the LDS unit executes a wave's
+// instructions in order, so a read issued after a write of the same wave sees it; the fences keep the
+// compiler from moving LDS accesses across this point.  No workgroup barrier: the waves stay independent.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Lane i receives lane i + N of its row of 16 lanes (zero beyond the row).
+template <int N>
+__device__ __forceinline__ double dpp_row_shl(double v)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0x100 + N, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0x100 + N, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int l)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned o = (unsigned)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// (value, index) minimum over a wave; the lower index wins among equal values.
+__device__ __forceinline__ void wave_argmin(double& e, int& j)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double oe = __shfl_xor(e, off, 64);
+        const int oj = __shfl_xor(j, off, 64);
+        if (oe < e || (oe == e && oj < j)) { e = oe; j = oj; }
+    }
+}
+
+// Binary-counter form of the pairwise sum: after chunk number ci has been pushed,
+// st[.][l] holds the sum of a complete aligned group of 2^l chunks whenever bit l of
+// (ci+1) is set.  ci is wave-uniform, so the ladder is scalar control flow.
+template <int C, int L, int l>
+__device__ __forceinline__ void tree_push_level(double (&st)[C][L], double (&t)[C], unsigned ci)
+{
+    if constexpr (l < L) {
+        if ((ci >> l) & 1u) {
+#pragma unroll
+            for (int u = 0; u < C; ++u) t[u] = st[u][l] + t[u];
+            tree_push_level<C, L, l + 1>(st, t, ci);
+        } else {
+#pragma unroll
+            for (int u = 0; u < C; ++u) st[u][l] = t[u];
+        }
+    }
+}
+
+template <int C, int L>
+__device__ __forceinline__ void tree_push(double (&st)[C][L], double (&t)[C], unsigned ci)
+{
+    tree_push_level<C, L, 0>(st, t, ci);
+}
+
+// Sum of the m chunks pushed so far (carries the unpaired partial groups upward).
+template <int C, int L>
+__device__ __forceinline__ void tree_fold(const double (&st)[C][L], unsigned m, double (&out)[C])
+{
+#pragma unroll
+    for (int u = 0; u < C; ++u) out[u] = 0.0;
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        if ((m >> l) & 1u) {
+#pragma unroll
+            for (int u = 0; u < C; ++u) out[u] = st[u][l] + out[u];
+        }
+    }
+}
+
+// Squared errors of NE elements against C candidates, accumulated into s[C] in element
+// order.  The five operations of an evaluation form a dependent chain, so they are issued
+// stage by stage over all NE*C evaluations: consecutive instructions are independent and
+// the VALU pipeline latency is covered inside one wave.  (Order of the accumulation, the
+// only thing that affects the result, is unchanged: element by element per candidate.)
+// Scheduling fences keep the compiler from re-serialising the stages; LDS/VMEM/SALU
+// instructions may still move across them.
+#define MMSE_STAGE_FENCE() __builtin_amdgcn_sched_barrier(0x94)
+template <int NE, int C>
+__device__ __forceinline__ void eval_stage(const float (&x)[NE], const float (&alpha)[C], const float (&inv)[C],
+                                           float lo, float hi, float (&s)[C])
+{
+    float t[NE][C];
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = x[i] * inv[u];
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = __builtin_rintf(t[i][u]);
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = __builtin_amdgcn_fmed3f(t[i][u], lo, hi);
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i)
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[i][u] = __builtin_fmaf(-alpha[u], t[i][u], x[i]);
+    MMSE_STAGE_FENCE();
+#pragma unroll
+    for (int i = 0; i < NE; ++i) {
+#pragma unroll
+        for (int u = 0; u < C; ++u) s[u] = __builtin_fmaf(t[i][u], t[i][u], s[u]);
+        MMSE_STAGE_FENCE();
+    }
+}
+
+// Sweep the `nelem` elements (a multiple of 8; zero padded) that sit in LDS at `slice` for the C
+// candidates of this lane: whole 64-element chunks, then a last shorter chunk that only walks the
+// 8-element groups it has (padding zeros would be exact no-ops, so skipping them changes nothing).
+template <int C, int L>
+__device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsigned& ci,
+                                            const float (&alpha)[C], const float (&inv)[C],
+                                            float lo, float hi, double (&st)[C][L])
+{
+    const float4* s4 = reinterpret_cast<const float4*>(slice);
+    constexpr int NE = (C >= 4) ? 4 : 8;            // elements per stage group
+    const int nfull = nelem / kChunk;
+    const int tail = nelem - nfull * kChunk;        // 0, 8, ..., 56 elements of a last partial chunk
+    const int ntotal = nfull + (tail > 0 ? 1 : 0);
+    for (int c = 0; c < ntotal; ++c, ++ci) {
+        float s[C];
+#pragma unroll
+        for (int u = 0; u < C; ++u) s[u] = 0.0f;
+        if (c < nfull) {
+            // elements come from LDS one group ahead of their use (same address in every lane: broadcast)
+            float4 nxt[NE / 4];
+#pragma unroll
+            for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + q];
+#pragma unroll
+            for (int e = 0; e < kChunk / NE; ++e) {
+                float x[NE];
+#pragma unroll
+                for (int q = 0; q < NE / 4; ++q) {
+                    x[4 * q + 0] = nxt[q].x; x[4 * q + 1] = nxt[q].y; x[4 * q + 2] = nxt[q].z; x[4 * q + 3] = nxt[q].w;
+                }
+                if (e + 1 < kChunk / NE) {
+#pragma unroll
+                    for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + (e + 1) * (NE / 4) + q];
+                }
+                __builtin_amdgcn_sched_barrier(0);       // the prefetch is issued before this group's arithmetic
+                eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
+            }
+        } else {
+            for (int e = 0; e < tail / NE; ++e) {
+                float x[NE];
+#pragma unroll
+                for (int q = 0; q < NE / 4; ++q) {
+                    const float4 v = s4[c * (kChunk / 4) + e * (NE / 4) + q];
+                    x[4 * q + 0] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+                }
+                eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
+            }
+        }
+        double t[C];
+#pragma unroll
+        for (int u = 0; u < C; ++u) t[u] = (double)s[u];
+        tree_push<C, L>(st, t, ci);
+    }
+}
+
+__device__ __forceinline__ int find_tensor(const Batch& B, int bid)
+{
+    int t = 0;
+    while (t + 1 < B.count && bid >= B.start[t + 1]) ++t;
+    return t;
+}
+
+}  // namespace
+
+#endif  // MMSE_COMMON_H_
