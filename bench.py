@@ -354,6 +354,7 @@ def bench_whole(args, cfg, torch, B) -> int:
     res_plans = [B.BatchedPlan([dev_w[i]], pw, want_packed=True, scale1=[plan_w.results[i].scale]) for i in range(nlayers)] \
         if nkey else []
     res_all = B.BatchedPlan(dev_w, pw, want_packed=True, scale1=[r.scale for r in plan_w.results]) if fixed_key else None
+    plan_sums = B.LayerSumsPlan([r.sse for r in plan_w.results])
     nstreams = max(0, args.streams)              # 0: the batched entry point on one side stream
     streams = [torch.cuda.Stream() for _ in range(max(1, nstreams))]
     order = sorted(range(len(dev_x)), key=lambda i: -dev_x[i].numel())            # large tensors first
@@ -390,7 +391,7 @@ def bench_whole(args, cfg, torch, B) -> int:
         if res_all is not None:
             res_all.run()
         elif nkey:
-            sums = torch.stack([r.sse.sum() for r in res]).cpu().numpy()          # device-to-host: the selection is host logic
+            sums = plan_sums.run().cpu().numpy()           # one small kernel, one device-to-host copy; the ranking is host logic
             key = select.select_top_fraction(select.normalized_mse(list(sums), energy), 0.10)
             key_used[:] = key
             for i in key:

@@ -231,6 +231,13 @@ int mmse_workspace_bytes_activation_batched(const int64_t *N_host, int32_t count
 int mmse_scale_search_activation_batched(const mmse_act_desc_t *descs_host, int32_t count, const mmse_params_t *p,
                                          void *ws_dev, size_t ws_bytes, void *stream);
 
+/* Layer errors for the choice of key layers (Section 3.5: the layers whose MSE is above a threshold get a
+ * second tensor): sums_dev[l] = sum_k sse_l[k] for `count` layers (1..MMSE_MAX_BATCH_TENSORS); the pointers
+ * sse_dev_ptrs_host[l] (device arrays of K_host[l] doubles, outputs of the searches above) and K_host are read
+ * on the host before the call returns.  Fixed summation order, fp64.  The ranking itself is host logic. */
+int mmse_layer_error_sums(const double *const *sse_dev_ptrs_host, const int64_t *K_host, int32_t count,
+                          double *sums_dev, void *stream);
+
 /* The grid evaluation alone (the f(alpha_j) of Eq. 8 for every candidate):
  * absmax_dev[k] = max_i |w_ki|, grid_sse_dev[k*G + j] = f_k(alpha_kj).  Used to
  * check and to time the candidate sweep by itself. */

@@ -24,7 +24,7 @@ EXPORTS = (
     "mmse_workspace_bytes_dual_batched", "dual_quantize_alternating_batched",
     "mmse_workspace_bytes_dual_linesearch", "dual_line_search",
     "activation_residual_quantize", "mmse_scale_search_offset", "mmse_scale_alternating_kernelwise",
-    "mmse_workspace_bytes_activation_batched", "mmse_scale_search_activation_batched",
+    "mmse_workspace_bytes_activation_batched", "mmse_scale_search_activation_batched", "mmse_layer_error_sums",
     "mmse_status_string",
 )
 
@@ -90,6 +90,7 @@ def load_library() -> C.CDLL:
     lib.mmse_workspace_bytes_activation_batched.argtypes = [C.POINTER(C.c_int64), i32, C.POINTER(MmseParams), szp]
     lib.mmse_scale_search_activation_batched.argtypes = [C.POINTER(MmseActDesc), i32, C.POINTER(MmseParams), vp,
                                                          C.c_size_t, vp]
+    lib.mmse_layer_error_sums.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_int64), i32, vp, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -481,3 +482,23 @@ class ActBatchedPlan:
 def mmse_scale_search_activation_batched(tensors: Sequence[torch.Tensor], p: MmseParams,
                                          want_packed: bool = True) -> List[SearchResult]:
     return ActBatchedPlan(tensors, p, want_packed).run()
+
+
+class LayerSumsPlan:
+    """Per-layer totals of per-kernel errors (``mmse_layer_error_sums``); buffers and tables built once."""
+
+    def __init__(self, sse_tensors: Sequence[torch.Tensor]):
+        self.tensors = list(sse_tensors)
+        n = len(self.tensors)
+        self.ptrs = (C.c_void_p * n)(*[_dev(t, torch.float64).data_ptr() for t in self.tensors])
+        self.sizes = (C.c_int64 * n)(*[t.numel() for t in self.tensors])
+        self.out = torch.empty(n, dtype=torch.float64, device=self.tensors[0].device)
+
+    def run(self) -> torch.Tensor:
+        _check(load_library().mmse_layer_error_sums(self.ptrs, self.sizes, len(self.tensors), self.out.data_ptr(),
+                                                    _stream()), "mmse_layer_error_sums")
+        return self.out
+
+
+def mmse_layer_error_sums(sse_tensors: Sequence[torch.Tensor]) -> torch.Tensor:
+    return LayerSumsPlan(sse_tensors).run()

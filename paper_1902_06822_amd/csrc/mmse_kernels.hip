@@ -621,6 +621,27 @@ static int dual_ls_splits(int64_t K, int G1, int G2)
     return (int)want;
 }
 
+int mmse_layer_error_sums(const double* const* sse_dev_ptrs_host, const int64_t* K_host, int32_t count,
+                          double* sums_dev, void* stream)
+{
+    if (!sse_dev_ptrs_host || !K_host || !sums_dev) return MMSE_ERR_NULL;
+    if (count <= 0 || count > MMSE_MAX_BATCH_TENSORS) return MMSE_ERR_SIZE;
+    if (!aligned_to(sums_dev, 8)) return MMSE_ERR_ALIGN;
+    for (int i = 0; i < count; ++i) {
+        if (!sse_dev_ptrs_host[i]) return MMSE_ERR_NULL;
+        if (K_host[i] <= 0 || K_host[i] > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
+        if (!aligned_to(sse_dev_ptrs_host[i], 8)) return MMSE_ERR_ALIGN;
+    }
+    for (int g0 = 0; g0 < count; g0 += kMaxSumBatch) {
+        SumBatch B{};
+        const int m = (count - g0) < kMaxSumBatch ? (count - g0) : kMaxSumBatch;
+        for (int i = 0; i < m; ++i) { B.v[i] = sse_dev_ptrs_host[g0 + i]; B.n[i] = (int)K_host[g0 + i]; }
+        hipLaunchKernelGGL(k_layer_sums, dim3(m), dim3(256), 0, static_cast<hipStream_t>(stream), B, sums_dev + g0);
+        if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+    }
+    return MMSE_OK;
+}
+
 int mmse_scale_alternating_kernelwise(const float* w_dev, int64_t K, int64_t n, int32_t qmin, int32_t qmax,
                                       int32_t max_iters, float* scale_dev, double* sse_dev, int32_t* updates_dev,
                                       void* stream)

@@ -492,6 +492,32 @@ __global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
     }
 }
 
+// ---------------------------------------------------------------------------------
+// k_layer_sums: per-layer total of the per-kernel errors (the layer MSE that picks the key layers,
+// Section 3.5), one workgroup per layer; fixed order: thread-strided fp64 partials, then a tree in LDS.
+// ---------------------------------------------------------------------------------
+constexpr int kMaxSumBatch = 64;
+struct SumBatch {
+    const double* v[kMaxSumBatch];
+    int n[kMaxSumBatch];
+};
+
+__global__ void __launch_bounds__(256) k_layer_sums(const SumBatch B, double* __restrict__ out)
+{
+    __shared__ double part[256];
+    const double* __restrict__ v = B.v[blockIdx.x];
+    const int n = B.n[blockIdx.x];
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) acc = acc + v[i];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] = part[threadIdx.x] + part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = part[0];
+}
+
 }  // namespace
 
 #endif  // MMSE_WEIGHTS_H_

@@ -129,6 +129,13 @@ def test_entry_points_validate_before_enqueue(B):
     assert lib.mmse_workspace_bytes_activation(64, C.byref(pu), C.byref(need1a)) == 0
     assert lib.mmse_workspace_bytes_activation(4097, C.byref(pu), C.byref(need1b)) == 0
     assert max(need1a.value, need1b.value) <= need2.value <= 2 * (need1a.value + need1b.value)
+    ptrs, ks = (C.c_void_p * 2)(a, a), (C.c_int64 * 2)(5, 7)
+    assert lib.mmse_layer_error_sums(ptrs, ks, 2, None, None) == -1
+    assert lib.mmse_layer_error_sums(None, ks, 2, a, None) == -1
+    assert lib.mmse_layer_error_sums(ptrs, ks, 0, a, None) == -2
+    assert lib.mmse_layer_error_sums(ptrs, (C.c_int64 * 2)(5, 0), 2, a, None) == -2
+    assert lib.mmse_layer_error_sums((C.c_void_p * 2)(a, a + 4), ks, 2, a, None) == -6
+    assert lib.mmse_layer_error_sums((C.c_void_p * 2)(a, None), ks, 2, a, None) == -1
     # sizes
     assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
     assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2

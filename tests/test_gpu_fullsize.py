@@ -69,7 +69,9 @@ def test_config4_weights_with_selected_residual_layers(B):
         np.testing.assert_array_equal(r.packed.cpu().numpy(), oracle.can_quantize_pack_int4(w, s, *SIGNED))
     # key layers: top 10 % by normalised error (host rule), second tensor on those only
     energy = [float(np.sum(w.astype(np.float64) ** 2)) for w in ws]
-    nmse = select.normalized_mse([float(r.sse.sum().item()) for r in res], energy)
+    layer_sse = B.mmse_layer_error_sums([r.sse for r in res]).cpu().numpy()
+    np.testing.assert_allclose(layer_sse, [e.sum() for (_, _, e) in ref], rtol=1e-13, atol=0)
+    nmse = select.normalized_mse(list(layer_sse), energy)
     key = select.select_top_fraction(nmse, 0.10)
     assert len(key) == 5
     say(f"config 4: residual on layers {key}")

@@ -286,3 +286,20 @@ def test_results_do_not_depend_on_tuning_or_repeat(B):
             base = cur
         for a, b in zip(base, cur):
             np.testing.assert_array_equal(a, b)
+
+
+def test_layer_error_sums(B):
+    """Per-layer totals for the key-layer choice: fp64, fixed order; against numpy's sum."""
+    import torch
+    say("layer error sums")
+    rng = np.random.default_rng(3)
+    sizes = [1, 2, 255, 256, 257, 1000, 100000] + [37 + i for i in range(70)]
+    host = [np.abs(rng.normal(0, 1, n)) * 10.0 ** rng.integers(-6, 3) for n in sizes]
+    dev = [torch.from_numpy(h).cuda() for h in host]
+    out = B.mmse_layer_error_sums(dev)
+    out2 = B.mmse_layer_error_sums(dev)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    np.testing.assert_array_equal(got, out2.cpu().numpy())                 # deterministic
+    np.testing.assert_allclose(got, [h.sum() for h in host], rtol=1e-13, atol=0)
+    assert got[0] == host[0][0] and got[1] == host[1][0] + host[1][1]
