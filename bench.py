@@ -376,7 +376,9 @@ def bench_whole(args, cfg, torch, B) -> int:
         start = torch.cuda.Event()
         start.record(main)
         # activations on side streams while the weight path runs on the main stream
-        if nstreams == 0:
+        if nstreams == 0 and args.serial:
+            plan_a.run()
+        elif nstreams == 0:
             streams[0].wait_event(start)
             with torch.cuda.stream(streams[0]):
                 plan_a.run()
@@ -468,6 +470,7 @@ def main() -> int:
                          "N > 0 = one call per tensor, spread over N side streams")
     ap.add_argument("--act-variant", choices=("plain", "residual", "offset"), default="plain",
                     help="--part activation: the per-layer search alone, with the second tensor, or in offset form")
+    ap.add_argument("--serial", action="store_true", help="--part whole: activations and weights one after the other on one stream")
     ap.add_argument("--grid-points", type=int, default=0, help="override G of the configuration")
     ap.add_argument("--refine-iters", type=int, default=-1, help="override the refinement iterations")
     args = ap.parse_args()
