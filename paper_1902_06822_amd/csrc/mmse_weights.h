@@ -218,18 +218,24 @@ __global__ void __launch_bounds__(256) k_sweep_small(const Batch B)
 // ---------------------------------------------------------------------------------
 // k_refine_kernelwise: golden-section refinement between the grid neighbours of j*
 // ---------------------------------------------------------------------------------
-// Pairwise sum across the m lanes (chunks) of one kernel through LDS, three tree levels
-// per barrier.  v: this lane's chunk sum; c: chunk number; l0: first lane of the kernel.
-// All lanes of the workgroup call it together.  `par` alternates the buffer so that
-// a call never overwrites what a slower lane is still reading from the previous call.
+// Pairwise sum across the m lanes (chunks) of one kernel.  v: this lane's chunk sum; c: chunk number;
+// the kernel's first lane is a multiple of m.  While m is even the lowest tree levels pair neighbouring
+// lanes of one 16-lane row, so they are DPP shifts (no LDS, no barrier): d = min(4, trailing zeros of m)
+// levels leave m >> d partial sums, which go through LDS three tree levels per barrier.
+// All lanes of the workgroup call it together.  cur / nxt: this kernel's slices of the two halves of the
+// combine buffer; they alternate so that a call never overwrites what a slower lane is still reading.
 __device__ __forceinline__ double tree_combine(double v, int c, int m, bool active,
                                                double*& cur, double*& nxt)
 {
-    // cur / nxt: this kernel's slice of the two halves of the combine buffer (lane c at [c]).
     if (m == 1) return v;                     // m is uniform over the workgroup
-    if (active) cur[c] = v;
+    int d = 0;
+    if ((m & 1) == 0) { v = v + dpp_row_shl<1>(v); d = 1; }
+    if ((m & 3) == 0) { v = v + dpp_row_shl<2>(v); d = 2; }
+    if ((m & 7) == 0) { v = v + dpp_row_shl<4>(v); d = 3; }
+    if ((m & 15) == 0) { v = v + dpp_row_shl<8>(v); d = 4; }
+    int cnt = m >> d;
+    if (active && (c & ((1 << d) - 1)) == 0) cur[c >> d] = v;
     __syncthreads();
-    int cnt = m;
     while (cnt > 1) {
         const int ncnt = (cnt + 7) >> 3;
         if (active && c < ncnt) {
