@@ -539,6 +539,12 @@ def main() -> int:
     torch.cuda.synchronize()
     per_step = sorted(a.elapsed_time(b) for a, b in evs)
     step_stats = {"runs": nrep, "median_ms": per_step[nrep // 2], "min_ms": per_step[0]}
+    # outputs stay on the device; what it costs to bring scales, indices and errors to the host, reported apart
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for r in plan.results:
+        r.scale.cpu(); r.idx.cpu(); r.sse.cpu()
+    step_stats["d2h_scales_idx_sse_ms"] = (time.perf_counter() - t0) * 1e3
 
     # ---- dominant kernel alone: grid sweep + argmin (refine_iters = 0, no packing => one kernel per launch)
     p_sweep = B.params(-8, 7, G, 0, args.cands_per_lane)
