@@ -108,3 +108,34 @@ def test_batched_activations_reject_bad_arguments(B):
         B.ActBatchedPlan([x] * 1025, B.params(*UNSIGNED, 16, 4))
     with pytest.raises(ValueError):
         B.ActBatchedPlan([x.cpu()], B.params(*UNSIGNED, 16, 4))
+
+
+def test_activation_tensors_at_odd_addresses(B):
+    """Views that start 4, 8 and 12 bytes past a 16-byte boundary take the scalar-load paths of abs-max,
+    sweep staging, probe passes and packing; same results as for an aligned copy."""
+    import torch
+    say("activation tensors at unaligned addresses")
+    p = B.params(*UNSIGNED, 128, 20)
+    base = synth.acts_relu_student_t(70000, 77)
+    big = dev(base)
+    views, hosts = [], []
+    for off, n in ((1, 65000), (2, 4099), (3, 12289)):
+        views.append(big[off:off + n])
+        hosts.append(base[off:off + n])
+        assert views[-1].data_ptr() % 16 == 4 * off
+    res = B.ActBatchedPlan(views, p).run()
+    torch.cuda.synchronize()
+    for x, v, r in zip(hosts, views, res):
+        o = oracle.can_search(x, *UNSIGNED, 128, 20)
+        assert (float(r.scale[0]), int(r.idx[0]), float(r.sse[0])) == (float(o["scale"]), o["idx"], o["sse"])
+        np.testing.assert_array_equal(r.packed.cpu().numpy(), oracle.can_quantize_pack_int4(x, [o["scale"]], *UNSIGNED))
+        second = B.activation_residual_quantize(v, r.scale, *UNSIGNED, B.params(*SIGNED, 128, 20))
+        off = B.mmse_scale_search_offset(v, p)
+        torch.cuda.synchronize()
+        o2 = oracle.can_act_residual_quantize(x, o["scale"], UNSIGNED, SIGNED, 128, 20)
+        oo = oracle.can_offset_search(x, 15, 128, 20)
+        assert (float(second.scale[0]), int(second.idx[0]), float(second.sse[0])) == (float(o2["scale"]), o2["idx"], o2["sse"])
+        np.testing.assert_array_equal(second.packed.cpu().numpy(), o2["packed"])
+        assert (float(off.scale[0]), int(off.idx[0]), float(off.sse[0]), float(off.delta[0])) == \
+            (float(oo["scale"]), oo["idx"], oo["sse"], float(oo["delta"]))
+        np.testing.assert_array_equal(off.packed.cpu().numpy(), oo["packed"])
