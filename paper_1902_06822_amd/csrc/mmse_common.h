@@ -9,7 +9,7 @@ namespace {
 
 
 constexpr int kChunk = 64;             // elements per sequential fp32 chunk
-constexpr int kMaxBatch = 32;          // tensors per launch (descriptor table lives in kernarg)
+constexpr int kMaxBatch = 40;          // tensors per launch: the descriptor table lives in kernarg (4 KB at most)
 constexpr int kTile = 8192;            // floats of one kernel staged in LDS at a time
 constexpr int kLevelsKW = 11;          // binary-counter levels for <= 1024 chunks (65536 elements)
 constexpr int kLevelsKWSmall = 8;      // ... for <= 128 chunks (8192 elements: one LDS tile)
@@ -47,6 +47,7 @@ struct Batch {
     int iters;
     float lo, hi;               // (float)qmin, (float)qmax
 };
+static_assert(sizeof(Batch) <= 4096, "the descriptor table must fit the kernel argument buffer");
 
 // ---------------------------------------------------------------------------------
 // element arithmetic
