@@ -363,9 +363,34 @@ __global__ void __launch_bounds__(256) k_act_reduce64(const ActBatch B, int leve
     out[(size_t)blockIdx.y * G + j] = v[0];
 }
 
+// Pairwise tree over `rows` (<= 64) values v[0], v[stride], ... as a 64-wide tree padded with zeros
+// (adding +0.0 to a sum changes nothing, so these are the bits of "a value without a partner is carried
+// up").  Four groups of 16 values, each loaded in one go so that the loads are in flight together.
+__device__ __forceinline__ double tree_rows64(const double* __restrict__ v, int rows, size_t stride)
+{
+    double g[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        double e[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) e[i] = (16 * q + i < rows) ? v[(size_t)(16 * q + i) * stride] : 0.0;
+#pragma unroll
+        for (int w = 1; w < 16; w <<= 1)
+#pragma unroll
+            for (int i = 0; i < 16; i += 2 * w) e[i] = e[i] + e[i + w];
+        g[q] = e[0];
+        if (16 * (q + 1) >= rows) {            // nothing but zeros beyond this group
+#pragma unroll
+            for (int r = 0; r < 4; ++r) if (r > q) g[r] = 0.0;
+            break;
+        }
+    }
+    return (g[0] + g[1]) + (g[2] + g[3]);
+}
+
 // Argmin over the G grid sums (one workgroup) and set-up of the refinement state.
-__global__ void __launch_bounds__(1024) k_act_argmin(const ActBatch B, const double* __restrict__ tot, int G, int qmax,
-                                                     int iters, const ActOut O)
+__global__ void __launch_bounds__(256) k_act_argmin(const ActBatch B, int level, const double* __restrict__ tot, int G,
+                                                     int qmax, int iters, const ActOut O)
 {
     __shared__ double s_bestE[16];
     __shared__ int s_bestJ[16];
@@ -374,7 +399,11 @@ __global__ void __launch_bounds__(1024) k_act_argmin(const ActBatch B, const dou
     float* scale = O.scale[blockIdx.x];
     int32_t* idx = O.idx[blockIdx.x];
     double* sse = O.sse[blockIdx.x];
-    tot += (size_t)blockIdx.x * G;                 // the last level holds one row per tensor
+    // the level handed over holds at most 64 rows per tensor: the last tree levels are taken here
+    int first = 0;
+    for (int u = 0; u < (int)blockIdx.x; ++u) first += act_rows(B.start[u + 1] - B.start[u], level);
+    const int rows = act_rows(B.start[blockIdx.x + 1] - B.start[blockIdx.x], level);
+    tot += (size_t)first * G;
     const float a = __uint_as_float(S->absmax_bits);
     if (!(a <= kHuge)) {
         if (tid == 0) {
@@ -387,7 +416,7 @@ __global__ void __launch_bounds__(1024) k_act_argmin(const ActBatch B, const dou
     double bE = __longlong_as_double(0x7ff0000000000000LL);
     int bJ = INT_MAX;
     for (int j = tid; j < G; j += blockDim.x) {
-        const double e = tot[j];
+        const double e = tree_rows64(tot + j, rows, (size_t)G);
         if (e < bE) { bE = e; bJ = j; }       // ascending j per thread: strict < keeps the lowest
     }
     wave_argmin(bE, bJ);
@@ -543,10 +572,12 @@ __global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, f
     }
 }
 
-// Last tree level(s) over <= 64 rows of per-scale sums, then the golden-section bookkeeping.
-__global__ void __launch_bounds__(64) k_act_finish(const ActBatch B, int level, const double* __restrict__ part, int iters,
-                                                   const ActOut O)
+// Last tree levels over <= 4096 rows of per-scale sums (groups of 64 rows, then the groups), then the
+// golden-section bookkeeping.  One workgroup per tensor; thread (g, p) owns group g of scale p.
+__global__ void __launch_bounds__(512) k_act_finish(const ActBatch B, int level, const double* __restrict__ part, int iters,
+                                                    const ActOut O)
 {
+    __shared__ double grp[64][kMaxProbes];
     __shared__ double vals[kMaxProbes];
     ActState* S = B.S + blockIdx.x;
     if (S->status != 0 || S->done) return;
@@ -556,17 +587,15 @@ __global__ void __launch_bounds__(64) k_act_finish(const ActBatch B, int level, 
     for (int u = 0; u < (int)blockIdx.x; ++u) first += act_rows(B.start[u + 1] - B.start[u], level);
     const int rows = act_rows(B.start[blockIdx.x + 1] - B.start[blockIdx.x], level);
     part += (size_t)first * kMaxProbes;
-    const int t = threadIdx.x;
-    if (t < kMaxProbes) {
-        double v[64];
-#pragma unroll
-        for (int i = 0; i < 64; ++i) v[i] = (i < rows && t < S->nprobe) ? part[(size_t)i * kMaxProbes + t] : 0.0;
-#pragma unroll
-        for (int w = 1; w < 64; w <<= 1)
-#pragma unroll
-            for (int i = 0; i < 64; i += 2 * w) v[i] = v[i] + v[i + w];
-        vals[t] = v[0];
+    const int t = threadIdx.x, g = t >> 3, pr = t & 7;
+    const int ngroups = (rows + 63) >> 6;
+    {
+        const int r0 = g * 64;
+        const int cnt = (g < ngroups && pr < S->nprobe) ? ((rows - r0) < 64 ? (rows - r0) : 64) : 0;
+        grp[g][pr] = tree_rows64(part + (size_t)r0 * kMaxProbes + pr, cnt, kMaxProbes);
     }
+    __syncthreads();
+    if (t < kMaxProbes) vals[t] = tree_rows64(&grp[0][t], ngroups, kMaxProbes);
     __syncthreads();
     if (t == 0) {
         act_advance(S, vals, iters);

@@ -248,8 +248,8 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
 struct ActPlan {
     int count;
     int start[kMaxActBatch + 1];   // first block of each tensor in the concatenated numbering
-    int levels;             // reduce64 stages of the grid sums until every tensor has one row
-    int plevels;            // reduce64 stages of the probe sums until every tensor has <= 64 rows
+    int levels;             // reduce64 stages of the grid sums until every tensor has <= 64 rows
+    int plevels;            // reduce64 stages of the probe sums until every tensor has <= 4096 rows
     int total_rows[8];      // rows of all tensors together at each level
     size_t off_part[8];     // byte offsets of the grid-sum levels ([rows][G] doubles)
     size_t off_probe[8];    // byte offsets of the probe levels ([rows][kMaxProbes] doubles)
@@ -267,8 +267,8 @@ ActPlan plan_activation(const long long* N, int count, int G)
         P.start[t + 1] = P.start[t] + nb;
         maxnb = nb > maxnb ? nb : maxnb;
     }
-    while (act_rows(maxnb, P.levels) > 1) ++P.levels;
-    while (act_rows(maxnb, P.plevels) > 64) ++P.plevels;
+    while (act_rows(maxnb, P.levels) > 64) ++P.levels;          // k_act_argmin takes the last <= 64 rows itself
+    while (act_rows(maxnb, P.plevels) > 4096) ++P.plevels;      // k_act_finish takes the last <= 4096 rows itself
     for (int l = 0; l <= P.levels; ++l) {
         int r = 0;
         for (int t = 0; t < count; ++t) r += act_rows(P.start[t + 1] - P.start[t], l);
@@ -781,8 +781,8 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     }
     {
         int threads = ((G + 63) / 64) * 64;
-        if (threads > 1024) threads = 1024;
-        hipLaunchKernelGGL(k_act_argmin, dim3(count), dim3(threads), 0, s, B,
+        if (threads > 256) threads = 256;
+        hipLaunchKernelGGL(k_act_argmin, dim3(count), dim3(threads), 0, s, B, P.levels,
                            reinterpret_cast<const double*>(ws + P.off_part[P.levels]), G, p->qmax, p->refine_iters, O);
         MMSE_CHECK_LAUNCH();
     }
@@ -796,7 +796,7 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
                                reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
             MMSE_CHECK_LAUNCH();
         }
-        hipLaunchKernelGGL(k_act_finish, dim3(count), dim3(64), 0, s, B, P.plevels,
+        hipLaunchKernelGGL(k_act_finish, dim3(count), dim3(512), 0, s, B, P.plevels,
                            reinterpret_cast<const double*>(ws + P.off_probe[P.plevels]), p->refine_iters, O);
         MMSE_CHECK_LAUNCH();
     }
