@@ -22,7 +22,7 @@
  *   - inputs must be finite.  A problem whose max |T| is below 2^-60 is coded
  *     as all-zero (scale 1, idx 0, sse = sum T^2); one whose max |T| exceeds
  *     2^60 or holds inf/NaN is rejected on the device: scale = NaN, idx = -1,
- *     sse = NaN for that problem, codes unspecified.
+ *     sse = NaN for that problem, its codes are written as zeros.
  *   - "sse" is the SUM of squared errors (the paper omits the mean factor,
  *     Section 3.2), accumulated as documented in csrc/mmse_kernels.hip.
  */
