@@ -244,6 +244,11 @@ int mmse_layer_error_sums(const double *const *sse_dev_ptrs_host, const int64_t 
 int mmse_grid_sse_kernelwise(const float *w_dev, int64_t K, int64_t n, const mmse_params_t *p,
                              float *absmax_dev, double *grid_sse_dev, void *stream);
 
+/* The same for an activation tensor: absmax_dev[0] = max_i |x_i|, grid_sse_dev[j] = f(alpha_j), j < G, summed over
+ * the whole tensor in the library's fixed order.  Workspace: mmse_workspace_bytes_activation(N, p). */
+int mmse_grid_sse_activation(const float *x_dev, int64_t N, const mmse_params_t *p, float *absmax_dev,
+                             double *grid_sse_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
 const char *mmse_status_string(int status);
 
 #ifdef __cplusplus

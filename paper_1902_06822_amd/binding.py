@@ -25,6 +25,7 @@ EXPORTS = (
     "mmse_workspace_bytes_dual_linesearch", "dual_line_search",
     "activation_residual_quantize", "mmse_scale_search_offset", "mmse_scale_alternating_kernelwise",
     "mmse_workspace_bytes_activation_batched", "mmse_scale_search_activation_batched", "mmse_layer_error_sums",
+    "mmse_grid_sse_activation",
     "mmse_status_string",
 )
 
@@ -91,6 +92,7 @@ def load_library() -> C.CDLL:
     lib.mmse_scale_search_activation_batched.argtypes = [C.POINTER(MmseActDesc), i32, C.POINTER(MmseParams), vp,
                                                          C.c_size_t, vp]
     lib.mmse_layer_error_sums.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_int64), i32, vp, vp]
+    lib.mmse_grid_sse_activation.argtypes = [vp, i64, pp, vp, vp, vp, C.c_size_t, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -502,3 +504,15 @@ class LayerSumsPlan:
 
 def mmse_layer_error_sums(sse_tensors: Sequence[torch.Tensor]) -> torch.Tensor:
     return LayerSumsPlan(sse_tensors).run()
+
+
+def mmse_grid_sse_activation(x: torch.Tensor, p: MmseParams):
+    """(absmax [1], f(alpha_j) [G]) of an activation tensor: the candidate sweep alone."""
+    _dev(x, torch.float32)
+    N = x.numel()
+    ws = alloc_workspace(mmse_workspace_bytes_activation(N, p), x.device)
+    absmax = torch.empty(1, dtype=torch.float32, device=x.device)
+    grid = torch.empty(p.grid_points, dtype=torch.float64, device=x.device)
+    _check(load_library().mmse_grid_sse_activation(x.data_ptr(), N, C.byref(p), absmax.data_ptr(), grid.data_ptr(),
+                                                   ws.data_ptr(), ws.numel(), _stream()), "mmse_grid_sse_activation")
+    return absmax, grid

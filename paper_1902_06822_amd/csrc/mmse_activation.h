@@ -28,6 +28,7 @@ struct ActState {
     float probes[kMaxProbes];
     double ec, ed, best;
     unsigned min_key, max_key;   // offset form: order-preserving keys of min and max
+    float out_scale; int out_idx; double out_sse;    // result slots for calls that only want the grid errors
     float delta;                 // offset form: min of the tensor
 };
 
@@ -390,7 +391,8 @@ __device__ __forceinline__ double tree_rows64(const double* __restrict__ v, int 
 
 // Argmin over the G grid sums (one workgroup) and set-up of the refinement state.
 __global__ void __launch_bounds__(256) k_act_argmin(const ActBatch B, int level, const double* __restrict__ tot, int G,
-                                                     int qmax, int iters, const ActOut O)
+                                                     int qmax, int iters, const ActOut O,
+                                                     float* absmax_out, double* grid_out)   // optional: [count], [count][G]
 {
     __shared__ double s_bestE[16];
     __shared__ int s_bestJ[16];
@@ -405,18 +407,22 @@ __global__ void __launch_bounds__(256) k_act_argmin(const ActBatch B, int level,
     const int rows = act_rows(B.start[blockIdx.x + 1] - B.start[blockIdx.x], level);
     tot += (size_t)first * G;
     const float a = __uint_as_float(S->absmax_bits);
+    if (tid == 0 && absmax_out) absmax_out[blockIdx.x] = a;
     if (!(a <= kHuge)) {
         if (tid == 0) {
             const float nanf_ = __uint_as_float(0x7fc00000u);
             S->status = 2; S->absmax = a;
             *scale = nanf_; *idx = -1; *sse = (double)nanf_;
         }
+        if (grid_out)
+            for (int j = tid; j < G; j += blockDim.x) grid_out[(size_t)blockIdx.x * G + j] = (double)__uint_as_float(0x7fc00000u);
         return;
     }
     double bE = __longlong_as_double(0x7ff0000000000000LL);
     int bJ = INT_MAX;
     for (int j = tid; j < G; j += blockDim.x) {
         const double e = tree_rows64(tot + j, rows, (size_t)G);
+        if (grid_out) grid_out[(size_t)blockIdx.x * G + j] = e;
         if (e < bE) { bE = e; bJ = j; }       // ascending j per thread: strict < keeps the lowest
     }
     wave_argmin(bE, bJ);

@@ -721,7 +721,8 @@ struct ActItem { const float* x; long long N; float* scale; int32_t* idx; double
 
 static int run_activation_group(const ActItem* items, int count, const mmse_params_t* p, int pre_mode,
                                 const float* scale1_dev, int qmin1, int qmax1, float* delta_dev,
-                                char* ws, const ActPlan& P, hipStream_t s)
+                                char* ws, const ActPlan& P, hipStream_t s,
+                                float* absmax_out = nullptr, double* grid_out = nullptr)
 {
     const int G = p->grid_points;
     ActBatch B{};
@@ -783,7 +784,8 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         int threads = ((G + 63) / 64) * 64;
         if (threads > 256) threads = 256;
         hipLaunchKernelGGL(k_act_argmin, dim3(count), dim3(threads), 0, s, B, P.levels,
-                           reinterpret_cast<const double*>(ws + P.off_part[P.levels]), G, p->qmax, p->refine_iters, O);
+                           reinterpret_cast<const double*>(ws + P.off_part[P.levels]), G, p->qmax, p->refine_iters, O,
+                           absmax_out, grid_out);
         MMSE_CHECK_LAUNCH();
     }
     for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
@@ -825,6 +827,25 @@ static int run_activation(const float* x_dev, int64_t N, const mmse_params_t* p,
     const ActItem item{x_dev, n1, scale_dev, idx_dev, sse_dev, packed_dev};
     return run_activation_group(&item, 1, p, pre_mode, scale1_dev, qmin1, qmax1, delta_dev,
                                 static_cast<char*>(ws_dev), P, static_cast<hipStream_t>(stream));
+}
+
+int mmse_grid_sse_activation(const float* x_dev, int64_t N, const mmse_params_t* p, float* absmax_dev,
+                             double* grid_sse_dev, void* ws_dev, size_t ws_bytes, void* stream)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (!x_dev || !absmax_dev || !grid_sse_dev) return MMSE_ERR_NULL;
+    if (N <= 0 || N > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
+    if (!aligned_to(x_dev, 4) || !aligned_to(absmax_dev, 4) || !aligned_to(grid_sse_dev, 8)) return MMSE_ERR_ALIGN;
+    const long long n1 = N;
+    mmse_params_t q = *p;
+    q.refine_iters = 0;
+    const ActPlan P = plan_activation(&n1, 1, q.grid_points);
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < P.bytes) return MMSE_ERR_WORKSPACE;
+    ActState* S = reinterpret_cast<ActState*>(ws_dev);
+    const ActItem item{x_dev, n1, &S->out_scale, &S->out_idx, &S->out_sse, nullptr};   // the search results stay in the workspace
+    return run_activation_group(&item, 1, &q, 0, nullptr, 0, 0, nullptr, static_cast<char*>(ws_dev), P,
+                                static_cast<hipStream_t>(stream), absmax_dev, grid_sse_dev);
 }
 
 int mmse_scale_search_activation_batched(const mmse_act_desc_t* descs_host, int32_t count, const mmse_params_t* p,

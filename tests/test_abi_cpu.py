@@ -136,6 +136,10 @@ def test_entry_points_validate_before_enqueue(B):
     assert lib.mmse_layer_error_sums(ptrs, (C.c_int64 * 2)(5, 0), 2, a, None) == -2
     assert lib.mmse_layer_error_sums((C.c_void_p * 2)(a, a + 4), ks, 2, a, None) == -6
     assert lib.mmse_layer_error_sums((C.c_void_p * 2)(a, None), ks, 2, a, None) == -1
+    assert lib.mmse_grid_sse_activation(a, 64, C.byref(pu), None, a, a, 1 << 20, None) == -1
+    assert lib.mmse_grid_sse_activation(a, 64, C.byref(pu), a, a + 4, a, 1 << 20, None) == -6
+    assert lib.mmse_grid_sse_activation(a, 0, C.byref(pu), a, a, a, 1 << 20, None) == -2
+    assert lib.mmse_grid_sse_activation(a, 64, C.byref(pu), a, a, a, 64, None) == -4
     # sizes
     assert lib.mmse_scale_search_kernelwise(a, 0, 4, C.byref(p), a, a, a, a, 4096, None) == -2
     assert lib.mmse_scale_search_kernelwise(a, 4, 65537, C.byref(p), a, a, a, a, 4096, None) == -2

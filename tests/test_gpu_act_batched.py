@@ -139,3 +139,32 @@ def test_activation_tensors_at_odd_addresses(B):
         assert (float(off.scale[0]), int(off.idx[0]), float(off.sse[0]), float(off.delta[0])) == \
             (float(oo["scale"]), oo["idx"], oo["sse"], float(oo["delta"]))
         np.testing.assert_array_equal(off.packed.cpu().numpy(), oo["packed"])
+
+
+@pytest.mark.parametrize("N,G,q", [(1, 4, UNSIGNED), (4097, 64, UNSIGNED), (100001, 500, UNSIGNED), (300000, 1024, SIGNED),
+                                   (1000003, 128, UNSIGNED)])
+def test_every_grid_error_of_an_activation_tensor(B, N, G, q):
+    """The candidate sweep by itself: f(alpha_j) for every j, against the oracle's, bit for bit."""
+    import torch
+    say(f"activation grid errors N={N} G={G}")
+    x = synth.acts_relu_student_t(N, 4000 + G)
+    if q[0] < 0:
+        x = (x - np.float32(0.5)).astype(np.float32)
+    absmax, grid = B.mmse_grid_sse_activation(dev(x), B.params(*q, G, 0))
+    torch.cuda.synchronize()
+    o = oracle.can_search(x, *q, G, 0, want_grid=True)
+    assert float(absmax[0]) == float(oracle.can_absmax(x))
+    np.testing.assert_array_equal(grid.cpu().numpy(), o["grid_sse"])
+    assert int(np.argmin(o["grid_sse"])) == o["idx"]
+
+
+def test_grid_errors_of_degenerate_activation_tensors(B):
+    import torch
+    z = np.zeros(5000, np.float32)
+    a, g = B.mmse_grid_sse_activation(dev(z), B.params(*UNSIGNED, 16, 0))
+    torch.cuda.synchronize()
+    assert float(a[0]) == 0.0 and np.all(g.cpu().numpy() == 0.0)
+    z[17] = np.nan
+    a, g = B.mmse_grid_sse_activation(dev(z), B.params(*UNSIGNED, 16, 0))
+    torch.cuda.synchronize()
+    assert np.isnan(float(a[0])) and np.all(np.isnan(g.cpu().numpy()))

@@ -103,6 +103,12 @@ def test_full_size_activation_tensors(B, cfg, which):
     check_equal(r, np.array([o["scale"]], np.float32), np.array([o["idx"]], np.int32), np.array([o["sse"]]),
                 f"cfg{cfg} act {li}")
     np.testing.assert_array_equal(packed.cpu().numpy(), oracle.can_quantize_pack_int4(x, [o["scale"]], *UNSIGNED))
+    if which == "largest":       # every grid error of the full-size tensor
+        amax, grid = B.mmse_grid_sse_activation(xd, B.params(*UNSIGNED, c.grid_points, 0))
+        torch.cuda.synchronize()
+        og = oracle.can_search(x, *UNSIGNED, c.grid_points, 0, want_grid=True)
+        np.testing.assert_array_equal(grid.cpu().numpy(), og["grid_sse"], err_msg=f"cfg{cfg} act {li} grid errors")
+        assert float(amax[0]) == float(x.max())
     # invariant that holds at any size: the result is no worse than the max-abs scale
     assert float(r.sse[0]) <= oracle.can_sse(x, np.float32(x.max()) / np.float32(15), *UNSIGNED)
 
