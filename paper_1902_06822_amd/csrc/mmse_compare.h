@@ -94,7 +94,7 @@ __global__ void __launch_bounds__(256) k_alt_kernelwise(const float* __restrict_
         __syncthreads();
         const int stop = s_stop;
         if (!stop) { alpha = s_alpha; upd = it + 1; }
-        __syncthreads();                   // s_stop, s_alpha and s_den are rewritten in the next round
+        __syncthreads();                   // s_stop, s_alpha and s_den are rewritten by the next iteration
         if (stop) break;
     }
     {
