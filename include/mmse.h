@@ -171,7 +171,8 @@ int dual_quantize_alternating(const float *w_dev, int64_t K, int64_t n, const mm
                               double *sse_dev, int32_t *sweeps_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
 /* The same for `count` layers described in HOST memory; every phi runs as one batched launch over
- * all layers.  Workspace: mmse_workspace_bytes_dual_batched (the sum of the per-layer sizes). */
+ * all layers.  Workspace: mmse_workspace_bytes_dual_batched (the sum of the per-layer sizes).  count in
+ * 1..4096 and sum K <= MMSE_MAX_TENSOR_ELEMS, else MMSE_ERR_SIZE. */
 int mmse_workspace_bytes_dual_batched(const mmse_dual_desc_t *descs_host, int32_t count,
                                       const mmse_params_t *p, size_t *bytes_out);
 int dual_quantize_alternating_batched(const mmse_dual_desc_t *descs_host, int32_t count, const mmse_params_t *p,
@@ -206,7 +207,8 @@ int mmse_scale_alternating_kernelwise(const float *w_dev, int64_t K, int64_t n, 
 /* Whole network in a handful of launches: `count` weight tensors described in HOST
  * memory (the descriptors are consumed before the call returns).  Semantics per
  * tensor are those of mmse_scale_search_kernelwise / residual_quantize /
- * quantize_pack_int4.  Workspace: mmse_workspace_bytes_kernelwise(sum K, ...). */
+ * quantize_pack_int4.  Workspace: mmse_workspace_bytes_kernelwise(sum K, ...).  count in 1..4096 and
+ * sum K <= MMSE_MAX_TENSOR_ELEMS, else MMSE_ERR_SIZE. */
 int mmse_scale_search_batched(const mmse_tensor_desc_t *descs_host, int32_t count,
                               const mmse_params_t *p, void *ws_dev, size_t ws_bytes, void *stream);
 

@@ -387,6 +387,7 @@ int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t coun
         if (rc) return rc;
         sumK += descs_host[i].K;
     }
+    if (sumK > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;     // one workgroup per kernel: a launch grid must hold them
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < round256((size_t)sumK * sizeof(float)))
         return MMSE_ERR_WORKSPACE;
     Item* items = new Item[count]();       // value-initialised: every optional pointer starts as nullptr
@@ -481,6 +482,7 @@ int dual_quantize_alternating_batched(const mmse_dual_desc_t* descs_host, int32_
     if (count <= 0 || count > 4096) return MMSE_ERR_SIZE;
     if (!(eps >= 0.0) || max_sweeps < 1 || max_sweeps > 64) return MMSE_ERR_PARAMS;
     size_t need = 0;
+    long long sumK = 0;
     for (int i = 0; i < count; ++i) {
         const mmse_dual_desc_t& d = descs_host[i];
         if (!d.w_dev || !d.scale1_dev || !d.scale2_dev || !d.packed1_dev || !d.packed2_dev || !d.sse_dev || !d.sweeps_dev)
@@ -490,7 +492,9 @@ int dual_quantize_alternating_batched(const mmse_dual_desc_t* descs_host, int32_
             !aligned_to(d.sse_dev, 8) || !aligned_to(d.sweeps_dev, 4))
             return MMSE_ERR_ALIGN;
         need += plan_dual(d.K, d.n).bytes;
+        sumK += d.K;
     }
+    if (sumK > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < need) return MMSE_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
