@@ -208,6 +208,20 @@ def acts_relu_normal(N: int, seed: int) -> np.ndarray:
     return _fill_blocks(N, lambda r, m: np.maximum(r.normal(0.0, 1.0, m), 0.0), seed)
 
 
+def tiled_normal(N: int, seed: int, period: int = 16_000_057, relu: bool = False) -> np.ndarray:
+    """N(0,1) values (optionally through ReLU) repeated with an odd period: fills the very large tensors of
+    the maximum-size cases in seconds.  The period shares no factor with any power of two, so data
+    addressed 2^k elements away from where it should be never looks the same."""
+    base = np.random.default_rng(seed).standard_normal(period).astype(np.float32)
+    if relu:
+        base = np.maximum(base, np.float32(0.0))
+    out = np.empty(N, dtype=np.float32)
+    for s in range(0, N, period):
+        e = min(N, s + period)
+        out[s:e] = base[:e - s]
+    return out
+
+
 def acts_relu_student_t(N: int, seed: int, nu: float = 5.0) -> np.ndarray:
     """ReLU(Student-t(nu)) (config 4)."""
     return _fill_blocks(N, lambda r, m: np.maximum(r.standard_t(nu, m), 0.0), seed)

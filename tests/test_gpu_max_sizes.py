@@ -1,0 +1,81 @@
+"""GPU parity at the largest sizes the C ABI accepts (MMSE_MAX_TENSOR_ELEMS elements in one activation
+tensor; K * n just below it with the longest kernel, MMSE_MAX_KERNEL_ELEMS): every index past 2^31 bytes and
+every block number near 2^19 is exercised.  Scales, indices and errors are compared completely; the codes on
+windows at the start, around the middle and at the ragged end (a window is coded exactly as in a full run)."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1902_06822_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1902_06822_amd import binding
+    binding.load_library()
+    return binding
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def test_activation_tensor_of_maximum_size(B):
+    import torch
+    N = 2 ** 31 - 1
+    G, iters = 32, 2
+    say(f"activation tensor of {N} elements, G={G}, {iters} refinement iterations")
+    x = synth.tiled_normal(N, 190206822 + 9001, relu=True)
+    x[N - 3] = np.float32(9.5)                       # the abs-max sits in the last, partial block
+    xd = torch.from_numpy(x).cuda()
+    p = B.params(0, 15, G, iters)
+    r = B.mmse_scale_search_activation(xd, p)
+    packed = B.quantize_pack_int4(xd, r.scale, 0, 15)
+    torch.cuda.synchronize()
+    say("oracle")
+    o = oracle.can_search(x, 0, 15, G, iters)
+    assert int(r.idx.cpu()[0]) == o["idx"]
+    assert float(r.scale.cpu()[0]) == float(o["scale"])
+    assert float(r.sse.cpu()[0]) == o["sse"]
+    assert packed.numel() == (N + 1) // 2
+    s = np.array([o["scale"]], np.float32)
+    for start, length in ((0, 70000), (2 ** 30 - 5000, 10000), (2 ** 31 - 2 ** 24 - 2, 12346), (N - 65537, 65537)):
+        assert start % 2 == 0
+        ref = oracle.can_quantize_pack_int4(x[start:start + length].reshape(1, -1), s, 0, 15)
+        got = packed[start // 2:start // 2 + ref.size].cpu().numpy()
+        np.testing.assert_array_equal(got, ref, err_msg=f"codes from element {start}")
+    del xd, packed
+    torch.cuda.empty_cache()
+
+
+def test_weight_tensor_of_maximum_size(B):
+    import torch
+    K, n = 32767, 65536                              # K * n = 2 147 418 112, the longest kernel the ABI takes
+    G, iters = 16, 1
+    say(f"weight tensor {K} x {n}, G={G}, {iters} refinement iteration")
+    w = synth.tiled_normal(K * n, 190206822 + 9002).reshape(K, n)
+    w *= np.float32(0.05)
+    wd = torch.from_numpy(w).cuda()
+    p = B.params(-8, 7, G, iters)
+    res = B.mmse_scale_search_batched([wd], p, want_packed=True)[0]
+    torch.cuda.synchronize()
+    say("oracle")
+    s, j, e = oracle.can_search_kernelwise(w, -8, 7, G, iters)
+    np.testing.assert_array_equal(res.idx.cpu().numpy(), j)
+    np.testing.assert_array_equal(res.scale.cpu().numpy(), s)
+    np.testing.assert_array_equal(res.sse.cpu().numpy(), e)
+    assert res.packed.numel() == K * n // 2
+    for k0 in (0, K // 2, 16384, K - 2):             # row 16384 starts at byte 2^29, element 2^30
+        ref = oracle.can_quantize_pack_int4(w[k0:k0 + 2], s[k0:k0 + 2], -8, 7)
+        got = res.packed[k0 * n // 2:(k0 + 2) * n // 2].cpu().numpy()
+        np.testing.assert_array_equal(got, ref, err_msg=f"codes of kernels {k0}, {k0 + 1}")
+    del wd, res
+    torch.cuda.empty_cache()
