@@ -48,7 +48,8 @@ def compare(B, w, q, G1, G2, tag, want_grid=False):
     (40, 9, "outliers", 16, 16), (12, 27, "normal", 32, 32), (9, 147, "laplace", 20, 70),
     (8, 576, "laplace", 24, 64), (3, 1152, "student", 16, 24), (2, 4608, "laplace", 8, 12),
     (5, 64, "normal", 32, 16), (7, 130, "laplace", 5, 130), (1, 8192, "normal", 4, 6),
-    (600, 9, "normal", 12, 8), (3, 7, "outliers", 1, 1), (4, 63, "student", 64, 1), (4, 65, "student", 1, 64)])
+    (600, 9, "normal", 12, 8), (3, 7, "outliers", 1, 1), (4, 63, "student", 64, 1), (4, 65, "student", 1, 64),
+    (2, 64, "normal", 1024, 3), (2, 70, "laplace", 3, 1024), (16, 9, "normal", 1024, 1024)])   # the largest grids
 def test_dual_line_search_matches_oracle(B, K, n, kind, G1, G2):
     say(f"dual line search K={K} n={n} {kind} G1={G1} G2={G2}")
     w = synth.small_weights(K, n, 9100 + K + n, kind)

@@ -79,3 +79,37 @@ def test_weight_tensor_of_maximum_size(B):
         np.testing.assert_array_equal(got, ref, err_msg=f"codes of kernels {k0}, {k0 + 1}")
     del wd, res
     torch.cuda.empty_cache()
+
+
+def test_batched_calls_with_the_most_tensors(B):
+    """4096 weight tensors and 1024 activation tensors in one call each: the largest descriptor tables
+    (103 and 16 launch groups)."""
+    import torch
+    say("batched weights: 4096 tensors")
+    rng = np.random.default_rng(190206822 + 9003)
+    ws = []
+    for i in range(4096):
+        K, n = int(rng.integers(1, 4)), int(rng.choice([1, 9, 27, 64, 65, 130, 576]))
+        ws.append(synth.small_weights(K, n, 40000 + i, ("laplace", "normal", "student", "outliers")[i % 4]))
+    p = B.params(-8, 7, 40, 6)
+    res = B.mmse_scale_search_batched([torch.from_numpy(w).cuda() for w in ws], p, want_packed=True)
+    torch.cuda.synchronize()
+    for i, (w, r) in enumerate(zip(ws, res)):
+        s, j, e = oracle.can_search_kernelwise(w, -8, 7, 40, 6)
+        np.testing.assert_array_equal(r.idx.cpu().numpy(), j, err_msg=f"idx of tensor {i}")
+        np.testing.assert_array_equal(r.scale.cpu().numpy(), s, err_msg=f"scale of tensor {i}")
+        np.testing.assert_array_equal(r.sse.cpu().numpy(), e, err_msg=f"sse of tensor {i}")
+        np.testing.assert_array_equal(r.packed.cpu().numpy(), oracle.can_quantize_pack_int4(w, s, -8, 7),
+                                      err_msg=f"codes of tensor {i}")
+    say("batched activations: 1024 tensors")
+    xs = [synth.acts_relu_normal(int(rng.integers(1, 9000)), 50000 + i) for i in range(1024)]
+    pa = B.params(0, 15, 48, 5)
+    res = B.mmse_scale_search_activation_batched([torch.from_numpy(x).cuda() for x in xs], pa)
+    torch.cuda.synchronize()
+    for i, (x, r) in enumerate(zip(xs, res)):
+        o = oracle.can_search(x, 0, 15, 48, 5)
+        assert int(r.idx.cpu()[0]) == o["idx"] and float(r.scale.cpu()[0]) == float(o["scale"]), i
+        assert float(r.sse.cpu()[0]) == o["sse"], i
+        np.testing.assert_array_equal(r.packed.cpu().numpy(),
+                                      oracle.can_quantize_pack_int4(x, np.array([o["scale"]], np.float32), 0, 15),
+                                      err_msg=f"codes of activation tensor {i}")
