@@ -53,6 +53,12 @@ def test_dual_alternating_matches_oracle(B, K, n, kind, max_sweeps, eps):
     run_and_compare(B, w, 128, 20, eps, max_sweeps, f"K={K} n={n}")
 
 
+def test_dual_alternating_with_the_most_sweeps(B):
+    say("dual: 64 sweeps allowed, no tolerance")
+    run_and_compare(B, synth.small_weights(12, 147, 611, "laplace"), 64, 8, 0.0, 64, "64 sweeps")
+    run_and_compare(B, synth.small_weights(30, 9, 612, "outliers"), 32, 64, 0.0, 64, "64 sweeps, 64 refinement iterations")
+
+
 def test_dual_alternating_coarse_grid_discards_worse_sweeps(B):
     say("dual coarse grid")
     for seed, (K, n, G, kind) in enumerate(((6, 27, 8, "normal"), (6, 9, 8, "outliers"), (4, 64, 16, "laplace"),
