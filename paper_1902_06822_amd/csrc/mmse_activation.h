@@ -340,14 +340,15 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
 
 // One tree stage over blocks: out[g][j] = pairwise sum of in[64g .. 64g+63][j].
 // When a stage leaves a single row and fin != nullptr the caller continues with it.
-// Output row blockIdx.y of level `level` belongs to one tensor; its inputs are that tensor's rows of level - 1.
+// Output row blockIdx.x of level `level` belongs to one tensor; its inputs are that tensor's rows of level - 1.
+// (Rows on the x axis of the grid: a batch of large tensors has more than 65535 of them.)
 __global__ void __launch_bounds__(256) k_act_reduce64(const ActBatch B, int level, const double* __restrict__ in, int G,
                                                       double* __restrict__ out)
 {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int j = blockIdx.y * blockDim.x + threadIdx.x;
     int first, below;
-    const int t = act_find_level(B, level, blockIdx.y, first, below);
-    const int g = blockIdx.y - first;                                   // group of 64 input rows inside the tensor
+    const int t = act_find_level(B, level, blockIdx.x, first, below);
+    const int g = blockIdx.x - first;                                   // group of 64 input rows inside the tensor
     const int rows = act_rows(B.start[t + 1] - B.start[t], level - 1);
     if (j >= G) return;
     in += (size_t)below * G;
@@ -361,7 +362,7 @@ __global__ void __launch_bounds__(256) k_act_reduce64(const ActBatch B, int leve
     for (int w = 1; w < 64; w <<= 1)
 #pragma unroll
         for (int i = 0; i < 64; i += 2 * w) v[i] = v[i] + v[i + w];
-    out[(size_t)blockIdx.y * G + j] = v[0];
+    out[(size_t)blockIdx.x * G + j] = v[0];
 }
 
 // Pairwise tree over `rows` (<= 64) values v[0], v[stride], ... as a 64-wide tree padded with zeros

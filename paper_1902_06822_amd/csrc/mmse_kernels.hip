@@ -779,7 +779,7 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         MMSE_CHECK_LAUNCH();
     }
     for (int l = 0; l < P.levels; ++l) {
-        hipLaunchKernelGGL(k_act_reduce64, dim3((G + 255) / 256, P.total_rows[l + 1]), dim3(256), 0, s, B, l + 1,
+        hipLaunchKernelGGL(k_act_reduce64, dim3(P.total_rows[l + 1], (G + 255) / 256), dim3(256), 0, s, B, l + 1,
                            reinterpret_cast<const double*>(ws + P.off_part[l]), G,
                            reinterpret_cast<double*>(ws + P.off_part[l + 1]));
         MMSE_CHECK_LAUNCH();
@@ -797,7 +797,7 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
                            reinterpret_cast<double*>(ws + P.off_probe[0]), pre);
         MMSE_CHECK_LAUNCH();
         for (int l = 0; l < P.plevels; ++l) {
-            hipLaunchKernelGGL(k_act_reduce64, dim3(1, P.total_rows[l + 1]), dim3(64), 0, s, B, l + 1,
+            hipLaunchKernelGGL(k_act_reduce64, dim3(P.total_rows[l + 1], 1), dim3(64), 0, s, B, l + 1,
                                reinterpret_cast<const double*>(ws + P.off_probe[l]), kMaxProbes,
                                reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
             MMSE_CHECK_LAUNCH();

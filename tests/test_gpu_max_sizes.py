@@ -113,3 +113,29 @@ def test_batched_calls_with_the_most_tensors(B):
         np.testing.assert_array_equal(r.packed.cpu().numpy(),
                                       oracle.can_quantize_pack_int4(x, np.array([o["scale"]], np.float32), 0, 15),
                                       err_msg=f"codes of activation tensor {i}")
+
+
+def test_batched_activations_with_more_than_65535_block_groups(B):
+    """64 tensors of about 65 536 blocks each in one launch group: 4.2 M blocks, 65 536 rows after the first
+    tree stage (more than a grid's y axis holds).  The tensors are views of one buffer with four different
+    lengths, so the oracle has four problems to solve."""
+    import torch
+    base_n = 2 ** 28
+    say(f"64 activation tensors of about {base_n} elements in one batched call")
+    x = synth.tiled_normal(base_n, 190206822 + 9004, relu=True)
+    lengths = [base_n, base_n - 1, base_n - 4097, base_n - 60000]
+    assert sum(((n + 4095) // 4096 + 63) // 64 for n in lengths) * 16 == 65536      # rows after one tree stage
+    xd = torch.from_numpy(x).cuda()
+    G, iters = 4, 1
+    p = B.params(0, 15, G, iters)
+    res = B.mmse_scale_search_activation_batched([xd[:lengths[i % 4]] for i in range(64)], p, want_packed=False)
+    torch.cuda.synchronize()
+    say("oracle")
+    ref = [oracle.can_search(x[:n], 0, 15, G, iters) for n in lengths]
+    for i, r in enumerate(res):
+        o = ref[i % 4]
+        assert int(r.idx.cpu()[0]) == o["idx"], i
+        assert float(r.scale.cpu()[0]) == float(o["scale"]), i
+        assert float(r.sse.cpu()[0]) == o["sse"], i
+    del xd, res
+    torch.cuda.empty_cache()
