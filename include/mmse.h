@@ -51,6 +51,7 @@ typedef enum mmse_status_t {
 #define MMSE_MAX_GRID_POINTS 2048        /* G                                           */
 #define MMSE_MAX_REFINE_ITERS 64
 #define MMSE_MAX_TENSOR_ELEMS 2147483647 /* K*n and N                                   */
+#define MMSE_MAX_KERNELS 4194304         /* K of one weight tensor (quantize_pack_int4: any K) */
 #define MMSE_MAX_BATCH_TENSORS 1024      /* activation tensors of one batched call      */
 
 /* Search parameters.
@@ -172,7 +173,7 @@ int dual_quantize_alternating(const float *w_dev, int64_t K, int64_t n, const mm
 
 /* The same for `count` layers described in HOST memory; every phi runs as one batched launch over
  * all layers.  Workspace: mmse_workspace_bytes_dual_batched (the sum of the per-layer sizes).  count in
- * 1..4096 and sum K <= MMSE_MAX_TENSOR_ELEMS, else MMSE_ERR_SIZE. */
+ * 1..4096, else MMSE_ERR_SIZE. */
 int mmse_workspace_bytes_dual_batched(const mmse_dual_desc_t *descs_host, int32_t count,
                                       const mmse_params_t *p, size_t *bytes_out);
 int dual_quantize_alternating_batched(const mmse_dual_desc_t *descs_host, int32_t count, const mmse_params_t *p,
@@ -207,8 +208,8 @@ int mmse_scale_alternating_kernelwise(const float *w_dev, int64_t K, int64_t n, 
 /* Whole network in a handful of launches: `count` weight tensors described in HOST
  * memory (the descriptors are consumed before the call returns).  Semantics per
  * tensor are those of mmse_scale_search_kernelwise / residual_quantize /
- * quantize_pack_int4.  Workspace: mmse_workspace_bytes_kernelwise(sum K, ...).  count in 1..4096 and
- * sum K <= MMSE_MAX_TENSOR_ELEMS, else MMSE_ERR_SIZE. */
+ * quantize_pack_int4.  Workspace: mmse_workspace_bytes_kernelwise(sum K, ...).  count in 1..4096, else
+ * MMSE_ERR_SIZE. */
 int mmse_scale_search_batched(const mmse_tensor_desc_t *descs_host, int32_t count,
                               const mmse_params_t *p, void *ws_dev, size_t ws_bytes, void *stream);
 

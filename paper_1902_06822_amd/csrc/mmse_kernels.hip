@@ -53,6 +53,12 @@ namespace {
 // ---------------------------------------------------------------------------------
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// A launch holds at most 2^32 - 1 work-items.  Workgroups have up to 512 threads where their count follows the
+// number of kernels or blocks (1024 only for kernels of more than 32768 elements, of which a tensor has fewer
+// than 65536), so launches are cut at this many workgroups.
+constexpr long long kMaxLaunchWG = 1LL << 22;
+static_assert(kMaxLaunchWG == MMSE_MAX_KERNELS, "one workgroup per kernel");
+
 int check_params(const mmse_params_t* p)
 {
     if (!p) return MMSE_ERR_NULL;
@@ -81,7 +87,7 @@ int check_tensor(const mmse_tensor_desc_t& d, bool need_outputs)
     if (!d.w_dev) return MMSE_ERR_NULL;
     if (need_outputs && (!d.scale_dev || !d.idx_dev || !d.sse_dev)) return MMSE_ERR_NULL;
     if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS) return MMSE_ERR_SIZE;
-    if (d.K > MMSE_MAX_TENSOR_ELEMS / d.n) return MMSE_ERR_SIZE;
+    if (d.K > MMSE_MAX_TENSOR_ELEMS / d.n || d.K > MMSE_MAX_KERNELS) return MMSE_ERR_SIZE;
     if (!aligned_to(d.w_dev, 4) || !aligned_to(d.scale_dev, 4) || !aligned_to(d.idx_dev, 4) ||
         !aligned_to(d.sse_dev, 8) || !aligned_to(d.scale1_dev, 4))
         return MMSE_ERR_ALIGN;
@@ -167,9 +173,11 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
                 const TensorArgs& a = items[i].a;
                 const bool small = small_ok && a.n <= kChunk;
                 if (small != (pass == 1)) continue;
+                const int add = pass == 0 ? a.K : (a.K + 3) / 4;
+                if (nb > 0 && wg + (long long)add > kMaxLaunchWG) { const int rc = flush(); if (rc) return rc; }
                 B.t[nb] = a;
                 B.start[nb] = wg;
-                wg += pass == 0 ? a.K : (a.K + 3) / 4;
+                wg += add;
                 const int npad = (a.n + kChunk - 1) & ~(kChunk - 1);
                 max_npad = npad > max_npad ? npad : max_npad;
                 if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
@@ -204,10 +212,12 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
                     if (c != cls) continue;
                     const int lanes = cls == 0 ? 1 : m;
                     const int cpw = threads / lanes;
+                    const int add = (a.K + cpw - 1) / cpw;
+                    if (nb > 0 && wg + (long long)add > kMaxLaunchWG) { const int rc = flush(); if (rc) return rc; }
                     B.t[nb] = a;
                     if (a.n & 1) B.t[nb].packed = nullptr;     // odd n: bytes straddle kernels, k_pack_int4 does those
                     B.start[nb] = wg;
-                    wg += (a.K + cpw - 1) / cpw;
+                    wg += add;
                     if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
                 }
                 const int rc = flush();
@@ -234,9 +244,11 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
             if (do_search && p->refine_iters > 0 && (a.n & 1) == 0) continue;   // coded by the refinement kernel
             const long long total = (long long)a.K * a.n;
             const long long per_wg = (long long)kPackThreads * kPackPerThread;
+            const int add = (int)((total + per_wg - 1) / per_wg);
+            if (nb > 0 && wg + (long long)add > kMaxLaunchWG) { const int rc = flush(); if (rc) return rc; }
             B.t[nb] = a;
             B.start[nb] = wg;
-            wg += (int)((total + per_wg - 1) / per_wg);
+            wg += add;
             if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
         }
         const int rc = flush();
@@ -286,6 +298,23 @@ int refine_passes(int iters)
 {
     if (iters <= 0) return 0;
     return 1 + (iters > 2 ? (iters - 2 + 2) / 3 : 0);
+}
+
+// The tensors of a batched activation call are searched in launch groups: at most kMaxActBatch tensors and at
+// most kMaxLaunchWG blocks each (one tensor alone has at most 2^19 blocks).  Returns how many tensors the group
+// that starts at tensor `first` takes; N_of(i) is the size of tensor i.
+template <class SizeOf>
+int act_group_size(int first, int count, SizeOf N_of)
+{
+    int m = 0;
+    long long blocks = 0;
+    while (first + m < count && m < kMaxActBatch) {
+        const long long nb = ((long long)N_of(first + m) + kBlockElems - 1) / kBlockElems;
+        if (m > 0 && blocks + nb > kMaxLaunchWG) break;
+        blocks += nb;
+        ++m;
+    }
+    return m;
 }
 
 struct DualPlan {           // workspace of dual_quantize_alternating, byte offsets
@@ -360,15 +389,15 @@ int mmse_workspace_bytes_activation_batched(const int64_t* N_host, int32_t count
     const int rc = check_params(p);
     if (rc) return rc;
     if (count <= 0 || count > MMSE_MAX_BATCH_TENSORS) return MMSE_ERR_SIZE;
+    for (int i = 0; i < count; ++i)
+        if (N_host[i] <= 0 || N_host[i] > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
     size_t total = 0;
-    for (int g0 = 0; g0 < count; g0 += kMaxActBatch) {
+    for (int g0 = 0; g0 < count;) {
+        const int m = act_group_size(g0, count, [&](int i) { return N_host[i]; });
         long long n[kMaxActBatch];
-        const int m = (count - g0) < kMaxActBatch ? (count - g0) : kMaxActBatch;
-        for (int i = 0; i < m; ++i) {
-            if (N_host[g0 + i] <= 0 || N_host[g0 + i] > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
-            n[i] = N_host[g0 + i];
-        }
+        for (int i = 0; i < m; ++i) n[i] = N_host[g0 + i];
         total += plan_activation(n, m, p->grid_points).bytes;
+        g0 += m;
     }
     *bytes_out = total;
     return MMSE_OK;
@@ -387,7 +416,6 @@ int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t coun
         if (rc) return rc;
         sumK += descs_host[i].K;
     }
-    if (sumK > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;     // one workgroup per kernel: a launch grid must hold them
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < round256((size_t)sumK * sizeof(float)))
         return MMSE_ERR_WORKSPACE;
     Item* items = new Item[count]();       // value-initialised: every optional pointer starts as nullptr
@@ -468,7 +496,7 @@ int mmse_workspace_bytes_dual(int64_t K, int64_t n, const mmse_params_t* p, size
     if (!bytes_out) return MMSE_ERR_NULL;
     const int rc = check_params(p);
     if (rc) return rc;
-    if (K <= 0 || n <= 0 || n > MMSE_MAX_KERNEL_ELEMS || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (K <= 0 || n <= 0 || n > MMSE_MAX_KERNEL_ELEMS || K > MMSE_MAX_TENSOR_ELEMS / n || K > MMSE_MAX_KERNELS) return MMSE_ERR_SIZE;
     *bytes_out = plan_dual(K, n).bytes;
     return MMSE_OK;
 }
@@ -482,19 +510,16 @@ int dual_quantize_alternating_batched(const mmse_dual_desc_t* descs_host, int32_
     if (count <= 0 || count > 4096) return MMSE_ERR_SIZE;
     if (!(eps >= 0.0) || max_sweeps < 1 || max_sweeps > 64) return MMSE_ERR_PARAMS;
     size_t need = 0;
-    long long sumK = 0;
     for (int i = 0; i < count; ++i) {
         const mmse_dual_desc_t& d = descs_host[i];
         if (!d.w_dev || !d.scale1_dev || !d.scale2_dev || !d.packed1_dev || !d.packed2_dev || !d.sse_dev || !d.sweeps_dev)
             return MMSE_ERR_NULL;
-        if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS || d.K > MMSE_MAX_TENSOR_ELEMS / d.n) return MMSE_ERR_SIZE;
+        if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS || d.K > MMSE_MAX_TENSOR_ELEMS / d.n || d.K > MMSE_MAX_KERNELS) return MMSE_ERR_SIZE;
         if (!aligned_to(d.w_dev, 4) || !aligned_to(d.scale1_dev, 4) || !aligned_to(d.scale2_dev, 4) ||
             !aligned_to(d.sse_dev, 8) || !aligned_to(d.sweeps_dev, 4))
             return MMSE_ERR_ALIGN;
         need += plan_dual(d.K, d.n).bytes;
-        sumK += d.K;
     }
-    if (sumK > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < need) return MMSE_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
@@ -538,29 +563,34 @@ int dual_quantize_alternating_batched(const mmse_dual_desc_t* descs_host, int32_
     };
     // bookkeeping kernels over all tensors: kind 0 init, 1 accept, 2 copy codes
     auto book = [&](int kind) -> int {
-        for (int b0 = 0; b0 < count; b0 += kMaxDualBatch) {
+        int b0 = 0;
+        while (b0 < count) {
             DualBatch D{};
             D.eps = eps;
-            const int nb = (count - b0) < kMaxDualBatch ? (count - b0) : kMaxDualBatch;
-            int wg = 0;
-            for (int j = 0; j < nb; ++j) {
-                const mmse_dual_desc_t& d = descs_host[b0 + j];
-                const W& w = wk[b0 + j];
-                DualTensor& T = D.t[j];
+            int nb = 0;
+            long long wg = 0;
+            while (b0 + nb < count && nb < kMaxDualBatch) {
+                const mmse_dual_desc_t& d = descs_host[b0 + nb];
+                const long long units = kind == 2 ? ((long long)d.K * d.n + 1) / 2 : d.K;
+                const long long add = (units + 255) / 256;
+                if (nb > 0 && wg + add > kMaxLaunchWG) break;          // the rest goes into the next launch
+                const W& w = wk[b0 + nb];
+                DualTensor& T = D.t[nb];
                 T.sse = d.sse_dev; T.tsse = w.tsse; T.s1 = d.scale1_dev; T.ts1 = w.ts1; T.s2 = d.scale2_dev; T.ts2 = w.ts2;
                 T.sweeps = d.sweeps_dev; T.active = w.active; T.accepted = w.accepted;
                 T.tp1 = w.tp1; T.p1 = d.packed1_dev; T.tp2 = w.tp2; T.p2 = d.packed2_dev;
                 T.K = (int)d.K; T.n = (int)d.n;
-                D.start[j] = wg;
-                const long long units = kind == 2 ? ((long long)d.K * d.n + 1) / 2 : d.K;
-                wg += (int)((units + 255) / 256);
+                D.start[nb] = (int)wg;
+                wg += add;
+                ++nb;
             }
-            D.start[nb] = wg;
+            D.start[nb] = (int)wg;
             D.count = nb;
-            if (kind == 0) hipLaunchKernelGGL(k_dual_init, dim3(wg), dim3(256), 0, s, D);
-            else if (kind == 1) hipLaunchKernelGGL(k_dual_accept, dim3(wg), dim3(256), 0, s, D);
-            else hipLaunchKernelGGL(k_dual_copy_codes, dim3(wg), dim3(256), 0, s, D);
+            if (kind == 0) hipLaunchKernelGGL(k_dual_init, dim3((unsigned)wg), dim3(256), 0, s, D);
+            else if (kind == 1) hipLaunchKernelGGL(k_dual_accept, dim3((unsigned)wg), dim3(256), 0, s, D);
+            else hipLaunchKernelGGL(k_dual_copy_codes, dim3((unsigned)wg), dim3(256), 0, s, D);
             if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH;
+            b0 += nb;
         }
         return MMSE_OK;
     };
@@ -590,7 +620,7 @@ int mmse_workspace_bytes_dual_batched(const mmse_dual_desc_t* descs_host, int32_
     size_t need = 0;
     for (int i = 0; i < count; ++i) {
         const mmse_dual_desc_t& d = descs_host[i];
-        if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS || d.K > MMSE_MAX_TENSOR_ELEMS / d.n) return MMSE_ERR_SIZE;
+        if (d.K <= 0 || d.n <= 0 || d.n > MMSE_MAX_KERNEL_ELEMS || d.K > MMSE_MAX_TENSOR_ELEMS / d.n || d.K > MMSE_MAX_KERNELS) return MMSE_ERR_SIZE;
         need += plan_dual(d.K, d.n).bytes;
     }
     *bytes_out = need;
@@ -651,7 +681,7 @@ int mmse_scale_alternating_kernelwise(const float* w_dev, int64_t K, int64_t n, 
                                       void* stream)
 {
     if (!w_dev || !scale_dev || !sse_dev || !updates_dev) return MMSE_ERR_NULL;
-    if (K <= 0 || n <= 0 || n > MMSE_MAX_KERNEL_ELEMS || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (K <= 0 || n <= 0 || n > MMSE_MAX_KERNEL_ELEMS || K > MMSE_MAX_TENSOR_ELEMS / n || K > MMSE_MAX_KERNELS) return MMSE_ERR_SIZE;
     if (!(qmin <= 0 && qmax > 0 && qmax - qmin <= 15) || max_iters < 0 || max_iters > 1000) return MMSE_ERR_PARAMS;
     if (!aligned_to(w_dev, 4) || !aligned_to(scale_dev, 4) || !aligned_to(sse_dev, 8) || !aligned_to(updates_dev, 4))
         return MMSE_ERR_ALIGN;
@@ -666,7 +696,7 @@ int mmse_scale_alternating_kernelwise(const float* w_dev, int64_t K, int64_t n, 
 int mmse_workspace_bytes_dual_linesearch(int64_t K, int64_t n, int32_t G1, int32_t G2, size_t* bytes_out)
 {
     if (!bytes_out) return MMSE_ERR_NULL;
-    if (K <= 0 || n <= 0 || n > kTile || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (K <= 0 || n <= 0 || n > kTile || K > MMSE_MAX_TENSOR_ELEMS / n || K > MMSE_MAX_KERNELS) return MMSE_ERR_SIZE;
     if (G1 < 1 || G2 < 1 || G1 > 1024 || G2 > 1024) return MMSE_ERR_PARAMS;
     const int sp = dual_ls_splits(K, G1, G2);
     *bytes_out = round256((size_t)K * sizeof(float)) + round256((size_t)K * sp * sizeof(double)) +
@@ -681,7 +711,7 @@ int dual_line_search(const float* w_dev, int64_t K, int64_t n, int32_t qmin, int
 {
     if (!w_dev || !scale1_dev || !scale2_dev || !idx1_dev || !idx2_dev || !sse_dev || !packed1_dev || !packed2_dev)
         return MMSE_ERR_NULL;
-    if (K <= 0 || n <= 0 || n > kTile || K > MMSE_MAX_TENSOR_ELEMS / n) return MMSE_ERR_SIZE;
+    if (K <= 0 || n <= 0 || n > kTile || K > MMSE_MAX_TENSOR_ELEMS / n || K > MMSE_MAX_KERNELS) return MMSE_ERR_SIZE;
     if (!(qmin <= 0 && qmax > 0 && qmax - qmin <= 15)) return MMSE_ERR_PARAMS;
     if (G1 < 1 || G2 < 1 || G1 > 1024 || G2 > 1024) return MMSE_ERR_PARAMS;
     if (!aligned_to(w_dev, 4) || !aligned_to(scale1_dev, 4) || !aligned_to(scale2_dev, 4) || !aligned_to(idx1_dev, 4) ||
@@ -859,7 +889,6 @@ int mmse_scale_search_activation_batched(const mmse_act_desc_t* descs_host, int3
     if (rc) return rc;
     if (!descs_host) return MMSE_ERR_NULL;
     if (count <= 0 || count > MMSE_MAX_BATCH_TENSORS) return MMSE_ERR_SIZE;
-    size_t need = 0;
     for (int i = 0; i < count; ++i) {
         const mmse_act_desc_t& d = descs_host[i];
         if (!d.x_dev || !d.scale_dev || !d.idx_dev || !d.sse_dev) return MMSE_ERR_NULL;
@@ -867,29 +896,31 @@ int mmse_scale_search_activation_batched(const mmse_act_desc_t* descs_host, int3
         if (!aligned_to(d.x_dev, 4) || !aligned_to(d.scale_dev, 4) || !aligned_to(d.idx_dev, 4) || !aligned_to(d.sse_dev, 8))
             return MMSE_ERR_ALIGN;
     }
-    // groups of at most kMaxActBatch tensors, each with its own slice of the workspace
-    ActPlan plans[(MMSE_MAX_BATCH_TENSORS + kMaxActBatch - 1) / kMaxActBatch];
-    int ngroups = 0;
-    for (int g0 = 0; g0 < count; g0 += kMaxActBatch, ++ngroups) {
+    // launch groups, each with its own slice of the workspace: sized first, then run
+    size_t need = 0;
+    for (int g0 = 0; g0 < count;) {
+        const int m = act_group_size(g0, count, [&](int i) { return descs_host[i].N; });
         long long n[kMaxActBatch];
-        const int m = (count - g0) < kMaxActBatch ? (count - g0) : kMaxActBatch;
         for (int i = 0; i < m; ++i) n[i] = descs_host[g0 + i].N;
-        plans[ngroups] = plan_activation(n, m, p->grid_points);
-        need += plans[ngroups].bytes;
+        need += plan_activation(n, m, p->grid_points).bytes;
+        g0 += m;
     }
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < need) return MMSE_ERR_WORKSPACE;
     char* ws = static_cast<char*>(ws_dev);
-    for (int g = 0; g < ngroups; ++g) {
+    for (int g0 = 0; g0 < count;) {
+        const int m = act_group_size(g0, count, [&](int i) { return descs_host[i].N; });
+        long long n[kMaxActBatch];
         ActItem items[kMaxActBatch];
-        const int g0 = g * kMaxActBatch;
-        const int m = plans[g].count;
         for (int i = 0; i < m; ++i) {
             const mmse_act_desc_t& d = descs_host[g0 + i];
+            n[i] = d.N;
             items[i] = ActItem{d.x_dev, (long long)d.N, d.scale_dev, d.idx_dev, d.sse_dev, d.packed_dev};
         }
-        rc = run_activation_group(items, m, p, 0, nullptr, 0, 0, nullptr, ws, plans[g], static_cast<hipStream_t>(stream));
+        const ActPlan P = plan_activation(n, m, p->grid_points);
+        rc = run_activation_group(items, m, p, 0, nullptr, 0, 0, nullptr, ws, P, static_cast<hipStream_t>(stream));
         if (rc) return rc;
-        ws += plans[g].bytes;
+        ws += P.bytes;
+        g0 += m;
     }
     return MMSE_OK;
 }

@@ -86,9 +86,11 @@ def test_entry_points_validate_before_enqueue(B):
     assert lib.residual_quantize(a, 4, 4, None, C.byref(p), a, a, a, a, a, 4096, None) == -1
     assert lib.mmse_scale_search_batched(None, 1, C.byref(p), a, 4096, None) == -1
     assert lib.mmse_grid_sse_kernelwise(a, 4, 4, C.byref(p), None, a, None) == -1
-    big = (B.MmseTensorDesc * 2)(B.MmseTensorDesc(a, 1 << 30, 1, None, a, a, a, None), B.MmseTensorDesc(a, 1 << 30, 1, None, a, a, a, None))
-    assert lib.mmse_scale_search_batched(big, 2, C.byref(p), a, 1 << 40, None) == -2          # sum K beyond one launch grid
-    bigd = (B.MmseDualDesc * 2)(B.MmseDualDesc(a, 1 << 30, 1, a, a, a, a, a, a), B.MmseDualDesc(a, 1 << 30, 1, a, a, a, a, a, a))
+    assert lib.mmse_scale_search_kernelwise(a, (1 << 22) + 1, 4, C.byref(p), a, a, a, a, 1 << 30, None) == -2   # more kernels than a launch holds
+    assert lib.mmse_scale_alternating_kernelwise(a, (1 << 22) + 1, 4, -8, 7, 10, a, a, a, None) == -2
+    big = (B.MmseTensorDesc * 2)(B.MmseTensorDesc(a, 4, 4, None, a, a, a, None), B.MmseTensorDesc(a, (1 << 22) + 1, 1, None, a, a, a, None))
+    assert lib.mmse_scale_search_batched(big, 2, C.byref(p), a, 1 << 40, None) == -2          # second tensor: too many kernels
+    bigd = (B.MmseDualDesc * 2)(B.MmseDualDesc(a, 4, 4, a, a, a, a, a, a), B.MmseDualDesc(a, (1 << 22) + 1, 1, a, a, a, a, a, a))
     assert lib.dual_quantize_alternating_batched(bigd, 2, C.byref(p), 1e-3, 4, a, 1 << 44, None) == -2
     assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), 1e-3, 4, a, a, None, a, a, a, a, 1 << 20, None) == -1
     assert lib.dual_quantize_alternating(a, 4, 4, C.byref(p), -1.0, 4, a, a, a, a, a, a, a, 1 << 20, None) == -3

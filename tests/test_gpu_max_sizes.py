@@ -116,13 +116,14 @@ def test_batched_calls_with_the_most_tensors(B):
 
 
 def test_batched_activations_with_more_than_65535_block_groups(B):
-    """64 tensors of about 65 536 blocks each in one launch group: 4.2 M blocks, 65 536 rows after the first
-    tree stage (more than a grid's y axis holds).  The tensors are views of one buffer with four different
-    lengths, so the oracle has four problems to solve."""
+    """64 tensors of about 65 536 blocks each in one launch group: 4.2 M blocks (the most one group takes),
+    65 536 rows after the first tree stage (more than a grid's y axis holds).  Then the same with one tensor
+    two blocks longer, which no longer fits the group and is searched by a second set of launches.  The
+    tensors are views of one buffer with five different lengths, so the oracle has five problems to solve."""
     import torch
     base_n = 2 ** 28
     say(f"64 activation tensors of about {base_n} elements in one batched call")
-    x = synth.tiled_normal(base_n, 190206822 + 9004, relu=True)
+    x = synth.tiled_normal(base_n + 8192, 190206822 + 9004, relu=True)
     lengths = [base_n, base_n - 1, base_n - 4097, base_n - 60000]
     assert sum(((n + 4095) // 4096 + 63) // 64 for n in lengths) * 16 == 65536      # rows after one tree stage
     xd = torch.from_numpy(x).cuda()
@@ -132,10 +133,91 @@ def test_batched_activations_with_more_than_65535_block_groups(B):
     torch.cuda.synchronize()
     say("oracle")
     ref = [oracle.can_search(x[:n], 0, 15, G, iters) for n in lengths]
+
+    def same(r, o, tag):
+        assert int(r.idx.cpu()[0]) == o["idx"], tag
+        assert float(r.scale.cpu()[0]) == float(o["scale"]), tag
+        assert float(r.sse.cpu()[0]) == o["sse"], tag
+
     for i, r in enumerate(res):
-        o = ref[i % 4]
-        assert int(r.idx.cpu()[0]) == o["idx"], i
-        assert float(r.scale.cpu()[0]) == float(o["scale"]), i
-        assert float(r.sse.cpu()[0]) == o["sse"], i
+        same(r, ref[i % 4], i)
+    say("one tensor longer: two launch groups")
+    sizes = [base_n + 8192] + [base_n] * 63
+    assert sum((n + 4095) // 4096 for n in sizes) == 2 ** 22 + 2
+    res = B.mmse_scale_search_activation_batched([xd[:n] for n in sizes], p, want_packed=False)
+    torch.cuda.synchronize()
+    same(res[0], oracle.can_search(x, 0, 15, G, iters), "longer tensor")
+    for i in range(1, 64):
+        same(res[i], ref[0], i)
     del xd, res
+    torch.cuda.empty_cache()
+
+
+def check_sampled_kernels(w, r, qr, G, iters, seed, tag):
+    """Oracle on a sample of whole kernels (the ends, the middle, random ones): kernels are independent
+    problems, so a sampled kernel is checked exactly as in a complete run."""
+    K, n = w.shape
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([np.arange(0, 2000), np.arange(K // 2 - 1000, K // 2 + 1000),
+                                     np.arange(K - 2000, K), rng.integers(0, K, 20000)]))
+    s, j, e = oracle.can_search_kernelwise(w[rows], *qr, G, iters)
+    np.testing.assert_array_equal(r.idx.cpu().numpy()[rows], j, err_msg=f"idx {tag}")
+    np.testing.assert_array_equal(r.scale.cpu().numpy()[rows], s, err_msg=f"scale {tag}")
+    np.testing.assert_array_equal(r.sse.cpu().numpy()[rows], e, err_msg=f"sse {tag}")
+    codes = oracle.can_codes(w[rows], s, *qr)
+    flat = (rows[:, None].astype(np.int64) * n + np.arange(n)[None, :]).ravel()
+    packed = r.packed.cpu().numpy()
+    got = ((packed[flat // 2] >> ((flat % 2) * 4)) & 0xF).astype(np.int32)
+    got = np.where(got >= 8, got - 16, got) if qr[0] < 0 else got
+    np.testing.assert_array_equal(got, codes.ravel(), err_msg=f"codes {tag}")
+
+
+def test_weight_launches_are_cut_at_the_work_item_limit(B):
+    """Tensors with the most kernels the ABI takes (2^22 each): a launch holds one of them on the
+    general path (one workgroup per kernel) and four on the short-kernel path (four kernels per workgroup)."""
+    import torch
+    K = 2 ** 22
+    say("short-kernel path: five tensors of 2^22 one-element kernels")
+    ws = [synth.tiled_normal(K, 190206822 + 9010 + i).reshape(K, 1) for i in range(5)]
+    p = B.params(-8, 7, 40, 2)
+    res = B.mmse_scale_search_batched([torch.from_numpy(w).cuda() for w in ws], p, want_packed=True)
+    torch.cuda.synchronize()
+    for i, (w, r) in enumerate(zip(ws, res)):
+        check_sampled_kernels(w, r, (-8, 7), 40, 2, 70 + i, f"short kernels, tensor {i}")
+    say("general path: two tensors of 2^22 two-element kernels, G = 520")
+    ws = [synth.tiled_normal(2 * K, 190206822 + 9020 + i).reshape(K, 2) for i in range(2)]
+    p = B.params(-8, 7, 520, 0)
+    res = B.mmse_scale_search_batched([torch.from_numpy(w).cuda() for w in ws], p, want_packed=True)
+    torch.cuda.synchronize()
+    for i, (w, r) in enumerate(zip(ws, res)):
+        check_sampled_kernels(w, r, (-8, 7), 520, 0, 80 + i, f"general path, tensor {i}")
+
+
+def test_dual_alternating_over_more_than_2_31_weights_in_one_call(B):
+    """Three layers of 10 923 kernels of 65 536 weights through the batched Algorithm 1: together just over
+    2^31 weights, so the launch that copies accepted codes (one workgroup per 512 weights) is cut in two.
+    Sampled kernels are compared with the oracle; every kernel must report a sweep count in range."""
+    import torch
+    K, n = 10923, 65536
+    assert 3 * ((K * n // 2 + 255) // 256) > 2 ** 22 >= 2 * ((K * n // 2 + 255) // 256)
+    say(f"Algorithm 1, three layers of {K} x {n}")
+    G, iters, eps, max_sweeps = 32, 4, 0.0, 3
+    p = B.params(-8, 7, G, iters)
+    ws = [synth.tiled_normal(K * n, 190206822 + 9030 + i).reshape(K, n) for i in range(3)]
+    res = B.dual_quantize_alternating_batched([torch.from_numpy(w).cuda() for w in ws], p, eps, max_sweeps)
+    torch.cuda.synchronize()
+    say("oracle on sampled kernels")
+    rows = np.array([0, 1, 4095, 4096, K // 2, K - 2, K - 1])
+    for i, (w, r) in enumerate(zip(ws, res)):
+        o = oracle.can_dual_alternating(np.ascontiguousarray(w[rows]), -8, 7, G, iters, eps, max_sweeps)
+        sw = r.sweeps.cpu().numpy()
+        assert sw.min() >= 1 and sw.max() <= max_sweeps
+        np.testing.assert_array_equal(sw[rows], o["sweeps"], err_msg=f"sweeps {i}")
+        np.testing.assert_array_equal(r.scale1.cpu().numpy()[rows], o["scale1"], err_msg=f"scale1 {i}")
+        np.testing.assert_array_equal(r.scale2.cpu().numpy()[rows], o["scale2"], err_msg=f"scale2 {i}")
+        np.testing.assert_array_equal(r.sse.cpu().numpy()[rows], o["sse"], err_msg=f"sse {i}")
+        for name in ("packed1", "packed2"):
+            got = torch.stack([getattr(r, name)[k * (n // 2):(k + 1) * (n // 2)] for k in rows]).cpu().numpy().ravel()
+            np.testing.assert_array_equal(got, o[name], err_msg=f"{name} {i}")
+    del res
     torch.cuda.empty_cache()
