@@ -74,22 +74,40 @@ __global__ void __launch_bounds__(256) k_dual_accept(const DualBatch D)
     T.accepted[k] = acc;
 }
 
-// Codes of the kernels whose sweep was kept move from the tentative to the kept buffers, nibble by
-// nibble (a byte can hold codes of two kernels when n is odd).
+// Codes of the kernels whose sweep was kept move from the tentative to the kept buffers: 16 bytes (32 codes)
+// per thread in one piece where they belong to one kernel, else nibble by nibble (a byte can hold codes of
+// two kernels when n is odd).
 __global__ void __launch_bounds__(256) k_dual_copy_codes(const DualBatch D)
 {
     const int t = find_dual_tensor(D, blockIdx.x);
     const DualTensor& T = D.t[t];
     const long long total = (long long)T.K * T.n;
-    const long long b = (long long)(blockIdx.x - D.start[t]) * blockDim.x + threadIdx.x;
-    if (2 * b >= total) return;
-    const unsigned e0 = (unsigned)(2 * b);
-    const bool a0 = T.accepted[e0 / (unsigned)T.n] != 0;
-    const bool a1 = (long long)e0 + 1 < total && T.accepted[(e0 + 1) / (unsigned)T.n] != 0;
-    if (!a0 && !a1) return;
-    const unsigned mask = (a0 ? 0x0Fu : 0u) | (a1 ? 0xF0u : 0u);
-    T.p1[b] = (uint8_t)((T.p1[b] & ~mask) | (T.tp1[b] & mask));
-    T.p2[b] = (uint8_t)((T.p2[b] & ~mask) | (T.tp2[b] & mask));
+    const long long nbytes = (total + 1) >> 1;
+    const long long b0 = ((long long)(blockIdx.x - D.start[t]) * blockDim.x + threadIdx.x) * 16;
+    if (b0 >= nbytes) return;
+    const unsigned n = (unsigned)T.n;
+    const long long elast = (2 * b0 + 31 < total) ? 2 * b0 + 31 : total - 1;
+    const unsigned k0 = (unsigned)(2 * b0) / n, k1 = (unsigned)elast / n;       // K * n < 2^31
+    const uintptr_t al = reinterpret_cast<uintptr_t>(T.p1) | reinterpret_cast<uintptr_t>(T.tp1) |
+                         reinterpret_cast<uintptr_t>(T.p2) | reinterpret_cast<uintptr_t>(T.tp2);
+    if (k0 == k1 && b0 + 16 <= nbytes && (al & 15u) == 0) {
+        if (T.accepted[k0] != 0) {
+            *reinterpret_cast<uint4*>(T.p1 + b0) = *reinterpret_cast<const uint4*>(T.tp1 + b0);
+            *reinterpret_cast<uint4*>(T.p2 + b0) = *reinterpret_cast<const uint4*>(T.tp2 + b0);
+        }
+        return;
+    }
+    for (int j = 0; j < 16; ++j) {
+        const long long b = b0 + j;
+        if (b >= nbytes) break;
+        const unsigned e0 = (unsigned)(2 * b);
+        const bool a0 = T.accepted[e0 / n] != 0;
+        const bool a1 = (long long)e0 + 1 < total && T.accepted[(e0 + 1) / n] != 0;
+        if (!a0 && !a1) continue;
+        const unsigned mask = (a0 ? 0x0Fu : 0u) | (a1 ? 0xF0u : 0u);
+        T.p1[b] = (uint8_t)((T.p1[b] & ~mask) | (T.tp1[b] & mask));
+        T.p2[b] = (uint8_t)((T.p2[b] & ~mask) | (T.tp2[b] & mask));
+    }
 }
 
 // ---------------------------------------------------------------------------------

@@ -200,8 +200,15 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
                     const int tile_chunks = cls == 0 ? 0 : 32 * 256 / threads;
                     const size_t lds = (size_t)threads * 2 * sizeof(double) +
                                        (size_t)(threads / 64) * tile_chunks * kTileStride * sizeof(float);
-                    if (cls == 0) hipLaunchKernelGGL(k_refine_kernelwise<16>, dim3(wg), dim3(threads), lds, s, B, tile_chunks);
-                    else hipLaunchKernelGGL(k_refine_kernelwise<kChunk>, dim3(wg), dim3(threads), lds, s, B, tile_chunks);
+                    bool xf = false;
+                    for (int i = 0; i < nb; ++i) xf = xf || B.t[i].scale1 != nullptr || B.t[i].sub_packed != nullptr;
+                    if (cls == 0) {
+                        if (xf) hipLaunchKernelGGL((k_refine_kernelwise<16, true>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
+                        else hipLaunchKernelGGL((k_refine_kernelwise<16, false>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
+                    } else {
+                        if (xf) hipLaunchKernelGGL((k_refine_kernelwise<kChunk, true>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
+                        else hipLaunchKernelGGL((k_refine_kernelwise<kChunk, false>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
+                    }
                     nb = 0; wg = 0;
                     return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
                 };
@@ -571,7 +578,7 @@ int dual_quantize_alternating_batched(const mmse_dual_desc_t* descs_host, int32_
             long long wg = 0;
             while (b0 + nb < count && nb < kMaxDualBatch) {
                 const mmse_dual_desc_t& d = descs_host[b0 + nb];
-                const long long units = kind == 2 ? ((long long)d.K * d.n + 1) / 2 : d.K;
+                const long long units = kind == 2 ? (((long long)d.K * d.n + 1) / 2 + 15) / 16 : d.K;   // 16 bytes of codes, or one kernel, per thread
                 const long long add = (units + 255) / 256;
                 if (nb > 0 && wg + add > kMaxLaunchWG) break;          // the rest goes into the next launch
                 const W& w = wk[b0 + nb];

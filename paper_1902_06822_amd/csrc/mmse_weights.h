@@ -256,7 +256,9 @@ __device__ __forceinline__ double tree_combine(double v, int c, int m, bool acti
 
 constexpr int kTileStride = 68;   // floats between chunks in the transpose tile (64 + 4: keeps 16-byte alignment)
 
-template <int CL>   // element slots per lane: 64 (general) or 16 (kernels of <= 16 elements)
+// CL: element slots per lane, 64 (general) or 16 (kernels of <= 16 elements).  XF: some tensor of the launch is
+// searched through a transform (the residual of a first tensor); without it that code is left out altogether.
+template <int CL, bool XF>
 __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int tile_chunks)
 {
     // dynamic LDS: [combine buffer: 2 x blockDim doubles][per-wave transpose tiles]
@@ -342,13 +344,30 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
             for (int i = 0; i < CL; ++i) x[i] = (i < len) ? src[i] : 0.0f;
         }
     }
-    if (X.mode != 0 && active) {
+    if (XF && X.mode != 0 && active) {
         const int e0x = c * kChunk;
         const int lenx = (n - e0x) < CL ? (n - e0x) : CL;
         const long long f0 = (long long)k * n + e0x;
+        const uint8_t* codes = X.mode == 2 ? X.sub + (f0 >> 1) : nullptr;
+        if (X.mode == 2 && CL >= 32 && lenx == CL && (f0 & 1) == 0 && (reinterpret_cast<uintptr_t>(codes) & 15u) == 0) {
+            // the stored codes of a whole chunk: CL / 2 bytes in 16-byte loads, unpacked from registers
 #pragma unroll
-        for (int i = 0; i < CL; ++i)
-            if (i < lenx) x[i] = xform_apply(X, x[i], f0 + i, lo, hi);
+            for (int v = 0; v < CL / 32; ++v) {
+                const uint4 q4 = reinterpret_cast<const uint4*>(codes)[v];
+                const unsigned words[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    const unsigned wd = words[i >> 3];
+                    const int q = X.sub_signed ? __builtin_amdgcn_sbfe((int)wd, 4 * (i & 7), 4)
+                                               : (int)__builtin_amdgcn_ubfe(wd, 4 * (i & 7), 4);
+                    x[32 * v + i] = __builtin_fmaf(-X.s1, (float)q, x[32 * v + i]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CL; ++i)
+                if (i < lenx) x[i] = xform_apply(X, x[i], f0 + i, lo, hi);
+        }
     }
 
     const int G = B.G;
