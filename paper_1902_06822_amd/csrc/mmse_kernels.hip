@@ -769,12 +769,13 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     ActBatch B{};
     ActOut O{};
     bool any_packed = false;
-    long long maxN = 0;
+    long long maxN = 0, sumN = 0;
     for (int t = 0; t < count; ++t) {
         B.x[t] = items[t].x; B.N[t] = items[t].N; B.start[t] = P.start[t];
         O.scale[t] = items[t].scale; O.idx[t] = items[t].idx; O.sse[t] = items[t].sse; O.packed[t] = items[t].packed;
         any_packed = any_packed || items[t].packed != nullptr;
         maxN = items[t].N > maxN ? items[t].N : maxN;
+        sumN += items[t].N;
     }
     B.start[count] = P.start[count];
     B.count = count;
@@ -793,9 +794,13 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     {
         // per tensor at most one workgroup per CU, eight 16-byte loads in flight per thread: measured fastest
         // on MI355X (6.9 TB/s on a 205 MB tensor; more, smaller workgroups lose up to 2x)
+        // (a batch shares the CUs: about two workgroups per CU over all tensors, each tensor in proportion to its size)
         constexpr int U = 8;
         long long want = (maxN + 1024 * U - 1) / (1024 * U);
-        const int grid = (int)(want < 256 ? (want < 1 ? 1 : want) : 256);
+        long long cap = (2 * 256 * maxN + sumN - 1) / sumN;
+        if (cap > 256) cap = 256;
+        if (want > cap) want = cap;
+        const int grid = (int)(want < 1 ? 1 : want);
         const dim3 g(grid, count);
         if (pre_mode == 0) hipLaunchKernelGGL((k_act_absmax<U, 0>), g, dim3(256), 0, s, B, pre);
         else if (pre_mode == 1) hipLaunchKernelGGL((k_act_absmax<U, 1>), g, dim3(256), 0, s, B, pre);
