@@ -145,13 +145,15 @@ def test_full_size_activation_second_tensor_and_offset_form(B, cfg):
     np.testing.assert_array_equal(ro.packed.cpu().numpy(), oo["packed"])
 
 
-def test_config4_all_activation_tensors_batched(B):
-    """Every calibration tensor of configuration 4 (54 tensors, 341 M elements) through the batched entry
-    point, in the launch configuration `bench.py --part whole` times, against the oracle tensor by tensor."""
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_all_activation_tensors_of_a_network_batched(B, cfg):
+    """Every calibration tensor of configurations 4 (54 tensors, 341 M elements) and 5 (16 tensors, 146 M
+    elements, G = 512) through the batched entry point, in the launch configuration `bench.py --part whole`
+    times, against the oracle tensor by tensor."""
     import torch
-    c = synth.config(4)
+    c = synth.config(cfg)
     G, it = c.grid_points, c.refine_iters
-    say(f"config 4: {len(c.act_shapes)} activation tensors, batched")
+    say(f"config {cfg}: {len(c.act_shapes)} activation tensors, batched")
     order = sorted(range(len(c.act_shapes)), key=lambda i: -c.act_shapes[i].per_image)
     dev = [to_dev(c.act_tensor(i)) for i in order]
     res = B.mmse_scale_search_activation_batched(dev, B.params(*UNSIGNED, G, it))
@@ -161,11 +163,11 @@ def test_config4_all_activation_tensors_batched(B):
     for n_, i in enumerate(order):
         x = c.act_tensor(i)
         o = oracle.can_search(x, *UNSIGNED, G, it)
-        assert got[n_] == (float(o["scale"]), o["idx"], o["sse"]), f"cfg4 activation tensor {i} ({c.act_shapes[i].name})"
+        assert got[n_] == (float(o["scale"]), o["idx"], o["sse"]), f"cfg{cfg} activation tensor {i} ({c.act_shapes[i].name})"
         if n_ % 9 == 0 or n_ == len(order) - 1:          # codes of every ninth tensor, the largest included
             np.testing.assert_array_equal(res[n_].packed.cpu().numpy(),
                                           oracle.can_quantize_pack_int4(x, [o["scale"]], *UNSIGNED),
-                                          err_msg=f"cfg4 activation codes {i}")
+                                          err_msg=f"cfg{cfg} activation codes {i}")
         res[n_].packed = None
 
 
