@@ -1,8 +1,9 @@
 """GPU parity at the full sizes of the benchmark's configurations 4 and 5, in the launch
 configuration ``bench.py`` times (the batched whole-net entry point; the per-layer activation
-entry point).  Where the oracle finishes in seconds the comparison is complete; for the
-138 M-weight configuration it is made on seeded samples of whole kernels (kernels are
-independent problems, so a sampled kernel is checked exactly as in a complete run)."""
+entry point).  Where the oracle finishes in seconds the comparison is complete (also the first
+search of the 138 M-weight configuration); the second tensor of that configuration is compared on
+seeded samples of whole kernels (kernels are independent problems, so a sampled kernel is checked
+exactly as in a complete run)."""
 import sys
 
 import numpy as np
@@ -209,3 +210,20 @@ def test_config5_weights_and_residual_on_sampled_kernels(B):
         assert np.all(np.isfinite(r.scale.cpu().numpy())) and np.all(r.idx.cpu().numpy() >= 0)
         assert np.all(r.idx.cpu().numpy() < G)
         assert pk.size == (K * n + 1) // 2
+
+
+def test_config5_first_search_complete(B):
+    """Every one of the 13 416 kernels of configuration 5 (138 M weights, G = 512): scales, indices, errors
+    and all packed codes of the first search against the oracle."""
+    import torch
+    c = synth.config(5)
+    G, it = c.grid_points, c.refine_iters
+    say("config 5: complete comparison of the first search")
+    ws = [c.weight_tensor(i) for i in range(len(c.weight_shapes))]
+    res = B.mmse_scale_search_batched([to_dev(w) for w in ws], B.params(*SIGNED, G, it), want_packed=True)
+    torch.cuda.synchronize()
+    for i, (w, r) in enumerate(zip(ws, res)):
+        s, j, e = oracle.can_search_kernelwise(w, *SIGNED, G, it)
+        check_equal(r, s, j, e, f"cfg5 tensor {i}")
+        np.testing.assert_array_equal(r.packed.cpu().numpy(), oracle.can_quantize_pack_int4(w, s, *SIGNED),
+                                      err_msg=f"cfg5 tensor {i} codes")
