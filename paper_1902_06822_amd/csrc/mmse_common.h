@@ -246,7 +246,7 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsig
                                             float lo, float hi, double (&st)[C][L])
 {
     const float4* s4 = reinterpret_cast<const float4*>(slice);
-    constexpr int NE = (C >= 4) ? 4 : 8;            // elements per stage group
+    constexpr int NE = (C >= 2) ? 4 : 8;            // elements per stage group (8 temporaries either way with C <= 2)
     const int nfull = nelem / kChunk;
     const int tail = nelem - nfull * kChunk;        // 0, 8, ..., 56 elements of a last partial chunk
     const int ntotal = nfull + (tail > 0 ? 1 : 0);
