@@ -291,14 +291,23 @@ __global__ void k_act_offset_setup(ActState* S, float* delta_out)
     *delta_out = (range <= kHuge) ? mn : nanf_;
 }
 
-// Grid sweep of one 4096-element block per workgroup; waves split the candidates.
+// Grid sweep of one 4096-element block per workgroup; waves split the candidates.  With split != 0 the waves
+// form two sets that each cover all candidates and take one half of the block (32 chunks) each: the halves are
+// the two subtrees under the root of the block's pairwise tree, so set 0 adds the two sums at the end (one
+// exchange through LDS).  That keeps four waves per workgroup, and with them eight waves per SIMD within the
+// LDS of a CU, for grids that two candidates per lane would otherwise cover with two waves.
+constexpr int kMaxSplitCands = 384;
+
 template <int C>
 __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int qmax,
-                                                    float lo, float hi, double* part0, const ActPre pre)
+                                                    float lo, float hi, double* part0, const ActPre pre, int split)
 {
     __shared__ float4 slice4[kBlockElems / 4];
+    __shared__ double xbuf[kMaxSplitCands];
     float* slice = reinterpret_cast<float*>(slice4);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+    const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
+    const int wps = split ? (nthreads >> 7) : (nthreads >> 6);          // waves per set
+    const int set = (tid >> 6) / wps, wave = (tid >> 6) - set * wps;     // wave: its number inside the set
     const int t = act_find(B, blockIdx.x);
     const float* __restrict__ x = B.x[t];
     const long long N = B.N[t];
@@ -330,12 +339,29 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
 #pragma unroll
         for (int l = 0; l < kLevelsBlk; ++l) st[u][l] = 0.0;
     unsigned ci = 0;
-    sweep_slice<C, kLevelsBlk>(slice, (len + 7) & ~7, ci, alpha, inv, lo, hi, st);
+    const int half = split ? kBlockElems / 2 : kBlockElems;
+    const int e0 = set * half;
+    int nel = ((len + 7) & ~7) - e0;
+    nel = nel < 0 ? 0 : (nel < half ? nel : half);
+    if (nel > 0) sweep_slice<C, kLevelsBlk>(slice + e0, nel, ci, alpha, inv, lo, hi, st);
     double E[C];
-    tree_fold<C, kLevelsBlk>(st, ci, E);
+    tree_fold<C, kLevelsBlk>(st, ci, E);                    // 0.0 when this set has no chunk
+    if (split) {
+        if (set == 1) {
 #pragma unroll
-    for (int u = 0; u < C; ++u)
-        if (jcand[u] < G) part0[(size_t)blockIdx.x * G + jcand[u]] = E[u];
+            for (int u = 0; u < C; ++u) xbuf[jcand[u]] = E[u];
+        }
+        __syncthreads();
+        if (set == 0) {
+#pragma unroll
+            for (int u = 0; u < C; ++u) E[u] = E[u] + xbuf[jcand[u]];
+        }
+    }
+    if (set == 0) {
+#pragma unroll
+        for (int u = 0; u < C; ++u)
+            if (jcand[u] < G) part0[(size_t)blockIdx.x * G + jcand[u]] = E[u];
+    }
 }
 
 // One tree stage over blocks: out[g][j] = pairwise sum of in[64g .. 64g+63][j].

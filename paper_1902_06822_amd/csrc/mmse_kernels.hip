@@ -815,12 +815,15 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         }
     }
     {
-        const int C = pick_cands(p);
-        const int waves = (G + 64 * C - 1) / (64 * C);
+        // 129 ... 384 grid points, tuning left to the library: two candidates per lane and two sets of waves that
+        // take half a block each (see k_act_sweep)
+        const int split = (p->cands_per_lane == 0 && G > 128 && G <= kMaxSplitCands) ? 1 : 0;
+        const int C = split ? 2 : pick_cands(p);
+        const int waves = (split ? 2 : 1) * ((G + 64 * C - 1) / (64 * C));
         double* part0 = reinterpret_cast<double*>(ws + P.off_part[0]);
-        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre);
-        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre);
-        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre);
+        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
+        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
+        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
         MMSE_CHECK_LAUNCH();
     }
     for (int l = 0; l < P.levels; ++l) {
