@@ -168,3 +168,26 @@ def test_grid_errors_of_degenerate_activation_tensors(B):
     a, g = B.mmse_grid_sse_activation(dev(z), B.params(*UNSIGNED, 16, 0))
     torch.cuda.synchronize()
     assert np.isnan(float(a[0])) and np.all(np.isnan(g.cpu().numpy()))
+
+
+@pytest.mark.parametrize("G", [130, 200, 256, 384, 385, 512])
+def test_activation_results_do_not_depend_on_tuning(B, G):
+    """The sweep has several launch shapes (one, two or four candidates per lane; for 129 ... 384 grid points
+    two sets of waves that take half a block each): every one gives the oracle's bits, for tensors whose last
+    block is shorter or longer than half a block."""
+    import torch
+    say(f"activation tuning shapes, G={G}")
+    for N in (1500, 2048, 2049, 4096 + 2100, 3 * 4096 + 63, 70001):
+        x = synth.acts_relu_student_t(N, 4000 + N)
+        o = oracle.can_search(x, *UNSIGNED, G, 6, want_grid=True)
+        xd = dev(x)
+        for cpl in (0, 1, 2, 4):
+            if cpl and (G + 64 * cpl - 1) // (64 * cpl) > 8:
+                continue
+            p = B.params(*UNSIGNED, G, 6, cpl)
+            r = B.mmse_scale_search_activation(xd, p)
+            amax, grid = B.mmse_grid_sse_activation(xd, p)
+            torch.cuda.synchronize()
+            tag = f"N={N} G={G} cands_per_lane={cpl}"
+            assert (float(r.scale[0]), int(r.idx[0]), float(r.sse[0])) == (float(o["scale"]), o["idx"], o["sse"]), tag
+            np.testing.assert_array_equal(grid.cpu().numpy().ravel(), o["grid_sse"], err_msg=tag)
