@@ -274,13 +274,15 @@ def test_config1_activations(B):
     assert int(r.idx[0]) == o["idx"] and float(r.scale[0]) == o["scale"] and float(r.sse[0]) == o["sse"]
 
 
-def test_results_do_not_depend_on_tuning_or_repeat(B):
-    say("determinism across cands_per_lane and repeats")
+@pytest.mark.parametrize("G", [256, 512])
+def test_results_do_not_depend_on_tuning_or_repeat(B, G):
+    say(f"determinism across cands_per_lane and repeats, G={G}")
     w = synth.small_weights(50, 1152, 9, "laplace")
     wd = to_dev(w)
-    base = None
+    s, j, e = oracle.can_search_kernelwise(w, *SIGNED, G, 20)
+    base = (s, j, e)
     for cpl in (1, 2, 4, 0, 2):
-        r = B.mmse_scale_search_kernelwise(wd, B.params(*SIGNED, 256, 20, cpl))
+        r = B.mmse_scale_search_kernelwise(wd, B.params(*SIGNED, G, 20, cpl))
         cur = (r.scale.cpu().numpy().copy(), r.idx.cpu().numpy().copy(), r.sse.cpu().numpy().copy())
         if base is None:
             base = cur
