@@ -11,6 +11,7 @@ namespace {
 constexpr int kChunk = 64;             // elements per sequential fp32 chunk
 constexpr int kMaxBatch = 40;          // tensors per launch: the descriptor table lives in kernarg (4 KB at most)
 constexpr int kTile = 8192;            // floats of one kernel staged in LDS at a time
+constexpr int kTileStream = 4096;      // ... for longer kernels, which stream through LDS tile by tile
 constexpr int kLevelsKW = 11;          // binary-counter levels for <= 1024 chunks (65536 elements)
 constexpr int kLevelsKWSmall = 8;      // ... for <= 128 chunks (8192 elements: one LDS tile)
 constexpr int kBlockChunks = 64;       // activation block = 64 chunks = 4096 elements

@@ -110,11 +110,21 @@ template <int C>
 int launch_sweep(const Batch& B, int nwg, int G, int max_npad, hipStream_t s)
 {
     const int waves = (G + 64 * C - 1) / (64 * C);
-    const size_t lds = (size_t)(max_npad < kTile ? max_npad : kTile) * sizeof(float);
-    if (max_npad <= kTile)
-        hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall>), dim3(nwg), dim3(64 * waves), lds, s, B);
-    else
-        hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW>), dim3(nwg), dim3(64 * waves), lds, s, B);
+    // LDS: the longest kernel that is staged whole (<= kTile floats), or the streaming tile of the longer ones
+    int lds_floats = 0;
+    for (int i = 0; i < B.count; ++i) {
+        const int npad = (B.t[i].n + kChunk - 1) & ~(kChunk - 1);
+        const int need = npad <= kTile ? npad : kTileStream;
+        lds_floats = need > lds_floats ? need : lds_floats;
+    }
+    const size_t lds = (size_t)lds_floats * sizeof(float);
+    const dim3 grid(nwg), block(64 * waves);
+    // binary-counter levels for the longest kernel of the launch: each level is two registers per candidate
+    const int chunks = max_npad / kChunk;
+    if (chunks <= 128) hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall>), grid, block, lds, s, B);
+    else if (chunks < 512) hipLaunchKernelGGL((k_sweep_kernelwise<C, 9>), grid, block, lds, s, B);
+    else if (chunks < 1024) hipLaunchKernelGGL((k_sweep_kernelwise<C, 10>), grid, block, lds, s, B);
+    else hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW>), grid, block, lds, s, B);
     return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
 }
 

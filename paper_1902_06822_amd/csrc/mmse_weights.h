@@ -92,8 +92,8 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
     if (single) {
         sweep_slice<C, LV>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st);
     } else {
-        for (int t0 = 0; t0 < npad; t0 += kTile) {
-            const int tlen = (npad - t0) < kTile ? (npad - t0) : kTile;
+        for (int t0 = 0; t0 < npad; t0 += kTileStream) {
+            const int tlen = (npad - t0) < kTileStream ? (npad - t0) : kTileStream;
             __syncthreads();
             for (int i = tid; i < tlen; i += nthreads) {
                 const int gi = t0 + i;
