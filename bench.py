@@ -1,16 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the MMSE INT4 scale search on one MI355X.
 
-A "step" is one pass of the whole hot path over one network's weights: per-kernel
-abs-max, G-point grid sweep, argmin, golden-section refinement and packed INT4
-codes for every tensor of the configuration (default: the ResNet-18-shaped
-configuration 2 of the benchmark spec; 11.7 M weights, G = 256, 20 refinement
-iterations), through ``mmse_scale_search_batched``.  Inputs are resident in HBM
-before the timed region starts.
+Default (``--part whole --config 5``): a "step" is one pass of the whole hot path over the
+VGG-16-shaped configuration of the benchmark spec (configs[4]) -- the largest workload that
+the configurations name: per-kernel abs-max, 512-point grid sweep, argmin, 20 golden-section
+iterations and packed INT4 codes for all 16 weight tensors (138 M weights), the second
+INT4 tensor on the residual of all 16 layers, and search + codes of all 16 calibration
+activation tensors (146 M elements) -- first enqueue to last kernel, inputs resident in
+HBM before the timed region starts, outputs left on the device.
 
-Prints ONE JSON line (see the keys below).  ``roofline`` times the dominant
-kernel (the grid sweep) by itself with HIP events on the launch stream;
-``cpu_baseline`` times the CPU oracle on the same inputs on the host cores.
+Prints ONE JSON line.  ``value`` = (element, candidate) evaluations per second of the whole
+step.  ``roofline`` describes the kernel with the most time per step, timed by itself between
+HIP events on its launch stream (``all_alu_kernels`` lists the others, ``hbm`` the streaming
+passes against the 8 TB/s of HBM3E); ``cpu_baseline`` times the CPU oracle on a bounded sample of
+the same inputs on the host cores and ``matches_oracle`` compares every output on that sample;
+``other_configs`` carries short runs of configurations 1-4.  ``--part weights|activation|dual|
+dual-ls|compare`` time single parts (default configuration 2).
 """
 from __future__ import annotations
 
@@ -34,6 +39,7 @@ METRIC = "element x candidate MSE evals/sec + end-to-end whole-net search ms (1 
 LANE_OPS_PER_S = 256 * 4 * 32 * 2.4e9
 OPS_PER_EVAL = 5          # v_mul, v_rndne, v_med3, v_fma, v_fma(c)
 FLOPS_PER_EVAL = 7        # 1 + 1 + 1 + 2 + 2
+HBM_GBS = 8000.0          # published HBM3E bandwidth of MI355X
 
 
 def bench_activation(args, cfg, torch, B) -> int:
@@ -323,7 +329,57 @@ def bench_compare(args, cfg, torch, B) -> int:
     return 0
 
 
-def bench_whole(args, cfg, torch, B) -> int:
+def _stage_table(rows):
+    """Aggregate [(stage, ms)] lists of several traced calls: stage -> (launches per call, ms per call)."""
+    agg = {}
+    for tr in rows:
+        for st, ms in tr:
+            c, t = agg.get(st, (0, 0.0))
+            agg[st] = (c + 1, t + ms)
+    n = max(1, len(rows))
+    return {st: (c / n, t / n) for st, (c, t) in agg.items()}
+
+
+def _traffic_table():
+    """profiles/hbm_traffic.txt: kernel, workload, fetched bytes, written bytes per launch (rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE, scaled by a device copy of known size in the same run)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            f = line.split("#")[0].split()
+            if len(f) == 4:
+                out[(f[0], f[1])] = (float(f[2]), float(f[3]))
+    return out
+
+
+def _alu_entry(name, evals, launches, ms_total, traffic=None):
+    lane_ops = evals * OPS_PER_EVAL / (ms_total * 1e-3)
+    tflops = evals * FLOPS_PER_EVAL / (ms_total * 1e-3) / 1e12
+    peak = LANE_OPS_PER_S * FLOPS_PER_EVAL / OPS_PER_EVAL / 1e12
+    return {"bound": "alu", "kernel": name, "achieved": round(tflops, 3), "peak": round(peak, 3), "unit": "TFLOP/s",
+            "frac": round(lane_ops / LANE_OPS_PER_S, 4), "traffic": traffic,
+            "launches_per_step": launches, "avg_launch_ms": round(ms_total / max(launches, 1e-9), 5),
+            "evals_per_launch": evals / max(launches, 1e-9), "evals_per_s": evals / (ms_total * 1e-3),
+            "frac_of_157.3_tflops": round(tflops / 157.3, 4)}
+
+
+def _hbm_entry(name, nbytes, launches, ms_total, traffic=None):
+    gbs = nbytes / (ms_total * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": name, "achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_GBS, 4), "traffic": traffic, "launches_per_step": launches,
+            "avg_launch_ms": round(ms_total / max(launches, 1e-9), 5),
+            "algorithmic_bytes_per_launch": nbytes / max(launches, 1e-9)}
+
+
+def _nibbles(packed: np.ndarray, count: int) -> np.ndarray:
+    out = np.empty(packed.size * 2, dtype=np.uint8)
+    out[0::2] = packed & 0xF
+    out[1::2] = packed >> 4
+    return out[:count]
+
+
+def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dict:
     """Everything the configuration names, first enqueue to last kernel: weights (search + codes), the second
     tensor on the selected layers, and search + codes of every layer's calibration activations."""
     from paper_1902_06822_amd import select
@@ -332,142 +388,277 @@ def bench_whole(args, cfg, torch, B) -> int:
     t_gen = time.perf_counter()
     host_w = [cfg.weight_tensor(i) for i in range(len(cfg.weight_shapes))]
     dev_w = [torch.from_numpy(w).cuda() for w in host_w]
-    energy = [float(np.sum(w.astype(np.float64) ** 2)) for w in host_w]        # constants of the network
+    nlayers = len(dev_w)
+    nkey = nlayers if cfg.residual == "all" else (max(1, round(0.10 * nlayers)) if cfg.residual == "top10pct" else 0)
+    energy = [float(np.sum(w.astype(np.float64) ** 2)) for w in host_w] if cfg.residual == "top10pct" else []   # constants of the network
+    keep_host = detail and not args.no_cpu_baseline
+    host_w_shapes = [w.shape for w in host_w]
+    if not keep_host:
+        host_w = None
     dev_x, host_x = [], []
     for i in range(len(cfg.act_shapes)):
-        host_x.append(cfg.act_tensor(i))
-        dev_x.append(torch.from_numpy(host_x[-1]).cuda())
-    if args.no_cpu_baseline:
-        host_x = []
-    print(f"bench.py: inputs generated in {time.perf_counter() - t_gen:.1f} s", file=sys.stderr, flush=True)
+        x = cfg.act_tensor(i)
+        dev_x.append(torch.from_numpy(x).cuda())
+        host_x.append(x if keep_host else None)
+    print(f"bench.py: configuration {cfg.cfg}: inputs generated in {time.perf_counter() - t_gen:.1f} s",
+          file=sys.stderr, flush=True)
     pw = B.params(-8, 7, G, iters, args.cands_per_lane)
     pa = B.params(0, 15, G, iters, args.cands_per_lane)
     plan_w = B.BatchedPlan(dev_w, pw, want_packed=True)
-    nlayers = len(dev_w)
-    if cfg.residual == "all":
-        fixed_key = list(range(nlayers))
-    else:
-        fixed_key = None
-    nkey = nlayers if cfg.residual == "all" else (max(1, round(0.10 * nlayers)) if cfg.residual == "top10pct" else 0)
-    # residual plans are built per selection; buffers for the largest possible selection are kept so that the
-    # timed region allocates nothing: one plan per layer, run individually
-    res_plans = [B.BatchedPlan([dev_w[i]], pw, want_packed=True, scale1=[plan_w.results[i].scale]) for i in range(nlayers)] \
-        if nkey else []
+    fixed_key = list(range(nlayers)) if cfg.residual == "all" else None
+    # second tensor: one plan over all layers (configuration 5), or one plan per layer, run for the layers the
+    # ranking picks (configuration 4); every buffer exists before the timed region
+    res_plans = [B.BatchedPlan([dev_w[i]], pw, want_packed=True, scale1=[plan_w.results[i].scale])
+                 for i in range(nlayers)] if (nkey and not fixed_key) else []
     res_all = B.BatchedPlan(dev_w, pw, want_packed=True, scale1=[r.scale for r in plan_w.results]) if fixed_key else None
-    plan_sums = B.LayerSumsPlan([r.sse for r in plan_w.results])
-    nstreams = max(0, args.streams)              # 0: the batched entry point on one side stream
-    streams = [torch.cuda.Stream() for _ in range(max(1, nstreams))]
+    plan_sums = B.LayerSumsPlan([r.sse for r in plan_w.results]) if res_plans else None
+    side = torch.cuda.Stream()
     order = sorted(range(len(dev_x)), key=lambda i: -dev_x[i].numel())            # large tensors first
-    if nstreams == 0:
+    plan_a, act_out = None, []
+    if dev_x:
         plan_a = B.ActBatchedPlan([dev_x[i] for i in order], pa, want_packed=True)
         act_out = [None] * len(dev_x)
         for n_, i in enumerate(order):
             act_out[i] = plan_a.results[n_]
-    else:
-        act_ws = [B.alloc_workspace(B.mmse_workspace_bytes_activation(x.numel(), pa)) for x in dev_x]
-        act_out = [B.SearchResult(torch.empty(1, dtype=torch.float32, device="cuda"),
-                                  torch.empty(1, dtype=torch.int32, device="cuda"),
-                                  torch.empty(1, dtype=torch.float64, device="cuda"),
-                                  torch.empty((x.numel() + 1) // 2, dtype=torch.uint8, device="cuda")) for x in dev_x]
     key_used = []
 
     def step():
         main = torch.cuda.current_stream()
-        start = torch.cuda.Event()
-        start.record(main)
-        # activations on side streams while the weight path runs on the main stream
-        if nstreams == 0 and args.serial:
-            plan_a.run()
-        elif nstreams == 0:
-            streams[0].wait_event(start)
-            with torch.cuda.stream(streams[0]):
+        if plan_a is not None and not args.serial:
+            # activations on a side stream while the weight path runs on the main stream
+            start = torch.cuda.Event()
+            start.record(main)
+            side.wait_event(start)
+            with torch.cuda.stream(side):
                 plan_a.run()
-        for n_, i in enumerate(order if nstreams else []):
-            st = streams[n_ % nstreams]
-            if n_ < nstreams:
-                st.wait_event(start)
-            with torch.cuda.stream(st):
-                B.mmse_scale_search_activation(dev_x[i], pa, act_ws[i], act_out[i])
-                B.quantize_pack_int4(dev_x[i], act_out[i].scale, 0, 15, act_out[i].packed)
-        res = plan_w.run()
+        elif plan_a is not None:
+            plan_a.run()
+        plan_w.run()
         if res_all is not None:
             res_all.run()
-        elif nkey:
+        elif res_plans:
             sums = plan_sums.run().cpu().numpy()           # one small kernel, one device-to-host copy; the ranking is host logic
             key = select.select_top_fraction(select.normalized_mse(list(sums), energy), 0.10)
             key_used[:] = key
             for i in key:
                 res_plans[i].run()
-        for st in streams:
-            main.wait_stream(st)
+        if plan_a is not None and not args.serial:
+            main.wait_stream(side)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
     P = G + 2 + iters
-    w_elems = sum(w.size for w in host_w)
-    key_elems = w_elems if fixed_key else sum(host_w[i].size for i in key_used)
+    w_elems = sum(K * n for K, n in host_w_shapes)
+    key_elems = w_elems if fixed_key else sum(host_w_shapes[i][0] * host_w_shapes[i][1] for i in key_used)
     a_elems = sum(x.numel() for x in dev_x)
     evals = (w_elems + key_elems + a_elems) * P
-    cpu_baseline, parity = None, None
-    if not args.no_cpu_baseline:
+    out = {"ms_per_step": ms_per_step, "evals_per_step": evals, "value": evals / (ms_per_step * 1e-3),
+           "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] whole network ({cfg.name}): kernel-wise weight "
+                                  f"search + codes, second tensor ({cfg.residual}), search + codes of all calibration "
+                                  f"activations",
+                      "weight_tensors": nlayers, "weights": w_elems,
+                      "second_tensor_layers": (nlayers if fixed_key else list(key_used)),
+                      "activation_tensors": len(dev_x), "activation_elements": a_elems, "grid_points": G,
+                      "refine_iters": iters, "ranges": "weights signed INT4 (-8..7), activations unsigned INT4 (0..15)",
+                      "streams": "one" if (args.serial or plan_a is None) else "weights on the main stream, activations on a side stream",
+                      "evals_per_step": evals}}
+
+    # ---- every kernel by itself: the weight path, the second tensor and the activation path one after the other on
+    # one stream, HIP events on that stream around every launch (mmse_trace_*)
+    reps = max(3, min(10, steps))
+    trace = B.StageTrace(512)
+    traffic = _traffic_table()
+    wl = f"cfg{cfg.cfg}"
+
+    def traced(plan):
+        rows = []
+        for _ in range(reps):
+            plan.run_traced(trace)
+            rows.append(trace.read())
+        return _stage_table(rows)
+
+    kernels = []
+    tw = traced(plan_w)
+    sw_l = tw.get(1, (0, 0.0))[0] + tw.get(2, (0, 0.0))[0]
+    sw_ms = tw.get(1, (0, 0.0))[1] + tw.get(2, (0, 0.0))[1]
+    e_w = _alu_entry("k_sweep_kernelwise (+ k_sweep_small): abs-max, grid sweep, argmin of all weight tensors",
+                     w_elems * G, sw_l, sw_ms, traffic.get(("k_sweep_kernelwise", wl), (None,))[0])
+    kernels.append(e_w)
+    rf_l = tw.get(3, (0, 0.0))[0] + tw.get(4, (0, 0.0))[0]
+    rf_ms = tw.get(3, (0, 0.0))[1] + tw.get(4, (0, 0.0))[1]
+    if rf_l:
+        kernels.append(_alu_entry("k_refine_kernelwise: golden-section refinement (+ codes) of all weight tensors",
+                                  w_elems * (2 + iters), rf_l, rf_ms))
+    weights_alone_ms = sum(t for _, t in tw.values())
+    second_alone_ms = 0.0
+    if res_all is not None:
+        tr2 = traced(res_all)
+        l2 = tr2.get(1, (0, 0.0))[0] + tr2.get(2, (0, 0.0))[0]
+        m2 = tr2.get(1, (0, 0.0))[1] + tr2.get(2, (0, 0.0))[1]
+        kernels.append(_alu_entry("k_sweep_kernelwise on the residual of the first tensor (second tensor, all layers)",
+                                  w_elems * G, l2, m2))
+        second_alone_ms = sum(t for _, t in tr2.values())
+    acts_alone_ms = 0.0
+    hbm = []
+    if plan_a is not None:
+        ta = traced(plan_a)
+        acts_alone_ms = sum(t for _, t in ta.values())
+        l, m = ta[12]
+        kernels.append(_alu_entry("k_act_sweep: grid sweep of all activation tensors", a_elems * G, l, m,
+                                  traffic.get(("k_act_sweep", wl), (None,))[0]))
+        l, m = ta[11]
+        tf = traffic.get(("k_act_absmax", wl))
+        hbm.append(_hbm_entry("k_act_absmax: max |x| of every activation tensor", 4.0 * a_elems, l, m,
+                              tf[0] + tf[1] if tf else None))
+        if 15 in ta:
+            l, m = ta[15]
+            tf = traffic.get(("k_act_probe", wl))
+            hbm.append(_hbm_entry("k_act_probe: one refinement pass over every activation tensor (up to 8 scales per element)",
+                                  4.0 * a_elems * l, l, m, tf[0] + tf[1] if tf else None))
+            if iters == 20:      # 2+2+4 scales per element in the first pass, 1+2+4 in each of the others
+                ev = (8 + 7 * (l - 1)) * a_elems
+                hbm[-1]["scales_evaluated_per_element"] = 8 + 7 * (round(l) - 1)
+                hbm[-1]["alu_frac"] = round(ev * OPS_PER_EVAL / (m * 1e-3) / LANE_OPS_PER_S, 4)
+        l, m = ta[18]
+        tf = traffic.get(("k_act_pack", wl))
+        hbm.append(_hbm_entry("k_act_pack: INT4 codes of every activation tensor", 4.5 * a_elems, l, m,
+                              tf[0] + tf[1] if tf else None))
+    trace.close()
+    dominant = max(kernels, key=lambda e: e["avg_launch_ms"] * e["launches_per_step"])
+    roofline = dict(dominant)
+    roofline["note"] = ("alu peak = 256 CUs x 4 SIMDs x 32 lanes/clk x 2.4 GHz = 78.6e12 VALU lane-ops/s (= 157.3 TFLOP/s fp32 "
+                        "vector when every instruction is an FMA); an evaluation is 5 instructions / 7 flops, so the peak in "
+                        "flops of this mix is 110.1 TFLOP/s; frac = lane-ops/s over 78.6e12.  Each kernel timed by itself "
+                        "between HIP events on its launch stream, after the timed steps.")
+    roofline["all_alu_kernels"] = kernels
+    roofline["hbm"] = hbm
+    roofline["hbm_note"] = (f"activation set {4 * a_elems / 1e6:.0f} MB, read once per pass; the chip's last-level cache is 256 MB"
+                            if dev_x else "no activation tensors in this configuration")
+    out["roofline"] = roofline
+    out["alone_ms"] = {"weights": round(weights_alone_ms, 4), "second_tensor": round(second_alone_ms, 4),
+                       "activations": round(acts_alone_ms, 4),
+                       "note": "each path by itself on one stream (sum of its kernels between events)"}
+
+    # ---- CPU oracle (reported baseline, not the target) on a bounded sample of the same workload, and parity on it
+    out["cpu_baseline"], out["matches_oracle"] = None, None
+    if keep_host:
         import oracle
-        got_act = [(float(o.scale[0]), int(o.idx[0]), float(o.sse[0])) for o in act_out]
-        got_w = [(r.scale.cpu().numpy(), r.idx.cpu().numpy()) for r in plan_w.results]
-        t0 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        every = max(1, args.cpu_sample_every)
         ok, sample = True, 0
-        for i, x in enumerate(host_x):                       # search only: the codes are checked by the tests
-            o = oracle.can_search(x, 0, 15, G, iters)
-            ok = ok and got_act[i] == (float(o["scale"]), o["idx"], o["sse"])
-            sample += x.size * P
+        secs = 0.0
         for i, w in enumerate(host_w):
-            sref, jref, eref = oracle.can_search_kernelwise(w, -8, 7, G, iters)
-            ok = ok and np.array_equal(got_w[i][0], sref) and np.array_equal(got_w[i][1], jref)
-            sample += w.size * P
-        dt = time.perf_counter() - t0
-        cpu_baseline = {"value": sample / dt, "unit": "evals/s", "cores": oracle.num_threads(), "kind": "oracle",
-                        "sample": "first search of every weight tensor and of every activation tensor, once "
-                                  "(no second tensor, no codes)", "seconds": round(dt, 3)}
-        parity = bool(ok)
+            K, n = w.shape
+            rows = np.arange(i % every, K, every)
+            if rows.size == 0:
+                continue
+            wr = np.ascontiguousarray(w[rows])
+            r1 = plan_w.results[i]
+            g_s, g_j, g_e = r1.scale.cpu().numpy(), r1.idx.cpu().numpy(), r1.sse.cpu().numpy()
+            g_nib = _nibbles(r1.packed.cpu().numpy(), K * n).reshape(K, n)[rows]
+            t0 = time.perf_counter()
+            s1, j1, e1 = oracle.can_search_kernelwise(wr, -8, 7, G, iters)
+            pk = oracle.can_quantize_pack_int4(wr, s1, -8, 7)
+            secs += time.perf_counter() - t0
+            sample += wr.size * P
+            ok = ok and np.array_equal(g_s[rows], s1) and np.array_equal(g_j[rows], j1) \
+                and np.allclose(g_e[rows], e1, rtol=1e-4, atol=0) \
+                and np.array_equal(g_nib, _nibbles(pk, wr.size).reshape(rows.size, n))
+            r2 = res_all.results[i] if res_all is not None else (res_plans[i].results[0] if i in key_used else None)
+            if r2 is not None:
+                g2_nib = _nibbles(r2.packed.cpu().numpy(), K * n).reshape(K, n)[rows]
+                t0 = time.perf_counter()
+                s2, j2, e2, p2 = oracle.can_residual_quantize(wr, s1, -8, 7, G, iters)
+                secs += time.perf_counter() - t0
+                sample += wr.size * P
+                ok = ok and np.array_equal(r2.scale.cpu().numpy()[rows], s2) and np.array_equal(r2.idx.cpu().numpy()[rows], j2) \
+                    and np.allclose(r2.sse.cpu().numpy()[rows], e2, rtol=1e-4, atol=0) \
+                    and np.array_equal(g2_nib, _nibbles(p2, wr.size).reshape(rows.size, n))
+        act_sampled = []
+        for n_, i in enumerate(order):                       # every `every`-th tensor in size order
+            if n_ % every != (1 % every):
+                continue
+            x = host_x[i]
+            g = act_out[i]
+            t0 = time.perf_counter()
+            o = oracle.can_search(x, 0, 15, G, iters)
+            pk = oracle.can_quantize_pack_int4(x, [o["scale"]], 0, 15)
+            secs += time.perf_counter() - t0
+            sample += x.size * P
+            act_sampled.append(cfg.act_shapes[i].name)
+            ok = ok and (float(g.scale[0]), int(g.idx[0])) == (float(o["scale"]), o["idx"]) \
+                and abs(float(g.sse[0]) - o["sse"]) <= 1e-4 * o["sse"] and np.array_equal(g.packed.cpu().numpy(), pk)
+        what = "the full workload: first and second tensor of every weight kernel and every activation tensor, search + codes" if every == 1 else \
+            (f"every {every}th kernel of every weight tensor (first and second tensor, codes included) and "
+             f"{len(act_sampled)} of {len(dev_x)} activation tensors ({', '.join(act_sampled)}; search + codes)")
+        out["cpu_baseline"] = {"value": sample / secs, "unit": "evals/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": what, "sample_evals": sample, "seconds": round(secs, 3)}
+        out["matches_oracle"] = bool(ok)
+    return out
+
+
+def bench_whole(args, cfg, torch, B) -> int:
+    res = run_whole(args, cfg, torch, B, detail=True, steps=args.steps, warmup=args.warmup)
+    others = {}
+    if not args.headline_only:
+        from paper_1902_06822_amd import synth
+        import gc
+        for c in (1, 2, 3, 4):
+            if c == cfg.cfg:
+                continue
+            gc.collect()
+            torch.cuda.empty_cache()
+            ocfg = synth.config(c)
+            big = c == 4
+            r = run_whole(args, ocfg, torch, B, detail=False, steps=(args.steps if big else 10 * args.steps),
+                          warmup=(args.warmup if big else 10 * args.warmup))
+            alu = r["roofline"]["all_alu_kernels"]
+            others[f"configs[{c - 1}]"] = {
+                "workload": r["config"]["workload"], "ms_per_step": r["ms_per_step"], "evals_per_s": r["value"],
+                "evals_per_step": r["evals_per_step"], "alone_ms": r["alone_ms"],
+                "alu_frac_by_kernel": {e["kernel"].split(":")[0]: e["frac"] for e in alu},
+                "hbm_frac_by_kernel": {e["kernel"].split(":")[0]: e["frac"] for e in r["roofline"]["hbm"]},
+                "second_tensor_layers": r["config"]["second_tensor_layers"]}
     print(json.dumps({
-        "metric": METRIC, "value": evals / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "metric": METRIC, "value": res["value"], "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"BASELINE.json configs[{cfg.cfg - 1}] whole network: weights, second tensor "
-                               f"({cfg.residual}), all calibration activations",
-                   "weight_tensors": nlayers, "weights": w_elems, "second_tensor_layers": (nlayers if fixed_key else key_used),
-                   "activation_tensors": len(dev_x), "activation_elements": a_elems, "grid_points": G,
-                   "refine_iters": iters,
-                   "activations": "batched entry point" if nstreams == 0 else f"per tensor on {nstreams} streams",
-                   "evals_per_step": evals},
-        "roofline": None, "cpu_baseline": cpu_baseline, "matches_oracle": parity}))
+        "config": res["config"], "alone_ms": res["alone_ms"], "roofline": res["roofline"],
+        "cpu_baseline": res["cpu_baseline"], "matches_oracle": res["matches_oracle"],
+        "other_configs": others}))
     return 0
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=50,
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10,
                     help="untimed steps; the GPU needs some tens of milliseconds of work to reach its steady clock")
-    ap.add_argument("--config", type=int, default=2, help="BASELINE.json configuration (weights part)")
+    ap.add_argument("--config", type=int, default=0,
+                    help="BASELINE.json configuration, 1..5 (default: 5 for --part whole, 2 for the other parts)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="--part whole: skip the short runs of the other configurations (the other_configs key)")
+    ap.add_argument("--cpu-sample-every", type=int, default=1,
+                    help="--part whole: 1 = the oracle runs on the full workload (about 10 s on 16 host threads); "
+                         "n > 1 = on every n-th kernel of every weight tensor and every n-th activation tensor")
     ap.add_argument("--cands-per-lane", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--part", choices=("weights", "activation", "dual", "dual-ls", "compare", "whole"), default="weights",
-                    help="weights: the whole-net kernel-wise path (default); activation: the largest "
-                         "calibration tensor of the configuration through the per-layer path")
+    ap.add_argument("--part", choices=("weights", "activation", "dual", "dual-ls", "compare", "whole"), default="whole",
+                    help="whole (default): everything the configuration names, end to end; weights: the kernel-wise "
+                         "path alone; activation: the largest calibration tensor through the per-layer path; "
+                         "dual, dual-ls, compare: the two-tensor methods and the comparison optimisers")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run plain device copies of this many MiB (for scaling FETCH_SIZE/WRITE_SIZE "
                          "counters under rocprofv3 --pmc); not part of any timed region")
     ap.add_argument("--pair-grid", type=int, default=32, help="G1 = G2 of --part dual-ls")
-    ap.add_argument("--streams", type=int, default=0,
-                    help="--part whole: 0 = all activation tensors through the batched entry point (default); "
-                         "N > 0 = one call per tensor, spread over N side streams")
     ap.add_argument("--act-variant", choices=("plain", "residual", "offset"), default="plain",
                     help="--part activation: the per-layer search alone, with the second tensor, or in offset form")
     ap.add_argument("--serial", action="store_true", help="--part whole: activations and weights one after the other on one stream")
@@ -496,6 +687,8 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    if args.config == 0:
+        args.config = 5 if args.part == "whole" else 2
     cfg = synth.config(args.config)
     if args.part == "activation":
         return bench_activation(args, cfg, torch, B)
@@ -549,7 +742,10 @@ def main() -> int:
     # ---- dominant kernel alone: grid sweep + argmin (refine_iters = 0, no packing => one kernel per launch)
     p_sweep = B.params(-8, 7, G, 0, args.cands_per_lane)
     sweep_plan = B.BatchedPlan(dev_w, p_sweep, want_packed=False)
-    nlaunch = (len(dev_w) + 31) // 32
+    trace = B.StageTrace(256)
+    sweep_plan.run_traced(trace)
+    nlaunch = len(trace.read())                 # sweep launches of one call (general and small-kernel passes)
+    trace.close()
     for _ in range(max(1, args.warmup)):
         sweep_plan.run()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -571,10 +767,9 @@ def main() -> int:
         "peak": round(peak_tflops, 3),
         "unit": "TFLOP/s",
         "frac": round(achieved_tflops / peak_tflops, 4),
-        # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
-        # (profiles/weights_cfg2_resnet18.md; counters scaled by a 1 GiB copy in the same run); only
-        # measured for the default configuration
-        "traffic": 47.6e6 if (args.config == 2 and args.grid_points == 0) else None,
+        # HBM-side bytes per step from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/hbm_traffic.txt)
+        "traffic": (lambda t: (t[0] + t[1]) if t else None)(_traffic_table().get(("k_sweep_kernelwise", f"cfg{args.config}"))
+                                                            if args.grid_points == 0 else None),
         "algorithmic_bytes": 4 * elements,
         "avg_launch_ms": round(sweep_ms / nlaunch, 5),
         "launches_per_step": nlaunch,

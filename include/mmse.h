@@ -12,7 +12,9 @@
  *
  * General conventions
  *   - every *_dev pointer is DEVICE memory owned by the caller; the library
- *     allocates nothing, keeps no state between calls and never synchronises:
+ *     allocates no device memory (a batched call of more than 64 tensors builds
+ *     its descriptor table in temporary host memory), keeps no state between
+ *     calls and never synchronises:
  *     all work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and results are valid once the stream has drained.
  *   - weight tensors are fp32, row-major [K][n]: K kernels of n elements
@@ -43,7 +45,8 @@ typedef enum mmse_status_t {
     MMSE_ERR_PARAMS = -3,      /* bad quantization range, grid size or refine count    */
     MMSE_ERR_WORKSPACE = -4,   /* ws_dev NULL / misaligned / ws_bytes too small        */
     MMSE_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch                     */
-    MMSE_ERR_ALIGN = -6        /* a device pointer is not aligned to its element type  */
+    MMSE_ERR_ALIGN = -6,       /* a device pointer is not aligned to its element type  */
+    MMSE_ERR_HOST_MEMORY = -7  /* host memory for a batched call's tables ran out      */
 } mmse_status_t;
 
 /* Limits (checked; MMSE_ERR_SIZE / MMSE_ERR_PARAMS otherwise). */
@@ -251,6 +254,40 @@ int mmse_grid_sse_kernelwise(const float *w_dev, int64_t K, int64_t n, const mms
  * the whole tensor in the library's fixed order.  Workspace: mmse_workspace_bytes_activation(N, p). */
 int mmse_grid_sse_activation(const float *x_dev, int64_t N, const mmse_params_t *p, float *absmax_dev,
                              double *grid_sse_dev, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Measurement aid (no part of the method): the two batched searches with a HIP event recorded on `stream`
+ * before the first and after every kernel launch, so that a harness can read how long each kernel of a call
+ * took without a profiler.  A trace object owns `capacity` (2..4096) events; a traced call overwrites what the
+ * trace held.  mmse_trace_read waits for the last event and returns, for each kernel launch i in launch order,
+ * stage_out[i] = MMSE_STAGE_* of the kernel and ms_out[i] = time from the previous event to the event after it
+ * (kernel duration plus the launch gap, a few microseconds); launches beyond the trace's capacity are not
+ * recorded.  Results of a traced call are those of the plain call. */
+typedef struct mmse_trace mmse_trace_t;
+enum {
+    MMSE_STAGE_START = 0,
+    MMSE_STAGE_W_SWEEP = 1,         /* k_sweep_kernelwise: abs-max, grid sweep, argmin (Section 3.4)      */
+    MMSE_STAGE_W_SWEEP_SMALL = 2,   /* k_sweep_small: the same for kernels of <= 64 elements             */
+    MMSE_STAGE_W_REFINE = 3,        /* k_refine_kernelwise<64>: refinement (+ codes when n is even)      */
+    MMSE_STAGE_W_REFINE_SMALL = 4,  /* k_refine_kernelwise<16>                                           */
+    MMSE_STAGE_W_PACK = 5,          /* k_pack_int4                                                       */
+    MMSE_STAGE_A_INIT = 10,
+    MMSE_STAGE_A_ABSMAX = 11,       /* k_act_absmax                                                      */
+    MMSE_STAGE_A_SWEEP = 12,        /* k_act_sweep (Section 3.7, Eq. 15)                                 */
+    MMSE_STAGE_A_REDUCE = 13,       /* k_act_reduce64 over the grid sums                                 */
+    MMSE_STAGE_A_ARGMIN = 14,
+    MMSE_STAGE_A_PROBE = 15,        /* k_act_probe: one refinement pass over the tensors                 */
+    MMSE_STAGE_A_PROBE_REDUCE = 16,
+    MMSE_STAGE_A_FINISH = 17,
+    MMSE_STAGE_A_PACK = 18          /* k_act_pack                                                        */
+};
+int mmse_trace_create(int32_t capacity, mmse_trace_t **trace_out);
+void mmse_trace_destroy(mmse_trace_t *trace);
+int mmse_trace_read(mmse_trace_t *trace, int32_t capacity, int32_t *count_out, int32_t *stage_out, float *ms_out);
+int mmse_scale_search_batched_traced(const mmse_tensor_desc_t *descs_host, int32_t count, const mmse_params_t *p,
+                                     void *ws_dev, size_t ws_bytes, void *stream, mmse_trace_t *trace);
+int mmse_scale_search_activation_batched_traced(const mmse_act_desc_t *descs_host, int32_t count,
+                                                const mmse_params_t *p, void *ws_dev, size_t ws_bytes,
+                                                void *stream, mmse_trace_t *trace);
 
 const char *mmse_status_string(int status);
 

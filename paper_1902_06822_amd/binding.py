@@ -26,8 +26,17 @@ EXPORTS = (
     "activation_residual_quantize", "mmse_scale_search_offset", "mmse_scale_alternating_kernelwise",
     "mmse_workspace_bytes_activation_batched", "mmse_scale_search_activation_batched", "mmse_layer_error_sums",
     "mmse_grid_sse_activation",
+    "mmse_trace_create", "mmse_trace_read", "mmse_scale_search_batched_traced",
+    "mmse_scale_search_activation_batched_traced",
     "mmse_status_string",
 )
+VOID_EXPORTS = ("mmse_trace_destroy",)
+
+# MMSE_STAGE_* of include/mmse.h: the kernel a traced launch ran
+STAGE_NAMES = {1: "k_sweep_kernelwise", 2: "k_sweep_small", 3: "k_refine_kernelwise<64>", 4: "k_refine_kernelwise<16>",
+               5: "k_pack_int4", 10: "k_act_init", 11: "k_act_absmax", 12: "k_act_sweep", 13: "k_act_reduce64 (grid sums)",
+               14: "k_act_argmin", 15: "k_act_probe", 16: "k_act_reduce64 (probe sums)", 17: "k_act_finish",
+               18: "k_act_pack"}
 
 
 class MmseParams(C.Structure):
@@ -93,6 +102,12 @@ def load_library() -> C.CDLL:
                                                          C.c_size_t, vp]
     lib.mmse_layer_error_sums.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_int64), i32, vp, vp]
     lib.mmse_grid_sse_activation.argtypes = [vp, i64, pp, vp, vp, vp, C.c_size_t, vp]
+    lib.mmse_trace_create.argtypes = [i32, C.POINTER(vp)]
+    lib.mmse_trace_destroy.argtypes = [vp]
+    lib.mmse_trace_destroy.restype = None
+    lib.mmse_trace_read.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float)]
+    lib.mmse_scale_search_batched_traced.argtypes = [C.POINTER(MmseTensorDesc), i32, pp, vp, C.c_size_t, vp, vp]
+    lib.mmse_scale_search_activation_batched_traced.argtypes = [C.POINTER(MmseActDesc), i32, pp, vp, C.c_size_t, vp, vp]
     lib.mmse_status_string.argtypes = [C.c_int]
     lib.mmse_status_string.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -116,6 +131,38 @@ def params(qmin: int, qmax: int, grid_points: int, refine_iters: int, cands_per_
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+class StageTrace:
+    """Per-kernel durations of a traced batched call (``mmse_trace_*``): HIP events on the launch stream."""
+
+    def __init__(self, capacity: int = 256):
+        self.capacity = capacity
+        self._h = C.c_void_p(None)
+        _check(load_library().mmse_trace_create(capacity, C.byref(self._h)), "mmse_trace_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def read(self):
+        """[(stage id, milliseconds)] per kernel launch, in launch order (waits for the last kernel)."""
+        n = C.c_int32(0)
+        stages = (C.c_int32 * self.capacity)()
+        ms = (C.c_float * self.capacity)()
+        _check(load_library().mmse_trace_read(self._h, self.capacity, C.byref(n), stages, ms), "mmse_trace_read")
+        return [(int(stages[i]), float(ms[i])) for i in range(n.value)]
+
+    def close(self):
+        if self._h:
+            load_library().mmse_trace_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -250,6 +297,12 @@ class BatchedPlan:
         _check(load_library().mmse_scale_search_batched(self.descs, len(self.weights), C.byref(self.p),
                                                         self.ws.data_ptr(), self.ws.numel(), _stream()),
                "mmse_scale_search_batched")
+        return self.results
+
+    def run_traced(self, trace: StageTrace) -> List[SearchResult]:
+        _check(load_library().mmse_scale_search_batched_traced(self.descs, len(self.weights), C.byref(self.p),
+                                                               self.ws.data_ptr(), self.ws.numel(), _stream(),
+                                                               trace.handle), "mmse_scale_search_batched_traced")
         return self.results
 
 
@@ -478,6 +531,12 @@ class ActBatchedPlan:
         _check(load_library().mmse_scale_search_activation_batched(self.descs, len(self.tensors), C.byref(self.p),
                                                                    self.ws.data_ptr(), self.ws.numel(), _stream()),
                "mmse_scale_search_activation_batched")
+        return self.results
+
+    def run_traced(self, trace: StageTrace) -> List[SearchResult]:
+        _check(load_library().mmse_scale_search_activation_batched_traced(
+            self.descs, len(self.tensors), C.byref(self.p), self.ws.data_ptr(), self.ws.numel(), _stream(),
+            trace.handle), "mmse_scale_search_activation_batched_traced")
         return self.results
 
 

@@ -37,6 +37,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <limits.h>
+#include <new>
 
 #include "mmse.h"
 
@@ -52,6 +53,28 @@ namespace {
 // host side
 // ---------------------------------------------------------------------------------
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace
+
+// Measurement aid: HIP events recorded on the launch stream after every kernel of a traced call.
+struct mmse_trace {
+    int capacity;
+    int used;
+    hipEvent_t* ev;
+    int* stage;
+};
+
+namespace {
+
+thread_local mmse_trace* t_trace = nullptr;     // set for the duration of a *_traced call on this host thread
+
+inline void trace_mark(hipStream_t s, int stage)
+{
+    mmse_trace* T = t_trace;
+    if (!T || T->used >= T->capacity) return;
+    if (hipEventRecord(T->ev[T->used], s) != hipSuccess) return;
+    T->stage[T->used++] = stage;
+}
 
 // A launch holds at most 2^32 - 1 work-items.  Workgroups have up to 512 threads where their count follows the
 // number of kernels or blocks (1024 only for kernels of more than 32768 elements, of which a tensor has fewer
@@ -125,6 +148,7 @@ int launch_sweep(const Batch& B, int nwg, int G, int max_npad, hipStream_t s)
     else if (chunks < 512) hipLaunchKernelGGL((k_sweep_kernelwise<C, 9>), grid, block, lds, s, B);
     else if (chunks < 1024) hipLaunchKernelGGL((k_sweep_kernelwise<C, 10>), grid, block, lds, s, B);
     else hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW>), grid, block, lds, s, B);
+    trace_mark(s, MMSE_STAGE_W_SWEEP);
     return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
 }
 
@@ -177,6 +201,7 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
                     else if (cs <= 2) hipLaunchKernelGGL(k_sweep_small<2>, dim3(wg), dim3(256), 0, s, B);
                     else if (cs <= 4) hipLaunchKernelGGL(k_sweep_small<4>, dim3(wg), dim3(256), 0, s, B);
                     else hipLaunchKernelGGL(k_sweep_small<8>, dim3(wg), dim3(256), 0, s, B);
+                    trace_mark(s, MMSE_STAGE_W_SWEEP_SMALL);
                     rc = hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
                 }
                 nb = 0; wg = 0; max_npad = 0;
@@ -222,6 +247,7 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
                         if (xf) hipLaunchKernelGGL((k_refine_kernelwise<kChunk, true>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
                         else hipLaunchKernelGGL((k_refine_kernelwise<kChunk, false>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
                     }
+                    trace_mark(s, cls == 0 ? MMSE_STAGE_W_REFINE_SMALL : MMSE_STAGE_W_REFINE);
                     nb = 0; wg = 0;
                     return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
                 };
@@ -255,6 +281,7 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
             B.start[nb] = wg;
             B.count = nb;
             hipLaunchKernelGGL(k_pack_int4, dim3(wg), dim3(kPackThreads), 0, s, B);
+            trace_mark(s, MMSE_STAGE_W_PACK);
             nb = 0; wg = 0;
             return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
         };
@@ -378,6 +405,7 @@ const char* mmse_status_string(int status)
         case MMSE_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
         case MMSE_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
         case MMSE_ERR_ALIGN: return "a device pointer is not aligned to its element type";
+        case MMSE_ERR_HOST_MEMORY: return "host memory for the call's descriptor tables could not be allocated";
         default: return "unknown status";
     }
 }
@@ -438,7 +466,14 @@ int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t coun
     }
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < round256((size_t)sumK * sizeof(float)))
         return MMSE_ERR_WORKSPACE;
-    Item* items = new Item[count]();       // value-initialised: every optional pointer starts as nullptr
+    // the host-side table: on the stack for up to kStackItems tensors, else temporary host memory
+    constexpr int kStackItems = 64;
+    Item stack_items[kStackItems] = {};
+    Item* items = stack_items;
+    if (count > kStackItems) {
+        items = new (std::nothrow) Item[count]();       // value-initialised: every optional pointer starts as nullptr
+        if (!items) return MMSE_ERR_HOST_MEMORY;
+    }
     float* ws = static_cast<float*>(ws_dev);
     long long off = 0;
     for (int i = 0; i < count; ++i) {
@@ -452,7 +487,7 @@ int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t coun
         off += d.K;
     }
     rc = run_weight_tensors(items, count, p, true, static_cast<hipStream_t>(stream));
-    delete[] items;
+    if (items != stack_items) delete[] items;
     return rc;
 }
 
@@ -544,8 +579,9 @@ int dual_quantize_alternating_batched(const mmse_dual_desc_t* descs_host, int32_
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     struct W { float* absmax; int32_t* idx; float *ts1, *ts2; double *tsse1, *tsse; uint8_t *active, *accepted, *tp1, *tp2; };
-    W* wk = new W[count]();
-    Item* items = new Item[count]();
+    W* wk = new (std::nothrow) W[count]();
+    Item* items = new (std::nothrow) Item[count]();
+    if (!wk || !items) { delete[] wk; delete[] items; return MMSE_ERR_HOST_MEMORY; }
     {
         char* ws = static_cast<char*>(ws_dev);
         for (int i = 0; i < count; ++i) {
@@ -800,10 +836,10 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     pre.mode = pre_mode;
     pre.s = pre_mode == 1 ? scale1_dev : (pre_mode == 2 ? &S->delta : nullptr);
     pre.lo1 = (float)qmin1; pre.hi1 = (float)qmax1;
-#define MMSE_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH; } while (0)
+#define MMSE_CHECK_LAUNCH(stage) do { if (hipGetLastError() != hipSuccess) return MMSE_ERR_LAUNCH; trace_mark(s, stage); } while (0)
 
     hipLaunchKernelGGL(k_act_init, dim3(1), dim3(64), 0, s, S, count);
-    MMSE_CHECK_LAUNCH();
+    MMSE_CHECK_LAUNCH(MMSE_STAGE_A_INIT);
     {
         // per tensor at most one workgroup per CU, eight 16-byte loads in flight per thread: measured fastest
         // on MI355X (6.9 TB/s on a 205 MB tensor; more, smaller workgroups lose up to 2x)
@@ -818,10 +854,10 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         if (pre_mode == 0) hipLaunchKernelGGL((k_act_absmax<U, 0>), g, dim3(256), 0, s, B, pre);
         else if (pre_mode == 1) hipLaunchKernelGGL((k_act_absmax<U, 1>), g, dim3(256), 0, s, B, pre);
         else hipLaunchKernelGGL((k_act_absmax<U, 2>), g, dim3(256), 0, s, B, pre);
-        MMSE_CHECK_LAUNCH();
+        MMSE_CHECK_LAUNCH(MMSE_STAGE_A_ABSMAX);
         if (pre_mode == 2) {
             hipLaunchKernelGGL(k_act_offset_setup, dim3(1), dim3(64), 0, s, S, delta_dev);
-            MMSE_CHECK_LAUNCH();
+            MMSE_CHECK_LAUNCH(MMSE_STAGE_A_ABSMAX);
         }
     }
     {
@@ -834,13 +870,13 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
         else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
         else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
-        MMSE_CHECK_LAUNCH();
+        MMSE_CHECK_LAUNCH(MMSE_STAGE_A_SWEEP);
     }
     for (int l = 0; l < P.levels; ++l) {
         hipLaunchKernelGGL(k_act_reduce64, dim3(P.total_rows[l + 1], (G + 255) / 256), dim3(256), 0, s, B, l + 1,
                            reinterpret_cast<const double*>(ws + P.off_part[l]), G,
                            reinterpret_cast<double*>(ws + P.off_part[l + 1]));
-        MMSE_CHECK_LAUNCH();
+        MMSE_CHECK_LAUNCH(MMSE_STAGE_A_REDUCE);
     }
     {
         int threads = ((G + 63) / 64) * 64;
@@ -848,25 +884,25 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         hipLaunchKernelGGL(k_act_argmin, dim3(count), dim3(threads), 0, s, B, P.levels,
                            reinterpret_cast<const double*>(ws + P.off_part[P.levels]), G, p->qmax, p->refine_iters, O,
                            absmax_out, grid_out);
-        MMSE_CHECK_LAUNCH();
+        MMSE_CHECK_LAUNCH(MMSE_STAGE_A_ARGMIN);
     }
     for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
         hipLaunchKernelGGL(k_act_probe, dim3((total + 3) / 4), dim3(256), 0, s, B, lo, hi,
                            reinterpret_cast<double*>(ws + P.off_probe[0]), pre);
-        MMSE_CHECK_LAUNCH();
+        MMSE_CHECK_LAUNCH(MMSE_STAGE_A_PROBE);
         for (int l = 0; l < P.plevels; ++l) {
             hipLaunchKernelGGL(k_act_reduce64, dim3(P.total_rows[l + 1], 1), dim3(64), 0, s, B, l + 1,
                                reinterpret_cast<const double*>(ws + P.off_probe[l]), kMaxProbes,
                                reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
-            MMSE_CHECK_LAUNCH();
+            MMSE_CHECK_LAUNCH(MMSE_STAGE_A_PROBE_REDUCE);
         }
         hipLaunchKernelGGL(k_act_finish, dim3(count), dim3(512), 0, s, B, P.plevels,
                            reinterpret_cast<const double*>(ws + P.off_probe[P.plevels]), p->refine_iters, O);
-        MMSE_CHECK_LAUNCH();
+        MMSE_CHECK_LAUNCH(MMSE_STAGE_A_FINISH);
     }
     if (any_packed) {
         hipLaunchKernelGGL(k_act_pack, dim3(total), dim3(kPackThreads), 0, s, B, pre, O, lo, hi);
-        MMSE_CHECK_LAUNCH();
+        MMSE_CHECK_LAUNCH(MMSE_STAGE_A_PACK);
     }
 #undef MMSE_CHECK_LAUNCH
     return MMSE_OK;
@@ -951,6 +987,79 @@ int mmse_scale_search_activation_batched(const mmse_act_desc_t* descs_host, int3
         g0 += m;
     }
     return MMSE_OK;
+}
+
+// ---- measurement aid: per-kernel durations of a batched call from HIP events on its stream ----
+int mmse_trace_create(int32_t capacity, mmse_trace_t** trace_out)
+{
+    if (!trace_out) return MMSE_ERR_NULL;
+    *trace_out = nullptr;
+    if (capacity < 2 || capacity > 4096) return MMSE_ERR_SIZE;
+    mmse_trace* T = new (std::nothrow) mmse_trace{};
+    if (!T) return MMSE_ERR_HOST_MEMORY;
+    T->ev = new (std::nothrow) hipEvent_t[capacity]();
+    T->stage = new (std::nothrow) int[capacity]();
+    if (!T->ev || !T->stage) { delete[] T->ev; delete[] T->stage; delete T; return MMSE_ERR_HOST_MEMORY; }
+    for (int i = 0; i < capacity; ++i) {
+        if (hipEventCreate(&T->ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(T->ev[j]);
+            delete[] T->ev; delete[] T->stage; delete T;
+            return MMSE_ERR_LAUNCH;
+        }
+    }
+    T->capacity = capacity;
+    T->used = 0;
+    *trace_out = T;
+    return MMSE_OK;
+}
+
+void mmse_trace_destroy(mmse_trace_t* T)
+{
+    if (!T) return;
+    for (int i = 0; i < T->capacity; ++i) (void)hipEventDestroy(T->ev[i]);
+    delete[] T->ev;
+    delete[] T->stage;
+    delete T;
+}
+
+int mmse_trace_read(mmse_trace_t* T, int32_t capacity, int32_t* count_out, int32_t* stage_out, float* ms_out)
+{
+    if (!T || !count_out || !stage_out || !ms_out) return MMSE_ERR_NULL;
+    const int n = T->used > 0 ? T->used - 1 : 0;          // event 0 precedes the first kernel
+    if (capacity < n) return MMSE_ERR_SIZE;
+    if (T->used > 0 && hipEventSynchronize(T->ev[T->used - 1]) != hipSuccess) return MMSE_ERR_LAUNCH;
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, T->ev[i], T->ev[i + 1]) != hipSuccess) return MMSE_ERR_LAUNCH;
+        stage_out[i] = T->stage[i + 1];
+        ms_out[i] = ms;
+    }
+    *count_out = n;
+    return MMSE_OK;
+}
+
+int mmse_scale_search_batched_traced(const mmse_tensor_desc_t* descs_host, int32_t count, const mmse_params_t* p,
+                                     void* ws_dev, size_t ws_bytes, void* stream, mmse_trace_t* trace)
+{
+    if (!trace) return MMSE_ERR_NULL;
+    trace->used = 0;
+    t_trace = trace;
+    trace_mark(static_cast<hipStream_t>(stream), MMSE_STAGE_START);
+    const int rc = mmse_scale_search_batched(descs_host, count, p, ws_dev, ws_bytes, stream);
+    t_trace = nullptr;
+    return rc;
+}
+
+int mmse_scale_search_activation_batched_traced(const mmse_act_desc_t* descs_host, int32_t count, const mmse_params_t* p,
+                                                void* ws_dev, size_t ws_bytes, void* stream, mmse_trace_t* trace)
+{
+    if (!trace) return MMSE_ERR_NULL;
+    trace->used = 0;
+    t_trace = trace;
+    trace_mark(static_cast<hipStream_t>(stream), MMSE_STAGE_START);
+    const int rc = mmse_scale_search_activation_batched(descs_host, count, p, ws_dev, ws_bytes, stream);
+    t_trace = nullptr;
+    return rc;
 }
 
 int mmse_scale_search_activation(const float* x_dev, int64_t N, const mmse_params_t* p,

@@ -22,13 +22,13 @@ def B():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "mmse.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"^\s*(?:const\s+char\s*\*\s*|int\s+)(\w+)\s*\(", text, flags=re.M)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*\s*|int\s+|void\s+)(\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
 def test_header_symbols_are_exported(B):
     names = declared_functions()
-    assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
+    assert set(names) == set(B.EXPORTS) | set(B.VOID_EXPORTS), (names, B.EXPORTS)
     lib = B.load_library()
     for n in names:
         assert getattr(lib, n) is not None
@@ -44,7 +44,7 @@ def test_struct_layouts_match_header(B):
 
 def test_status_strings(B):
     assert B.status_string(0) == "ok"
-    for rc in range(-6, 0):
+    for rc in range(-7, 0):
         assert B.status_string(rc) not in ("ok", "unknown status")
     assert B.status_string(-99) == "unknown status"
 
