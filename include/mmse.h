@@ -103,6 +103,18 @@ int mmse_scale_search_kernelwise(const float *w_dev, int64_t K, int64_t n, const
                                  float *scale_dev, int32_t *idx_dev, double *sse_dev,
                                  void *ws_dev, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): mmse_scale_search_kernelwise with the workspace replaced by a fixed
+ * array inside the library (4 bytes per kernel, MMSE_NOALLOC_MAX_KERNELS kernels = 1 MiB per GPU, held
+ * until the process ends).  Same arguments otherwise, same results.  K above the limit is MMSE_ERR_SIZE.
+ * The call allocates nothing on the device or the host.  All calls on one GPU share that GPU's array:
+ * two calls that overlap on one GPU (different streams, or different host threads) race and give wrong
+ * results; calls on one stream, or ordered by events, are fine.  Nothing in the array needs clearing
+ * between calls: the sweep writes every entry that the refinement of the same call reads. */
+#define MMSE_NOALLOC_MAX_KERNELS 262144
+int mmse_scale_search_kernelwise_noalloc(const float *w_dev, int64_t K, int64_t n, const mmse_params_t *p,
+                                         float *scale_dev, int32_t *idx_dev, double *sse_dev, void *stream);
+
 /* Per-layer search for calibration activations (Section 3.7, Eq. 15): one problem
  * of N elements; scale_dev, idx_dev, sse_dev hold one element each. */
 int mmse_scale_search_activation(const float *x_dev, int64_t N, const mmse_params_t *p,

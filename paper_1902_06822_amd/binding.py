@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmmse_hip.so")
 
 EXPORTS = (
     "mmse_workspace_bytes_kernelwise", "mmse_workspace_bytes_activation",
-    "mmse_scale_search_kernelwise", "mmse_scale_search_activation",
+    "mmse_scale_search_kernelwise", "mmse_scale_search_activation", "mmse_scale_search_kernelwise_noalloc",
     "quantize_pack_int4", "residual_quantize", "mmse_scale_search_batched",
     "mmse_grid_sse_kernelwise", "mmse_workspace_bytes_dual", "dual_quantize_alternating",
     "mmse_workspace_bytes_dual_batched", "dual_quantize_alternating_batched",
@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
     lib.mmse_workspace_bytes_activation.argtypes = [i64, pp, szp]
     lib.mmse_scale_search_kernelwise.argtypes = [vp, i64, i64, pp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.mmse_scale_search_activation.argtypes = [vp, i64, pp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.mmse_scale_search_kernelwise_noalloc.argtypes = [vp, i64, i64, pp, vp, vp, vp, vp]
     lib.quantize_pack_int4.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp]
     lib.residual_quantize.argtypes = [vp, i64, i64, vp, pp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.mmse_scale_search_batched.argtypes = [C.POINTER(MmseTensorDesc), i32, pp, vp, C.c_size_t, vp]
@@ -218,6 +219,16 @@ def mmse_scale_search_kernelwise(w: torch.Tensor, p: MmseParams, ws: Optional[to
     _check(load_library().mmse_scale_search_kernelwise(
         w.data_ptr(), K, n, C.byref(p), out.scale.data_ptr(), out.idx.data_ptr(), out.sse.data_ptr(),
         ws.data_ptr(), ws.numel(), _stream()), "mmse_scale_search_kernelwise")
+    return out
+
+
+def mmse_scale_search_kernelwise_noalloc(w: torch.Tensor, p: MmseParams, out: SearchResult) -> SearchResult:
+    """The kernel-wise search without a workspace (a fixed array inside the library); `out` must exist."""
+    _dev(w, torch.float32)
+    K, n = w.shape
+    _check(load_library().mmse_scale_search_kernelwise_noalloc(
+        w.data_ptr(), K, n, C.byref(p), out.scale.data_ptr(), out.idx.data_ptr(), out.sse.data_ptr(), _stream()),
+        "mmse_scale_search_kernelwise_noalloc")
     return out
 
 

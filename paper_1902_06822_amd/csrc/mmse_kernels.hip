@@ -37,6 +37,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <limits.h>
+#include <atomic>
 #include <new>
 
 #include "mmse.h"
@@ -364,6 +365,28 @@ int act_group_size(int first, int count, SizeOf N_of)
     return m;
 }
 
+// Scratch of mmse_scale_search_kernelwise_noalloc: one abs-max per kernel.  Every GPU the library runs on holds
+// its own copy of the array, at its own address, until the process ends.
+static __device__ __align__(256) float scratch[MMSE_NOALLOC_MAX_KERNELS];
+
+constexpr int kMaxDevices = 64;
+std::atomic<float*> scratch_ptr[kMaxDevices];       // per device: the array's address there, once known
+
+int scratch_address(float** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MMSE_ERR_LAUNCH;
+    float* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        void* sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return MMSE_ERR_LAUNCH;
+        ptr = static_cast<float*>(sym);
+        scratch_ptr[dev].store(ptr, std::memory_order_release);    // two threads racing here store the same value
+    }
+    *out = ptr;
+    return MMSE_OK;
+}
+
 struct DualPlan {           // workspace of dual_quantize_alternating, byte offsets
     size_t absmax, idx, ts1, ts2, tsse1, tsse, active, accepted, tp1, tp2, bytes;
 };
@@ -499,6 +522,27 @@ int mmse_scale_search_kernelwise(const float* w_dev, int64_t K, int64_t n, const
     d.w_dev = w_dev; d.K = K; d.n = n; d.scale1_dev = nullptr;
     d.scale_dev = scale_dev; d.idx_dev = idx_dev; d.sse_dev = sse_dev; d.packed_dev = nullptr;
     return mmse_scale_search_batched(&d, 1, p, ws_dev, ws_bytes, stream);
+}
+
+// For callers that cannot allocate: the per-kernel abs-max that the sweep hands to the refinement lives in the
+// file-scope device array `scratch` instead of a caller's workspace.  Host code never uses the array's name as
+// an address: scratch_address() asks the runtime for the array's address on the current device, once per device.
+int mmse_scale_search_kernelwise_noalloc(const float* w_dev, int64_t K, int64_t n, const mmse_params_t* p,
+                                         float* scale_dev, int32_t* idx_dev, double* sse_dev, void* stream)
+{
+    // every argument check of the plain entry point first, so that a bad call fails the same way without a GPU
+    int rc = check_params(p);
+    if (rc) return rc;
+    mmse_tensor_desc_t d{};
+    d.w_dev = w_dev; d.K = K; d.n = n; d.scale_dev = scale_dev; d.idx_dev = idx_dev; d.sse_dev = sse_dev;
+    rc = check_tensor(d, true);
+    if (rc) return rc;
+    if (K > MMSE_NOALLOC_MAX_KERNELS) return MMSE_ERR_SIZE;
+    float* ptr = nullptr;
+    rc = scratch_address(&ptr);
+    if (rc) return rc;
+    return mmse_scale_search_kernelwise(w_dev, K, n, p, scale_dev, idx_dev, sse_dev, ptr,
+                                        sizeof(float) * (size_t)MMSE_NOALLOC_MAX_KERNELS, stream);
 }
 
 int residual_quantize(const float* w_dev, int64_t K, int64_t n, const float* scale1_dev,
