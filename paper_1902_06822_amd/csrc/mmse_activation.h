@@ -26,6 +26,7 @@ struct ActState {
     float absmax;
     float lo_a, hi_a, pc, pd, best_a;
     float probes[kMaxProbes];
+    float probe_inv[kMaxProbes];     // 1 / probes[i], for the kernels that evaluate them
     double ec, ed, best;
     unsigned min_key, max_key;   // offset form: order-preserving keys of min and max
     float out_scale; int out_idx; double out_sse;    // result slots for calls that only want the grid errors
@@ -127,7 +128,7 @@ __global__ void k_act_init(ActState* Sall, int count)
         S->absmax_bits = 0; S->status = 0; S->j = 0; S->it = 0; S->done = 1;
         S->have_c = S->have_d = 0; S->nprobe = 0; S->absmax = 0.0f;
         S->lo_a = S->hi_a = S->pc = S->pd = S->best_a = 1.0f;
-        for (int i = 0; i < kMaxProbes; ++i) S->probes[i] = 1.0f;
+        for (int i = 0; i < kMaxProbes; ++i) { S->probes[i] = 1.0f; S->probe_inv[i] = 1.0f; }
         S->ec = S->ed = S->best = 0.0;
         S->min_key = 0xffffffffu; S->max_key = 0u; S->delta = 0.0f;
     }
@@ -173,7 +174,11 @@ __device__ void act_plan(ActState* S, int iters)
         act_enumerate<2>(S->lo_a, S->hi_a, S->pc, S->pd, depth, list, n);
     }
     S->nprobe = n;
-    for (int i = 0; i < kMaxProbes; ++i) S->probes[i] = i < n ? list[i] : 1.0f;
+    for (int i = 0; i < kMaxProbes; ++i) {
+        const float a = i < n ? list[i] : 1.0f;
+        S->probes[i] = a;
+        S->probe_inv[i] = 1.0f / a;
+    }
 }
 
 __device__ bool act_lookup(const float* probes, const double* vals, int n, float a, double& out)
@@ -219,15 +224,19 @@ __device__ void act_advance(ActState* S, const double* vals, int iters)
 
 // MODE 0: max |x| (integer max of the bit patterns); 1: max |residual of the first tensor|;
 // 2: min and max of x as order-preserving keys (offset form).
+// Large workgroups: the pass needs some 50 MB of loads in flight to fill HBM, and every workgroup ends with one
+// atomic on its tensor's state word; atomics on one address retire one after the other (about 9 ns each on
+// MI355X), and all workgroups finish together, so there should be few of them.
+constexpr int kAbsmaxThreads = 1024;
 template <int U, int MODE>
-__global__ void __launch_bounds__(256) k_act_absmax(const ActBatch B, const ActPre pre)
+__global__ void __launch_bounds__(kAbsmaxThreads) k_act_absmax(const ActBatch B, const ActPre pre)
 {
     const float* __restrict__ x = B.x[blockIdx.y];
     const long long N = B.N[blockIdx.y];
     ActState* S = B.S + blockIdx.y;
     if ((long long)blockIdx.x * blockDim.x * 4 * U >= N) return;       // nothing of this tensor for this workgroup
-    __shared__ unsigned s_amax[4];
-    __shared__ unsigned s_amin[4];
+    __shared__ unsigned s_amax[kAbsmaxThreads / 64];
+    __shared__ unsigned s_amin[kAbsmaxThreads / 64];
     unsigned amax = 0, amin = 0xffffffffu;
     ActPreV V{};
     if constexpr (MODE == 1) V = act_pre_load(pre);
@@ -251,7 +260,7 @@ __global__ void __launch_bounds__(256) k_act_absmax(const ActBatch B, const ActP
             float4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                v[u] = *reinterpret_cast<const float4*>(x + base + ((long long)u * blockDim.x + threadIdx.x) * 4);
+                v[u] = load_stream_f4(x + base + ((long long)u * blockDim.x + threadIdx.x) * 4);
 #pragma unroll
             for (int u = 0; u < U; ++u) { take(v[u].x); take(v[u].y); take(v[u].z); take(v[u].w); }
         } else {
@@ -368,12 +377,19 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
 // When a stage leaves a single row and fin != nullptr the caller continues with it.
 // Output row blockIdx.x of level `level` belongs to one tensor; its inputs are that tensor's rows of level - 1.
 // (Rows on the x axis of the grid: a batch of large tensors has more than 65535 of them.)
+// probe_cols != 0: the columns are the scales of a refinement pass; only those the tensor's state asks for were
+// written by k_act_probe (none for a tensor that is finished, all-zero or rejected), the rest is skipped here
+// as it is in k_act_finish.
 __global__ void __launch_bounds__(256) k_act_reduce64(const ActBatch B, int level, const double* __restrict__ in, int G,
-                                                      double* __restrict__ out)
+                                                      double* __restrict__ out, int probe_cols)
 {
     const int j = blockIdx.y * blockDim.x + threadIdx.x;
     int first, below;
     const int t = act_find_level(B, level, blockIdx.x, first, below);
+    if (probe_cols) {
+        const ActState* S = B.S + t;
+        if (S->status != 0 || S->done || j >= S->nprobe) return;
+    }
     const int g = blockIdx.x - first;                                   // group of 64 input rows inside the tensor
     const int rows = act_rows(B.start[t + 1] - B.start[t], level - 1);
     if (j >= G) return;
@@ -482,126 +498,70 @@ __global__ void __launch_bounds__(256) k_act_argmin(const ActBatch B, int level,
     }
 }
 
-// One refinement pass: f at up to kMaxProbes scales for every block of 64 chunks.
-// lane = chunk, wave = block.  A block is handled as two halves by element: elements 0..31 of every
-// chunk, then elements 32..63 (the fp32 chunk sums simply continue, so the order of additions is
-// unchanged).  All 16 coalesced 16-byte loads of the wave are issued up front; the first half goes
-// through a wave-private LDS tile to become half a chunk per lane and is evaluated for all scales
-// while the loads of the second half are still in flight.  Tree over the 64 chunk sums by DPP.
-constexpr int kHalfStride = 36;        // floats between chunks in the half-chunk tile (32 + 4: keeps 16-byte alignment)
-
-__device__ __forceinline__ void probe_fetch(const float* __restrict__ x, long long N, long long base, int h, int lane,
-                                            bool aligned, float4 (&stg)[8])
-{
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int f = r * 64 + lane;                         // float4 number inside the half: chunk f / 8, position f % 8
-        const long long e = base + (long long)(f >> 3) * kChunk + h * 32 + (f & 7) * 4;
-        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (aligned && e + 4 <= N) {
-            v = *reinterpret_cast<const float4*>(x + e);
-        } else if (e < N) {
-            v.x = x[e];
-            if (e + 1 < N) v.y = x[e + 1];
-            if (e + 2 < N) v.z = x[e + 2];
-            if (e + 3 < N) v.w = x[e + 3];
-        }
-        stg[r] = v;
-    }
-}
-
-__device__ __forceinline__ void probe_stage(float* tile, const ActPreV& V, long long N, long long base, int h, int lane,
-                                            const float4 (&stg)[8], float (&xr)[32])
-{
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int f = r * 64 + lane;
-        float4 v = stg[r];
-        if (V.mode != 0) {                                   // padding stays exactly zero
-            const long long e = base + (long long)(f >> 3) * kChunk + h * 32 + (f & 7) * 4;
-            if (e < N) v.x = act_pre(V, v.x);
-            if (e + 1 < N) v.y = act_pre(V, v.y);
-            if (e + 2 < N) v.z = act_pre(V, v.z);
-            if (e + 3 < N) v.w = act_pre(V, v.w);
-        }
-        *reinterpret_cast<float4*>(tile + (f >> 3) * kHalfStride + (f & 7) * 4) = v;
-    }
-    wave_lds_sync();
-    const float4* t4 = reinterpret_cast<const float4*>(tile + lane * kHalfStride);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float4 v = t4[i];
-        xr[4 * i + 0] = v.x; xr[4 * i + 1] = v.y; xr[4 * i + 2] = v.z; xr[4 * i + 3] = v.w;
-    }
-    wave_lds_sync();
-}
-
-__device__ __forceinline__ void probe_eval(const float (&xr)[32], int np, const float (&pr)[kMaxProbes],
-                                           const float (&pinv)[kMaxProbes], float lo, float hi, float (&s)[kMaxProbes])
-{
-#pragma unroll
-    for (int pi = 0; pi < kMaxProbes; ++pi) {
-        if (pi < np) {
-            float sp[1] = {s[pi]};
-            const float al[1] = {pr[pi]}, iv[1] = {pinv[pi]};
-#pragma unroll
-            for (int i = 0; i < 32; i += 8) {
-                const float xs[8] = {xr[i], xr[i + 1], xr[i + 2], xr[i + 3], xr[i + 4], xr[i + 5], xr[i + 6], xr[i + 7]};
-                eval_stage<8, 1>(xs, al, iv, lo, hi, sp);
-            }
-            s[pi] = sp[0];
-        }
-    }
-}
+// One refinement pass: f at up to kMaxProbes scales for every block of 64 chunks, one workgroup of four waves
+// per block.  Both roofs bind here about equally (eight scales are 40 VALU instructions per 4 bytes read, the
+// machine's own ratio), so the kernel has the shape of the grid sweep, which keeps the VALU busy at eight waves
+// per SIMD, and streams its input like the abs-max pass: the block is staged into LDS with coalesced
+// non-temporal 16-byte loads (chunks padded apart by four floats), lane = (scale, pair of chunks): the eight
+// lanes of a scale-group read the same element (a broadcast), the eight groups of a wave read eight different
+// chunks (different banks), and every lane runs the same sweep core over its two chunks.  The chunk sums of a
+// scale are then 32 level-1 nodes of the block's pairwise tree; the first wave adds them up.
+constexpr int kProbeChunkStride = kChunk + 4;
 
 __global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, float hi, double* probe0, const ActPre pre)
 {
-    __shared__ float4 tile4[4][64 * kHalfStride / 4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int blk = blockIdx.x * 4 + wave;                    // block in the concatenated numbering
-    const int total = B.start[B.count];
-    if (blk >= total) return;                                 // the waves of a workgroup are independent: no barriers below
-    const int t = act_find(B, blk);
+    __shared__ float4 tile4[kBlockChunks * kProbeChunkStride / 4];
+    __shared__ double node[kBlockChunks / 2][kMaxProbes];
+    float* tile = reinterpret_cast<float*>(tile4);
+    const int tid = threadIdx.x;
+    const int t = act_find(B, blockIdx.x);
     const ActState* S = B.S + t;
-    if (S->status != 0 || S->done) return;
+    if (S->status != 0 || S->done) return;                    // uniform over the workgroup
     const float* __restrict__ x = B.x[t];
     const long long N = B.N[t];
     const ActPreV V = act_pre_load(pre);
     const int np = S->nprobe;
-    const long long base = (long long)(blk - B.start[t]) * kBlockElems;   // first element of this wave's block
-    float* tile = reinterpret_cast<float*>(tile4[wave]);
-    const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
+    const long long base = (long long)(blockIdx.x - B.start[t]) * kBlockElems;
+    const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
 
-    float4 stg0[8], stg1[8];
-    probe_fetch(x, N, base, 0, lane, aligned, stg0);
-    probe_fetch(x, N, base, 1, lane, aligned, stg1);
-    // the scales of this pass (unused slots hold 1.0)
-    float pr[kMaxProbes], pinv[kMaxProbes], s[kMaxProbes];
+    // stage the block: element i of the block goes to tile[i + 4 * (i / 64)]; beyond the tensor: exact zeros
+    if (len == kBlockElems && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
+        float4 v[kBlockElems / 4 / 256];
 #pragma unroll
-    for (int i = 0; i < kMaxProbes; ++i) pr[i] = S->probes[i];
+        for (int r = 0; r < kBlockElems / 4 / 256; ++r) v[r] = load_stream_f4(x + base + (size_t)(r * 256 + tid) * 4);
 #pragma unroll
-    for (int i = 0; i < kMaxProbes; ++i) { pinv[i] = 1.0f / pr[i]; s[i] = 0.0f; }
-
-    float xr[32];
-    probe_stage(tile, V, N, base, 0, lane, stg0, xr);
-    probe_eval(xr, np, pr, pinv, lo, hi, s);
-    probe_stage(tile, V, N, base, 1, lane, stg1, xr);
-    probe_eval(xr, np, pr, pinv, lo, hi, s);
-
-    // pairwise tree over the 64 chunk sums: lane i (a multiple of 2w) adds lane i + w; four levels inside
-    // rows of 16 lanes by DPP shifts, the last two on the four row heads as scalar operands
-#pragma unroll
-    for (int pi = 0; pi < kMaxProbes; ++pi) {
-        if (pi < np) {
-            double v = (double)s[pi];
-            v = v + dpp_row_shl<1>(v);
-            v = v + dpp_row_shl<2>(v);
-            v = v + dpp_row_shl<4>(v);
-            v = v + dpp_row_shl<8>(v);
-            const double r0 = readlane_f64(v, 0), r1 = readlane_f64(v, 16), r2 = readlane_f64(v, 32), r3 = readlane_f64(v, 48);
-            const double tot = (r0 + r1) + (r2 + r3);
-            if (lane == 0) probe0[(size_t)blk * kMaxProbes + pi] = tot;
+        for (int r = 0; r < kBlockElems / 4 / 256; ++r) {
+            const int i = (r * 256 + tid) * 4;
+            float4 w = v[r];
+            if (V.mode != 0) { w.x = act_pre(V, w.x); w.y = act_pre(V, w.y); w.z = act_pre(V, w.z); w.w = act_pre(V, w.w); }
+            *reinterpret_cast<float4*>(tile + i + 4 * (i / kChunk)) = w;
         }
+    } else {
+        for (int i = tid; i < kBlockElems; i += 256) tile[i + 4 * (i / kChunk)] = i < len ? act_pre(V, x[base + i]) : 0.0f;
+    }
+    __syncthreads();
+
+    const int p = tid & 7, g = tid >> 3;                      // scale, pair of chunks (2g, 2g + 1)
+    const float alpha[1] = {S->probes[p]};
+    const float inv[1] = {S->probe_inv[p]};
+    double st[1][2] = {{0.0, 0.0}};
+    unsigned ci = 0;
+    sweep_slice<1, 2, kProbeChunkStride>(tile + 2 * g * kProbeChunkStride, 2 * kChunk, ci, alpha, inv, lo, hi, st);
+    double E[1];
+    tree_fold<1, 2>(st, ci, E);
+    node[g][p] = E[0];
+    __syncthreads();
+    if (tid < 64) {
+        // the upper five tree levels of a scale: lane (p, k) adds the eight nodes 8k .. 8k + 7 pairwise, the four
+        // results are combined as (k0 + k1) + (k2 + k3) through shuffles (the whole first wave takes part)
+        const int k = (tid >> 3) & 3;
+        double v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = node[8 * k + i][p];
+        double r = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+        r = r + __shfl_down(r, 8, 64);
+        r = r + __shfl_down(r, 16, 64);
+        if (tid < np) probe0[(size_t)blockIdx.x * kMaxProbes + tid] = r;
     }
 }
 
@@ -660,8 +620,8 @@ __global__ void __launch_bounds__(kPackThreads) k_act_pack(const ActBatch B, con
         const int cnt = (N - e0) < kPackPerThread ? (int)(N - e0) : kPackPerThread;
         float v[kPackPerThread];
         if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
-            const float4 p0 = reinterpret_cast<const float4*>(x + e0)[0];
-            const float4 p1 = reinterpret_cast<const float4*>(x + e0)[1];
+            const float4 p0 = load_stream_f4(x + e0);
+            const float4 p1 = load_stream_f4(x + e0 + 4);
             v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w;
             v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
         } else {
@@ -678,7 +638,7 @@ __global__ void __launch_bounds__(kPackThreads) k_act_pack(const ActBatch B, con
         }
         uint8_t* dst = packed + (e0 >> 1);
         if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(packed) & 3u) == 0) {
-            *reinterpret_cast<unsigned*>(dst) = word;
+            store_stream_u32(reinterpret_cast<unsigned*>(dst), word);
         } else {
             const int nbytes = (cnt + 1) >> 1;
             for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));

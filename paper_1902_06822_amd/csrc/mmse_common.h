@@ -135,6 +135,17 @@ __device__ __forceinline__ double readlane_f64(double v, int l)
     return __hiloint2double(hi, lo);
 }
 
+// 16-byte load / 4-byte store for data that is streamed through once (a whole activation tensor per pass):
+// the non-temporal hint keeps such lines from displacing what the caches hold for others, which on MI355X is
+// worth about a tenth of the read bandwidth of a pass over a tensor much larger than the caches.
+typedef float mmse_vf4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream_f4(const float* p)
+{
+    const mmse_vf4 v = __builtin_nontemporal_load(reinterpret_cast<const mmse_vf4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream_u32(unsigned* p, unsigned v) { __builtin_nontemporal_store(v, p); }
+
 __device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v)
@@ -241,7 +252,9 @@ __device__ __forceinline__ void eval_stage(const float (&x)[NE], const float (&a
 // Sweep the `nelem` elements (a multiple of 8; zero padded) that sit in LDS at `slice` for the C
 // candidates of this lane: whole 64-element chunks, then a last shorter chunk that only walks the
 // 8-element groups it has (padding zeros would be exact no-ops, so skipping them changes nothing).
-template <int C, int L>
+// CS: floats between the starts of consecutive chunks in LDS (kChunk, or more when the chunks are padded apart
+// so that lanes reading different chunks at the same time hit different banks).
+template <int C, int L, int CS = kChunk>
 __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsigned& ci,
                                             const float (&alpha)[C], const float (&inv)[C],
                                             float lo, float hi, double (&st)[C][L])
@@ -259,7 +272,7 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsig
             // elements come from LDS one group ahead of their use (same address in every lane: broadcast)
             float4 nxt[NE / 4];
 #pragma unroll
-            for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + q];
+            for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (CS / 4) + q];
 #pragma unroll
             for (int e = 0; e < kChunk / NE; ++e) {
                 float x[NE];
@@ -269,7 +282,7 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsig
                 }
                 if (e + 1 < kChunk / NE) {
 #pragma unroll
-                    for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (kChunk / 4) + (e + 1) * (NE / 4) + q];
+                    for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (CS / 4) + (e + 1) * (NE / 4) + q];
                 }
                 __builtin_amdgcn_sched_barrier(0);       // the prefetch is issued before this group's arithmetic
                 eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
@@ -279,7 +292,7 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsig
                 float x[NE];
 #pragma unroll
                 for (int q = 0; q < NE / 4; ++q) {
-                    const float4 v = s4[c * (kChunk / 4) + e * (NE / 4) + q];
+                    const float4 v = s4[c * (CS / 4) + e * (NE / 4) + q];
                     x[4 * q + 0] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
                 }
                 eval_stage<NE, C>(x, alpha, inv, lo, hi, s);

@@ -312,7 +312,8 @@ struct ActPlan {
     int plevels;            // reduce64 stages of the probe sums until every tensor has <= 4096 rows
     int total_rows[8];      // rows of all tensors together at each level
     size_t off_part[8];     // byte offsets of the grid-sum levels ([rows][G] doubles)
-    size_t off_probe[8];    // byte offsets of the probe levels ([rows][kMaxProbes] doubles)
+    size_t off_probe[8];    // byte offsets of the probe levels ([rows][kMaxProbes] doubles); only the columns below a
+                            // tensor's nprobe are written in a pass, and only those are read
     size_t bytes;
 };
 
@@ -885,19 +886,20 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     hipLaunchKernelGGL(k_act_init, dim3(1), dim3(64), 0, s, S, count);
     MMSE_CHECK_LAUNCH(MMSE_STAGE_A_INIT);
     {
-        // per tensor at most one workgroup per CU, eight 16-byte loads in flight per thread: measured fastest
-        // on MI355X (6.9 TB/s on a 205 MB tensor; more, smaller workgroups lose up to 2x)
-        // (a batch shares the CUs: about two workgroups per CU over all tensors, each tensor in proportion to its size)
+        // 24 waves per CU over all tensors of the batch (each tensor in proportion to its size), eight non-temporal
+        // 16-byte loads in flight per thread: measured fastest on MI355X for sets of tensors much larger than
+        // the caches (6.9-7.0 TB/s on 0.58 and 1.4 GB; a third of the waves: 3.8, plain loads: 6.2)
         constexpr int U = 8;
-        long long want = (maxN + 1024 * U - 1) / (1024 * U);
-        long long cap = (2 * 256 * maxN + sumN - 1) / sumN;
-        if (cap > 256) cap = 256;
+        const long long per_wg = 4LL * kAbsmaxThreads * U;             // elements per workgroup and trip
+        long long want = (maxN + per_wg - 1) / per_wg;
+        long long cap = (384 * maxN + sumN - 1) / sumN;
+        if (cap > 384) cap = 384;
         if (want > cap) want = cap;
         const int grid = (int)(want < 1 ? 1 : want);
         const dim3 g(grid, count);
-        if (pre_mode == 0) hipLaunchKernelGGL((k_act_absmax<U, 0>), g, dim3(256), 0, s, B, pre);
-        else if (pre_mode == 1) hipLaunchKernelGGL((k_act_absmax<U, 1>), g, dim3(256), 0, s, B, pre);
-        else hipLaunchKernelGGL((k_act_absmax<U, 2>), g, dim3(256), 0, s, B, pre);
+        if (pre_mode == 0) hipLaunchKernelGGL((k_act_absmax<U, 0>), g, dim3(kAbsmaxThreads), 0, s, B, pre);
+        else if (pre_mode == 1) hipLaunchKernelGGL((k_act_absmax<U, 1>), g, dim3(kAbsmaxThreads), 0, s, B, pre);
+        else hipLaunchKernelGGL((k_act_absmax<U, 2>), g, dim3(kAbsmaxThreads), 0, s, B, pre);
         MMSE_CHECK_LAUNCH(MMSE_STAGE_A_ABSMAX);
         if (pre_mode == 2) {
             hipLaunchKernelGGL(k_act_offset_setup, dim3(1), dim3(64), 0, s, S, delta_dev);
@@ -919,7 +921,7 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     for (int l = 0; l < P.levels; ++l) {
         hipLaunchKernelGGL(k_act_reduce64, dim3(P.total_rows[l + 1], (G + 255) / 256), dim3(256), 0, s, B, l + 1,
                            reinterpret_cast<const double*>(ws + P.off_part[l]), G,
-                           reinterpret_cast<double*>(ws + P.off_part[l + 1]));
+                           reinterpret_cast<double*>(ws + P.off_part[l + 1]), 0);
         MMSE_CHECK_LAUNCH(MMSE_STAGE_A_REDUCE);
     }
     {
@@ -931,13 +933,13 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         MMSE_CHECK_LAUNCH(MMSE_STAGE_A_ARGMIN);
     }
     for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
-        hipLaunchKernelGGL(k_act_probe, dim3((total + 3) / 4), dim3(256), 0, s, B, lo, hi,
+        hipLaunchKernelGGL(k_act_probe, dim3(total), dim3(256), 0, s, B, lo, hi,
                            reinterpret_cast<double*>(ws + P.off_probe[0]), pre);
         MMSE_CHECK_LAUNCH(MMSE_STAGE_A_PROBE);
         for (int l = 0; l < P.plevels; ++l) {
             hipLaunchKernelGGL(k_act_reduce64, dim3(P.total_rows[l + 1], 1), dim3(64), 0, s, B, l + 1,
                                reinterpret_cast<const double*>(ws + P.off_probe[l]), kMaxProbes,
-                               reinterpret_cast<double*>(ws + P.off_probe[l + 1]));
+                               reinterpret_cast<double*>(ws + P.off_probe[l + 1]), 1);
             MMSE_CHECK_LAUNCH(MMSE_STAGE_A_PROBE_REDUCE);
         }
         hipLaunchKernelGGL(k_act_finish, dim3(count), dim3(512), 0, s, B, P.plevels,
