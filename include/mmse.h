@@ -224,7 +224,8 @@ int mmse_scale_alternating_kernelwise(const float *w_dev, int64_t K, int64_t n, 
  * memory (the descriptors are consumed before the call returns).  Semantics per
  * tensor are those of mmse_scale_search_kernelwise / residual_quantize /
  * quantize_pack_int4.  Workspace: mmse_workspace_bytes_kernelwise(sum K, ...).  count in 1..4096, else
- * MMSE_ERR_SIZE. */
+ * MMSE_ERR_SIZE.  Up to 59 tensors are one launch per stage (sweep, refinement by kernel-size class, codes);
+ * longer lists run in groups of 59, each with its own launches. */
 int mmse_scale_search_batched(const mmse_tensor_desc_t *descs_host, int32_t count,
                               const mmse_params_t *p, void *ws_dev, size_t ws_bytes, void *stream);
 

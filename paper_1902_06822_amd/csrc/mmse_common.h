@@ -9,7 +9,8 @@ namespace {
 
 
 constexpr int kChunk = 64;             // elements per sequential fp32 chunk
-constexpr int kMaxBatch = 40;          // tensors per launch: the descriptor table lives in kernarg (4 KB at most)
+constexpr int kMaxBatch = 59;          // tensors per launch: the descriptor table lives in kernarg (4 KB at most)
+constexpr int kMaxBatchExt = 36;       // ... when some tensor of the launch uses the fields of TensorExt
 constexpr int kTile = 8192;            // floats of one kernel staged in LDS at a time
 constexpr int kTileStream = 4096;      // ... for longer kernels, which stream through LDS tile by tile
 constexpr int kLevelsKW = 11;          // binary-counter levels for <= 1024 chunks (65536 elements)
@@ -39,15 +40,43 @@ struct TensorArgs {
     int n;
 };
 
+// The tensors of one launch travel in the kernel argument buffer (no host-to-device copy, no allocation): 64
+// bytes per tensor, so that a network of up to kMaxBatch layers is one launch per stage; the fields only the
+// two-tensor methods and the grid-error output use are a second, shorter array that overlays the end of the first.
+struct TensorCore {
+    const float* w;
+    const float* scale1;
+    float* scale;
+    int32_t* idx;
+    double* sse;
+    float* absmax;
+    uint8_t* packed;
+    int K;
+    int n;
+};
+struct TensorExt {
+    double* grid_sse;
+    const uint8_t* sub_packed;
+    const float* sub_scale;
+    const uint8_t* active;
+};
 struct Batch {
-    TensorArgs t[kMaxBatch];
-    int start[kMaxBatch + 1];   // prefix sum of workgroups per tensor
+    union {
+        TensorCore t[kMaxBatch];
+        struct {
+            TensorCore t_with_ext[kMaxBatchExt];
+            TensorExt e[kMaxBatchExt];          // has_ext != 0: count <= kMaxBatchExt
+        };
+    };
+    int start[kMaxBatch + 1];   // prefix sum of the workgroups each tensor gets in this launch
     int count;
     int G;
     int qmax;
     int iters;
     float lo, hi;               // (float)qmin, (float)qmax
+    int has_ext;
 };
+static_assert(sizeof(TensorCore) == 64 && sizeof(TensorExt) == 32, "descriptor sizes");
 static_assert(sizeof(Batch) <= 4096, "the descriptor table must fit the kernel argument buffer");
 
 // ---------------------------------------------------------------------------------
@@ -305,11 +334,27 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsig
     }
 }
 
-__device__ __forceinline__ int find_tensor(const Batch& B, int bid)
+// Tensor that owns workgroup bid, and that workgroup's number inside the tensor.
+__device__ __forceinline__ int find_tensor(const Batch& B, int bid, int& local)
 {
     int t = 0;
     while (t + 1 < B.count && bid >= B.start[t + 1]) ++t;
+    local = bid - B.start[t];
     return t;
+}
+
+__device__ __forceinline__ TensorArgs tensor_of(const Batch& B, int t)
+{
+    const TensorCore& c = B.t[t];
+    TensorArgs A;
+    A.w = c.w; A.scale1 = c.scale1; A.scale = c.scale; A.idx = c.idx; A.sse = c.sse; A.absmax = c.absmax;
+    A.packed = c.packed; A.K = c.K; A.n = c.n;
+    A.grid_sse = nullptr; A.sub_packed = nullptr; A.sub_scale = nullptr; A.active = nullptr;
+    if (B.has_ext) {
+        const TensorExt& e = B.e[t];
+        A.grid_sse = e.grid_sse; A.sub_packed = e.sub_packed; A.sub_scale = e.sub_scale; A.active = e.active;
+    }
+    return A;
 }
 
 }  // namespace

@@ -130,34 +130,87 @@ void fill_common(Batch& B, const mmse_params_t* p)
     B.hi = (float)p->qmax;
 }
 
-template <int C>
-int launch_sweep(const Batch& B, int nwg, int G, int max_npad, hipStream_t s)
+// ---- the weight path: which workgroups every tensor gets in every launch ----------------------------------
+// Launches of one call: the sweep (ordinary kernels and, in the same launch, tiny ones), the refinement by
+// class of lanes per kernel, the code pass for what the refinement did not code.
+enum { ST_SWEEP = 0, ST_REF0, ST_REF1, ST_REF2, ST_REF3, ST_PACK, ST_COUNT };
+
+struct WeightShape {        // launch shape of the call: the same for host and device
+    int waves;              // waves of a sweep workgroup
+    int CS;                 // candidates per lane of the one-wave-per-kernel path (0: not used)
+    int do_search;
+    int iters;
+};
+
+__host__ __device__ inline int refine_class(int n)
 {
-    const int waves = (G + 64 * C - 1) / (64 * C);
-    // LDS: the longest kernel that is staged whole (<= kTile floats), or the streaming tile of the longer ones
-    int lds_floats = 0;
-    for (int i = 0; i < B.count; ++i) {
-        const int npad = (B.t[i].n + kChunk - 1) & ~(kChunk - 1);
-        const int need = npad <= kTile ? npad : kTileStream;
-        lds_floats = need > lds_floats ? need : lds_floats;
+    const int m = (n + kChunk - 1) / kChunk;
+    return n <= 16 ? 0 : (m <= 256 ? 1 : (m <= 512 ? 2 : 3));
+}
+__host__ __device__ inline int refine_threads(int cls) { return cls == 3 ? 1024 : (cls == 2 ? 512 : 256); }
+
+// Workgroups tensor (K, n) gets in launch `stage` (0: none).
+__host__ __device__ inline long long stage_wgs(int stage, long long K, int n, bool has_packed, const WeightShape& sh)
+{
+    if (stage == ST_SWEEP) {
+        if (!sh.do_search) return 0;
+        return (sh.CS > 0 && n <= kChunk) ? (K + sh.waves - 1) / sh.waves : K;
     }
-    const size_t lds = (size_t)lds_floats * sizeof(float);
-    const dim3 grid(nwg), block(64 * waves);
-    // binary-counter levels for the longest kernel of the launch: each level is two registers per candidate
-    const int chunks = max_npad / kChunk;
-    if (chunks <= 128) hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall>), grid, block, lds, s, B);
-    else if (chunks < 512) hipLaunchKernelGGL((k_sweep_kernelwise<C, 9>), grid, block, lds, s, B);
-    else if (chunks < 1024) hipLaunchKernelGGL((k_sweep_kernelwise<C, 10>), grid, block, lds, s, B);
-    else hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW>), grid, block, lds, s, B);
-    trace_mark(s, MMSE_STAGE_W_SWEEP);
-    return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+    if (stage >= ST_REF0 && stage <= ST_REF3) {
+        const int cls = stage - ST_REF0;
+        if (!sh.do_search || sh.iters <= 0 || refine_class(n) != cls) return 0;
+        const int lanes = cls == 0 ? 1 : (n + kChunk - 1) / kChunk;
+        const int cpw = refine_threads(cls) / lanes;
+        return (K + cpw - 1) / cpw;
+    }
+    // codes: everything without a search; with one, what the refinement kernel did not code itself (odd n, or no refinement)
+    if (!has_packed) return 0;
+    if (sh.do_search && sh.iters > 0 && (n & 1) == 0) return 0;
+    const long long per_wg = (long long)kPackThreads * kPackPerThread;
+    return (K * n + per_wg - 1) / per_wg;
 }
 
-int launch_sweep_any(int C, const Batch& B, int nwg, int G, int max_npad, hipStream_t s)
+// Candidates per lane of the one-wave-per-kernel path for a sweep with C candidates per lane in the ordinary
+// path, or 0 when that combination is not compiled (explicit tuning values, grids above 512 points).
+int small_cs(int C, int G)
 {
-    if (C == 1) return launch_sweep<1>(B, nwg, G, max_npad, s);
-    if (C == 2) return launch_sweep<2>(B, nwg, G, max_npad, s);
-    return launch_sweep<4>(B, nwg, G, max_npad, s);
+    if (C == 1 && G <= 64) return 1;
+    if (C == 1 && G <= 128) return 2;
+    if (C == 1 && G <= 256) return 4;
+    if (C == 1 && G <= 384) return 8;
+    if (C == 2 && G > 384 && G <= 512) return 8;
+    return 0;
+}
+
+template <int C, int CS>
+void launch_sweep_lv(const Batch& B, dim3 grid, dim3 block, size_t lds, int chunks, hipStream_t s)
+{
+    // binary-counter levels for the longest kernel of the launch: each level is two registers per candidate
+    if constexpr (CS > 0) {
+        hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall, CS>), grid, block, lds, s, B);
+    } else {
+        if (chunks <= 128) hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall, 0>), grid, block, lds, s, B);
+        else if (chunks < 512) hipLaunchKernelGGL((k_sweep_kernelwise<C, 9, 0>), grid, block, lds, s, B);
+        else if (chunks < 1024) hipLaunchKernelGGL((k_sweep_kernelwise<C, 10, 0>), grid, block, lds, s, B);
+        else hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW, 0>), grid, block, lds, s, B);
+    }
+}
+
+// CS > 0 only together with kernels of at most 128 chunks (the caller checks)
+int launch_sweep(int C, int CS, const Batch& B, int nwg, int waves, size_t lds, int chunks, hipStream_t s)
+{
+    const dim3 grid(nwg), block(64 * waves);
+    if (C == 1 && CS == 0) launch_sweep_lv<1, 0>(B, grid, block, lds, chunks, s);
+    else if (C == 1 && CS == 1) launch_sweep_lv<1, 1>(B, grid, block, lds, chunks, s);
+    else if (C == 1 && CS == 2) launch_sweep_lv<1, 2>(B, grid, block, lds, chunks, s);
+    else if (C == 1 && CS == 4) launch_sweep_lv<1, 4>(B, grid, block, lds, chunks, s);
+    else if (C == 1 && CS == 8) launch_sweep_lv<1, 8>(B, grid, block, lds, chunks, s);
+    else if (C == 2 && CS == 0) launch_sweep_lv<2, 0>(B, grid, block, lds, chunks, s);
+    else if (C == 2 && CS == 8) launch_sweep_lv<2, 8>(B, grid, block, lds, chunks, s);
+    else if (C == 4 && CS == 0) launch_sweep_lv<4, 0>(B, grid, block, lds, chunks, s);
+    else return MMSE_ERR_PARAMS;
+    trace_mark(s, MMSE_STAGE_W_SWEEP);
+    return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
 }
 
 struct Item {              // one tensor of a batched call, host side
@@ -165,7 +218,38 @@ struct Item {              // one tensor of a batched call, host side
     int order;
 };
 
-// The three stages for a list of tensors (already validated): sweep, refine, pack.
+// One launch of `stage` for the tensors in B (kernel-argument table or device-resident table), nwg workgroups.
+// lds_floats / chunks: LDS of the sweep and the longest kernel of the launch in chunks; xf: some member is
+// searched through a transform.
+int launch_stage(int stage, const Batch& B, int nwg, int C, const WeightShape& sh, int lds_floats, int chunks, bool xf,
+                 hipStream_t s)
+{
+    if (nwg <= 0) return MMSE_OK;
+    if (stage == ST_SWEEP)
+        return launch_sweep(C, sh.CS, B, nwg, sh.waves, (size_t)lds_floats * sizeof(float), chunks, s);
+    if (stage == ST_PACK) {
+        hipLaunchKernelGGL(k_pack_int4, dim3(nwg), dim3(kPackThreads), 0, s, B);
+        trace_mark(s, MMSE_STAGE_W_PACK);
+        return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+    }
+    const int cls = stage - ST_REF0;
+    const int threads = refine_threads(cls);
+    // LDS: combine buffer (2 doubles per thread) + one transpose tile per wave
+    const int tile_chunks = cls == 0 ? 0 : 32 * 256 / threads;
+    const size_t lds = (size_t)threads * 2 * sizeof(double) + (size_t)(threads / 64) * tile_chunks * kTileStride * sizeof(float);
+    if (cls == 0) {
+        if (xf) hipLaunchKernelGGL((k_refine_kernelwise<16, true>), dim3(nwg), dim3(threads), lds, s, B, tile_chunks);
+        else hipLaunchKernelGGL((k_refine_kernelwise<16, false>), dim3(nwg), dim3(threads), lds, s, B, tile_chunks);
+    } else {
+        if (xf) hipLaunchKernelGGL((k_refine_kernelwise<kChunk, true>), dim3(nwg), dim3(threads), lds, s, B, tile_chunks);
+        else hipLaunchKernelGGL((k_refine_kernelwise<kChunk, false>), dim3(nwg), dim3(threads), lds, s, B, tile_chunks);
+    }
+    trace_mark(s, cls == 0 ? MMSE_STAGE_W_REFINE_SMALL : MMSE_STAGE_W_REFINE);
+    return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+}
+
+// The stages for a list of tensors (already validated): sweep, refinement, codes; one launch per stage for up to
+// kMaxBatch tensors (kMaxBatchExt when the call uses the extension fields), groups of that many beyond.
 int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_search, hipStream_t s)
 {
     const int G = p->grid_points;
@@ -178,126 +262,69 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
         while (j >= 0 && items[j].a.n < it.a.n) { items[j + 1] = items[j]; --j; }
         items[j + 1] = it;
     }
-    if (do_search) {
-        // kernels of <= 64 elements go to the one-wave-per-kernel path (when the grid fits 8 candidates a lane)
-        // ... and when there are enough of them to pay for a launch of their own
-        long long small_rows = 0;
-        for (int i = 0; i < count; ++i)
-            if (items[i].a.n <= kChunk) small_rows += items[i].a.K;
-        const bool small_ok = G <= 512 && small_rows >= 2048;
-        for (int pass = 0; pass < 2; ++pass) {                 // 0: general kernels, 1: small ones
-            Batch B{};
-            fill_common(B, p);
-            int nb = 0, wg = 0, max_npad = 0;
-            auto flush = [&]() -> int {
-                if (nb == 0) return MMSE_OK;
-                B.start[nb] = wg;
-                B.count = nb;
-                int rc = MMSE_OK;
-                if (pass == 0) {
-                    rc = launch_sweep_any(C, B, wg, G, max_npad, s);
-                } else {
-                    const int cs = (G + 63) / 64;
-                    if (cs <= 1) hipLaunchKernelGGL(k_sweep_small<1>, dim3(wg), dim3(256), 0, s, B);
-                    else if (cs <= 2) hipLaunchKernelGGL(k_sweep_small<2>, dim3(wg), dim3(256), 0, s, B);
-                    else if (cs <= 4) hipLaunchKernelGGL(k_sweep_small<4>, dim3(wg), dim3(256), 0, s, B);
-                    else hipLaunchKernelGGL(k_sweep_small<8>, dim3(wg), dim3(256), 0, s, B);
-                    trace_mark(s, MMSE_STAGE_W_SWEEP_SMALL);
-                    rc = hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
-                }
-                nb = 0; wg = 0; max_npad = 0;
-                return rc;
-            };
-            for (int i = 0; i < count; ++i) {
-                const TensorArgs& a = items[i].a;
-                const bool small = small_ok && a.n <= kChunk;
-                if (small != (pass == 1)) continue;
-                const int add = pass == 0 ? a.K : (a.K + 3) / 4;
-                if (nb > 0 && wg + (long long)add > kMaxLaunchWG) { const int rc = flush(); if (rc) return rc; }
-                B.t[nb] = a;
-                B.start[nb] = wg;
-                wg += add;
-                const int npad = (a.n + kChunk - 1) & ~(kChunk - 1);
-                max_npad = npad > max_npad ? npad : max_npad;
-                if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
-            }
-            const int rc = flush();
-            if (rc) return rc;
-        }
-        if (p->refine_iters > 0) {
-            // classes: kernels of <= 16 elements (one lane each, 16 slots), then by lanes per kernel
-            for (int cls = 0; cls < 4; ++cls) {
-                const int threads = cls == 3 ? 1024 : (cls == 2 ? 512 : 256);
-                Batch B{};
-                fill_common(B, p);
-                int nb = 0, wg = 0;
-                auto flush = [&]() -> int {
-                    if (nb == 0) return MMSE_OK;
-                    B.start[nb] = wg;
-                    B.count = nb;
-                    // LDS: combine buffer (2 doubles per thread) + one transpose tile per wave
-                    const int tile_chunks = cls == 0 ? 0 : 32 * 256 / threads;
-                    const size_t lds = (size_t)threads * 2 * sizeof(double) +
-                                       (size_t)(threads / 64) * tile_chunks * kTileStride * sizeof(float);
-                    bool xf = false;
-                    for (int i = 0; i < nb; ++i) xf = xf || B.t[i].scale1 != nullptr || B.t[i].sub_packed != nullptr;
-                    if (cls == 0) {
-                        if (xf) hipLaunchKernelGGL((k_refine_kernelwise<16, true>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
-                        else hipLaunchKernelGGL((k_refine_kernelwise<16, false>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
-                    } else {
-                        if (xf) hipLaunchKernelGGL((k_refine_kernelwise<kChunk, true>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
-                        else hipLaunchKernelGGL((k_refine_kernelwise<kChunk, false>), dim3(wg), dim3(threads), lds, s, B, tile_chunks);
-                    }
-                    trace_mark(s, cls == 0 ? MMSE_STAGE_W_REFINE_SMALL : MMSE_STAGE_W_REFINE);
-                    nb = 0; wg = 0;
-                    return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
-                };
-                for (int i = 0; i < count; ++i) {
-                    const TensorArgs& a = items[i].a;
-                    const int m = (a.n + kChunk - 1) / kChunk;
-                    const int c = a.n <= 16 ? 0 : (m <= 256 ? 1 : (m <= 512 ? 2 : 3));
-                    if (c != cls) continue;
-                    const int lanes = cls == 0 ? 1 : m;
-                    const int cpw = threads / lanes;
-                    const int add = (a.K + cpw - 1) / cpw;
-                    if (nb > 0 && wg + (long long)add > kMaxLaunchWG) { const int rc = flush(); if (rc) return rc; }
-                    B.t[nb] = a;
-                    if (a.n & 1) B.t[nb].packed = nullptr;     // odd n: bytes straddle kernels, k_pack_int4 does those
-                    B.start[nb] = wg;
-                    wg += add;
-                    if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
-                }
-                const int rc = flush();
-                if (rc) return rc;
-            }
-        }
+    int max_n = 0;
+    bool any_small = false, xf = false;
+    for (int i = 0; i < count; ++i) {
+        max_n = items[i].a.n > max_n ? items[i].a.n : max_n;
+        any_small = any_small || items[i].a.n <= kChunk;
+        xf = xf || items[i].a.scale1 != nullptr || items[i].a.sub_packed != nullptr;
     }
-    // pack
-    {
+    WeightShape sh{};
+    sh.waves = (G + 64 * C - 1) / (64 * C);
+    sh.do_search = do_search ? 1 : 0;
+    sh.iters = p->refine_iters;
+    // tiny kernels take the one-wave-per-kernel path inside the sweep launch, when that variant is compiled for this
+    // grid and no kernel of the call needs more than the short binary counter
+    sh.CS = (any_small && max_n <= kTile) ? small_cs(C, G) : 0;
+
+    // sweep launch: LDS for the longest kernel that is staged whole, or the streaming tile of the longer ones
+    auto sweep_lds = [&](const TensorArgs& a) -> int {
+        if (sh.CS > 0 && a.n <= kChunk) return 0;
+        const int npad = (a.n + kChunk - 1) & ~(kChunk - 1);
+        return npad <= kTile ? npad : kTileStream;
+    };
+
+    long long totals[ST_COUNT] = {};
+    for (int st = 0; st < ST_COUNT; ++st)
+        for (int i = 0; i < count; ++i)
+            totals[st] += stage_wgs(st, items[i].a.K, items[i].a.n, items[i].a.packed != nullptr, sh);
+    bool has_ext = false;
+    for (int i = 0; i < count; ++i) {
+        const TensorArgs& a = items[i].a;
+        has_ext = has_ext || a.grid_sse || a.sub_packed || a.sub_scale || a.active;
+    }
+    const int cap = has_ext ? kMaxBatchExt : kMaxBatch;
+    for (int st = 0; st < ST_COUNT; ++st) {
+        if (totals[st] == 0) continue;
         Batch B{};
         fill_common(B, p);
-        int nb = 0, wg = 0;
+        B.has_ext = has_ext ? 1 : 0;
+        int nb = 0, wg = 0, lds_floats = 0, gmax_n = 0;
+        bool gxf = false;
         auto flush = [&]() -> int {
             if (nb == 0) return MMSE_OK;
             B.start[nb] = wg;
             B.count = nb;
-            hipLaunchKernelGGL(k_pack_int4, dim3(wg), dim3(kPackThreads), 0, s, B);
-            trace_mark(s, MMSE_STAGE_W_PACK);
-            nb = 0; wg = 0;
-            return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+            WeightShape gsh = sh;
+            const int chunks = ((gmax_n + kChunk - 1) & ~(kChunk - 1)) / kChunk;
+            const int rc = launch_stage(st, B, wg, C, gsh, lds_floats, chunks, gxf, s);
+            nb = 0; wg = 0; lds_floats = 0; gmax_n = 0; gxf = false;
+            return rc;
         };
         for (int i = 0; i < count; ++i) {
             const TensorArgs& a = items[i].a;
-            if (!a.packed) continue;
-            if (do_search && p->refine_iters > 0 && (a.n & 1) == 0) continue;   // coded by the refinement kernel
-            const long long total = (long long)a.K * a.n;
-            const long long per_wg = (long long)kPackThreads * kPackPerThread;
-            const int add = (int)((total + per_wg - 1) / per_wg);
-            if (nb > 0 && wg + (long long)add > kMaxLaunchWG) { const int rc = flush(); if (rc) return rc; }
-            B.t[nb] = a;
+            const long long add = stage_wgs(st, a.K, a.n, a.packed != nullptr, sh);
+            if (add == 0) continue;
+            if (nb > 0 && wg + add > kMaxLaunchWG) { const int rc = flush(); if (rc) return rc; }
+            B.t[nb] = TensorCore{a.w, a.scale1, a.scale, a.idx, a.sse, a.absmax, a.packed, a.K, a.n};
+            if (has_ext) B.e[nb] = TensorExt{a.grid_sse, a.sub_packed, a.sub_scale, a.active};
             B.start[nb] = wg;
-            wg += add;
-            if (++nb == kMaxBatch) { const int rc = flush(); if (rc) return rc; }
+            wg += (int)add;
+            const int l = sweep_lds(a);
+            lds_floats = l > lds_floats ? l : lds_floats;
+            gmax_n = a.n > gmax_n ? a.n : gmax_n;
+            gxf = gxf || a.scale1 != nullptr || a.sub_packed != nullptr;
+            if (++nb == cap) { const int rc = flush(); if (rc) return rc; }
         }
         const int rc = flush();
         if (rc) return rc;
@@ -488,8 +515,8 @@ int mmse_scale_search_batched(const mmse_tensor_desc_t* descs_host, int32_t coun
         if (rc) return rc;
         sumK += descs_host[i].K;
     }
-    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < round256((size_t)sumK * sizeof(float)))
-        return MMSE_ERR_WORKSPACE;
+    const size_t absmax_bytes = round256((size_t)sumK * sizeof(float));
+    if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < absmax_bytes) return MMSE_ERR_WORKSPACE;
     // the host-side table: on the stack for up to kStackItems tensors, else temporary host memory
     constexpr int kStackItems = 64;
     Item stack_items[kStackItems] = {};

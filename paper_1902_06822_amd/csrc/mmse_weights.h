@@ -8,7 +8,12 @@ namespace {
 // ---------------------------------------------------------------------------------
 // k_sweep_kernelwise: abs-max + grid sweep + argmin, one workgroup per weight kernel
 // ---------------------------------------------------------------------------------
-template <int C, int LV>   // LV: binary-counter levels, enough for the longest kernel of the launch
+template <int CS> __device__ __forceinline__ void sweep_small_wave(const Batch& B, const TensorArgs& A, int k, int lane);
+
+// LV: binary-counter levels, enough for the longest kernel of the launch.  CS > 0: kernels of at most 64
+// elements take the one-wave-per-kernel path (sweep_small_wave with CS candidates per lane), as many per
+// workgroup as it has waves; the host counts their workgroups accordingly.
+template <int C, int LV, int CS>
 __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 {
     extern __shared__ float4 smem4[];
@@ -19,10 +24,17 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x, nwaves = nthreads >> 6;
-    const int t = find_tensor(B, blockIdx.x);
-    const TensorArgs& A = B.t[t];
-    const int k = blockIdx.x - B.start[t];
+    int k;
+    const int t = find_tensor(B, blockIdx.x, k);
+    const TensorArgs A = tensor_of(B, t);
     const int n = A.n;
+    if constexpr (CS > 0) {
+        if (n <= kChunk) {                                    // uniform over the workgroup; no barrier on this path
+            const int ks = k * nwaves + wave;
+            if (ks < A.K) sweep_small_wave<CS>(B, A, ks, lane);
+            return;
+        }
+    }
     const float* __restrict__ src = A.w + (size_t)k * n;
     const float lo = B.lo, hi = B.hi;
     if (A.active != nullptr && A.active[k] == 0) return;      // uniform: the whole workgroup leaves
@@ -137,19 +149,15 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 }
 
 // ---------------------------------------------------------------------------------
-// k_sweep_small: the same for kernels of at most 64 elements (depthwise 3x3, first layers,
-// narrow pointwise layers): one WAVE per kernel, four kernels per workgroup, no LDS and no
-// barrier.  Lane i holds element i; an element reaches all lanes as a scalar operand
-// (v_readlane), lanes own C = ceil(G/64) candidates each; a single chunk needs no tree.
+// sweep_small_wave: the same for kernels of at most 64 elements (depthwise 3x3, first layers,
+// narrow pointwise layers): one WAVE per kernel, as many kernels per workgroup as it has waves, no LDS and no
+// barrier; part of k_sweep_kernelwise, so that a network's tiny and ordinary kernels share one launch.  Lane i
+// holds element i; an element reaches all lanes as a scalar operand (v_readlane), lanes own C >= ceil(G/64)
+// candidates each; a single chunk needs no tree.
 // ---------------------------------------------------------------------------------
 template <int C>
-__global__ void __launch_bounds__(256) k_sweep_small(const Batch B)
+__device__ __forceinline__ void sweep_small_wave(const Batch& B, const TensorArgs& A, int k, int lane)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t = find_tensor(B, blockIdx.x);
-    const TensorArgs& A = B.t[t];
-    const int k = (blockIdx.x - B.start[t]) * 4 + wave;
-    if (k >= A.K) return;                                     // waves are independent: no barrier below
     if (A.active != nullptr && A.active[k] == 0) return;
     const int n = A.n;                                        // <= 64
     const float lo = B.lo, hi = B.hi;
@@ -267,9 +275,9 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
     float* tiles = reinterpret_cast<float*>(smem_d + 2 * blockDim.x);
 
     const int tid = threadIdx.x;
-    const int t = find_tensor(B, blockIdx.x);
-    const TensorArgs& A = B.t[t];
-    const int g = blockIdx.x - B.start[t];
+    int g;
+    const int t = find_tensor(B, blockIdx.x, g);
+    const TensorArgs A = tensor_of(B, t);
     const int n = A.n;
     const int m = (CL == kChunk) ? (n + kChunk - 1) / kChunk : 1;
     const int cpw = blockDim.x / m;           // kernels per workgroup (host guarantees m <= blockDim)
@@ -426,9 +434,9 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
         A.sse[k] = best;
     }
 
-    // Fused INT4 codes (the host passes `packed` here only when n is even, so that every chunk
-    // starts and ends on a byte boundary): the chunk is still in registers, the scale is final.
-    if (A.packed != nullptr && in_range) {
+    // Fused INT4 codes, when n is even, so that every chunk starts and ends on a byte boundary (tensors with
+    // odd n are coded by k_pack_int4): the chunk is still in registers, the scale is final.
+    if (A.packed != nullptr && (n & 1) == 0 && in_range) {
         const float inv = 1.0f / (active ? best_a : 1.0f);      // all-zero / rejected kernels: x is 0 here, codes 0
         const int e0 = c * kChunk;
         const int len = (n - e0) < CL ? (n - e0) : CL;
@@ -463,9 +471,9 @@ __global__ void __launch_bounds__(1024) k_refine_kernelwise(const Batch B, int t
 // ---------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kPackThreads) k_pack_int4(const Batch B)
 {
-    const int t = find_tensor(B, blockIdx.x);
-    const TensorArgs& A = B.t[t];
-    const int g = blockIdx.x - B.start[t];
+    int g;
+    const int t = find_tensor(B, blockIdx.x, g);
+    const TensorArgs A = tensor_of(B, t);
     const int n = A.n;
     const long long total = (long long)A.K * n;
     const long long e0 = ((long long)g * kPackThreads + threadIdx.x) * kPackPerThread;

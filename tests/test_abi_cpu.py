@@ -220,7 +220,7 @@ def test_kernels_spill_nothing():
         m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
         if m and name:
             seen[name] = int(m.group(1))
-    for must in ("k_sweep_kernelwise", "k_sweep_small", "k_refine_kernelwise", "k_pack_int4", "k_act_sweep", "k_act_probe",
+    for must in ("k_sweep_kernelwise", "k_refine_kernelwise", "k_pack_int4", "k_act_sweep", "k_act_probe",
                  "k_act_absmax", "k_act_reduce64", "k_act_argmin", "k_act_finish", "k_dual_ls", "k_alt_kernelwise"):
         assert any(must in k for k in seen), (must, sorted(seen))
     assert len(seen) >= 30
