@@ -485,8 +485,8 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
 
     kernels = []
     tw = traced(plan_w)
-    sw_l = tw.get(1, (0, 0.0))[0] + tw.get(2, (0, 0.0))[0]
-    sw_ms = tw.get(1, (0, 0.0))[1] + tw.get(2, (0, 0.0))[1]
+    sw_l = tw.get(1, (0, 0.0))[0] + tw.get(2, (0, 0.0))[0] + tw.get(6, (0, 0.0))[0]
+    sw_ms = tw.get(1, (0, 0.0))[1] + tw.get(2, (0, 0.0))[1] + tw.get(6, (0, 0.0))[1]
     e_w = _alu_entry("k_sweep_kernelwise (+ k_sweep_small): abs-max, grid sweep, argmin of all weight tensors",
                      w_elems * G, sw_l, sw_ms, traffic.get(("k_sweep_kernelwise", wl), (None,))[0])
     kernels.append(e_w)

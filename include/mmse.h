@@ -283,6 +283,7 @@ enum {
     MMSE_STAGE_W_REFINE = 3,        /* k_refine_kernelwise<64>: refinement (+ codes when n is even)      */
     MMSE_STAGE_W_REFINE_SMALL = 4,  /* k_refine_kernelwise<16>                                           */
     MMSE_STAGE_W_PACK = 5,          /* k_pack_int4                                                       */
+    MMSE_STAGE_W_FUSED = 6,         /* k_sweep_kernelwise, whole search in one launch (small calls)      */
     MMSE_STAGE_A_INIT = 10,
     MMSE_STAGE_A_ABSMAX = 11,       /* k_act_absmax                                                      */
     MMSE_STAGE_A_SWEEP = 12,        /* k_act_sweep (Section 3.7, Eq. 15)                                 */

@@ -13,26 +13,6 @@ namespace {
 //   part0[nb][G] doubles                  per-block tree sums of the grid sweep
 //   part1[ceil(nb/64)][G], part2, ...     upper tree levels, 64 blocks at a time
 //   probe0[nb], probe1[...], ...          same hierarchy for one refinement probe
-constexpr int kMaxProbes = 8;          // scales evaluated in one pass over an activation tensor
-
-struct ActState {
-    unsigned absmax_bits;
-    int status;              // 0 normal, 1 all-zero (scale 1), 2 rejected
-    int j;                   // grid argmin
-    int it;                  // golden-section iterations decided so far
-    int done;                // refinement finished
-    int have_c, have_d;      // f(pc), f(pd) known
-    int nprobe;              // scales to evaluate in the next pass
-    float absmax;
-    float lo_a, hi_a, pc, pd, best_a;
-    float probes[kMaxProbes];
-    float probe_inv[kMaxProbes];     // 1 / probes[i], for the kernels that evaluate them
-    double ec, ed, best;
-    unsigned min_key, max_key;   // offset form: order-preserving keys of min and max
-    float out_scale; int out_idx; double out_sse;    // result slots for calls that only want the grid errors
-    float delta;                 // offset form: min of the tensor
-};
-
 // What the activation kernels search instead of the stored tensor (never written to memory):
 //   mode 1: the residual of a first tensor, x - s*[x/s] saturated to [lo1, hi1]   (Section 3.7, Eq. 16)
 //   mode 2: the shifted tensor x - delta, delta = min x                            (Section 3.1, Eq. 2)
@@ -132,94 +112,6 @@ __global__ void k_act_init(ActState* Sall, int count)
         S->ec = S->ed = S->best = 0.0;
         S->min_key = 0xffffffffu; S->max_key = 0u; S->delta = 0.0f;
     }
-}
-
-// ---- golden-section bookkeeping (one thread) ---------------------------------------
-// The search is sequential: each iteration needs f at one new scale.  One pass over a big
-// tensor costs a full read of it, so a pass evaluates the scale(s) the search is waiting
-// for *and* every scale the next two iterations could ask for (both outcomes of each
-// comparison: 1 + 2 + 4, or 2 + 2 + 4 at the start).  act_advance then replays the plain
-// sequential algorithm, looking values up by scale; it stops when a value is missing.
-// The probes are produced by the same fp32 expressions on both paths, so a lookup is an
-// exact match.  Nothing about the result depends on how much was evaluated ahead.
-template <int DEPTH>
-__device__ void act_enumerate(float lo_a, float hi_a, float pc, float pd, int depth, float* list, int& n)
-{
-    if constexpr (DEPTH > 0) {
-        if (depth == 0) return;
-        {   // f(pc) <= f(pd): keep [lo, pd]
-            const float nh = pd, npd = pc;
-            const float npc = __builtin_fmaf(-kPhi, nh - lo_a, nh);
-            if (n < kMaxProbes) list[n++] = npc;
-            act_enumerate<DEPTH - 1>(lo_a, nh, npc, npd, depth - 1, list, n);
-        }
-        {   // otherwise: keep [pc, hi]
-            const float nl = pc, npc = pd;
-            const float npd = __builtin_fmaf(kPhi, hi_a - nl, nl);
-            if (n < kMaxProbes) list[n++] = npd;
-            act_enumerate<DEPTH - 1>(nl, hi_a, npc, npd, depth - 1, list, n);
-        }
-    }
-}
-
-__device__ void act_plan(ActState* S, int iters)
-{
-    int n = 0;
-    float list[kMaxProbes];
-    if (!S->done) {
-        if (!S->have_c) list[n++] = S->pc;
-        if (!S->have_d) list[n++] = S->pd;
-        int depth = iters - S->it;
-        if (depth > 2) depth = 2;
-        act_enumerate<2>(S->lo_a, S->hi_a, S->pc, S->pd, depth, list, n);
-    }
-    S->nprobe = n;
-    for (int i = 0; i < kMaxProbes; ++i) {
-        const float a = i < n ? list[i] : 1.0f;
-        S->probes[i] = a;
-        S->probe_inv[i] = 1.0f / a;
-    }
-}
-
-__device__ bool act_lookup(const float* probes, const double* vals, int n, float a, double& out)
-{
-    for (int i = 0; i < n; ++i)
-        if (probes[i] == a) { out = vals[i]; return true; }
-    return false;
-}
-
-__device__ void act_advance(ActState* S, const double* vals, int iters)
-{
-    float lo_a = S->lo_a, hi_a = S->hi_a, pc = S->pc, pd = S->pd, best_a = S->best_a;
-    double ec = S->ec, ed = S->ed, best = S->best;
-    int have_c = S->have_c, have_d = S->have_d, it = S->it, done = S->done;
-    const int n = S->nprobe;
-    while (!done) {
-        if (!have_c) {
-            if (!act_lookup(S->probes, vals, n, pc, ec)) break;
-            have_c = 1;
-            if (ec < best) { best = ec; best_a = pc; }
-        }
-        if (!have_d) {
-            if (!act_lookup(S->probes, vals, n, pd, ed)) break;
-            have_d = 1;
-            if (ed < best) { best = ed; best_a = pd; }
-        }
-        if (it == iters) { done = 1; break; }
-        if (ec <= ed) {
-            hi_a = pd; pd = pc; ed = ec;
-            pc = __builtin_fmaf(-kPhi, hi_a - lo_a, hi_a);
-            have_c = 0;
-        } else {
-            lo_a = pc; pc = pd; ec = ed;
-            pd = __builtin_fmaf(kPhi, hi_a - lo_a, lo_a);
-            have_d = 0;
-        }
-        ++it;
-    }
-    S->lo_a = lo_a; S->hi_a = hi_a; S->pc = pc; S->pd = pd; S->best_a = best_a;
-    S->ec = ec; S->ed = ed; S->best = best;
-    S->have_c = have_c; S->have_d = have_d; S->it = it; S->done = done;
 }
 
 // MODE 0: max |x| (integer max of the bit patterns); 1: max |residual of the first tensor|;
@@ -591,8 +483,7 @@ __global__ void __launch_bounds__(512) k_act_finish(const ActBatch B, int level,
     if (t < kMaxProbes) vals[t] = tree_rows64(&grp[0][t], ngroups, kMaxProbes);
     __syncthreads();
     if (t == 0) {
-        act_advance(S, vals, iters);
-        act_plan(S, iters);
+        act_advance_plan(S, vals, iters);
         *scale = S->best_a;
         *sse = S->best;
     }

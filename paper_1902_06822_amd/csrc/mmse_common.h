@@ -75,6 +75,7 @@ struct Batch {
     int iters;
     float lo, hi;               // (float)qmin, (float)qmax
     int has_ext;
+    int fused_part_off;         // fused search: floats from the start of the LDS slice to its reduction buffers
 };
 static_assert(sizeof(TensorCore) == 64 && sizeof(TensorExt) == 32, "descriptor sizes");
 static_assert(sizeof(Batch) <= 4096, "the descriptor table must fit the kernel argument buffer");
@@ -332,6 +333,161 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsig
         for (int u = 0; u < C; ++u) t[u] = (double)s[u];
         tree_push<C, L>(st, t, ci);
     }
+}
+
+constexpr int kMaxProbes = 8;          // scales evaluated in one pass over an activation tensor
+
+// State of one golden-section refinement with look-ahead (per activation tensor in device memory; per kernel in
+// LDS in the fused weight search).
+struct ActState {
+    unsigned absmax_bits;
+    int status;              // 0 normal, 1 all-zero (scale 1), 2 rejected
+    int j;                   // grid argmin
+    int it;                  // golden-section iterations decided so far
+    int done;                // refinement finished
+    int have_c, have_d;      // f(pc), f(pd) known
+    int nprobe;              // scales to evaluate in the next pass
+    float absmax;
+    float lo_a, hi_a, pc, pd, best_a;
+    float probes[kMaxProbes];
+    float probe_inv[kMaxProbes];     // 1 / probes[i], for the kernels that evaluate them
+    double ec, ed, best;
+    unsigned min_key, max_key;   // offset form: order-preserving keys of min and max
+    float out_scale; int out_idx; double out_sse;    // result slots for calls that only want the grid errors
+    float delta;                 // offset form: min of the tensor
+};
+
+// ---- golden-section bookkeeping (one thread) ---------------------------------------
+// The search is sequential: each iteration needs f at one new scale.  One pass over a big
+// tensor costs a full read of it, so a pass evaluates the scale(s) the search is waiting
+// for *and* every scale the next two iterations could ask for (both outcomes of each
+// comparison: 1 + 2 + 4, or 2 + 2 + 4 at the start).  gs_advance then replays the plain
+// sequential algorithm, looking values up by scale; it stops when a value is missing.
+// The probes are produced by the same fp32 expressions on both paths, so a lookup is an
+// exact match.  Nothing about the result depends on how much was evaluated ahead.
+// The search state in registers (one thread does the bookkeeping; memory is read once and written once).
+struct GsRegs {
+    float lo_a, hi_a, pc, pd, best_a;
+    double ec, ed, best;
+    int have_c, have_d, it, done;
+};
+
+__device__ __forceinline__ GsRegs gs_load(const ActState* S)
+{
+    GsRegs R;
+    R.lo_a = S->lo_a; R.hi_a = S->hi_a; R.pc = S->pc; R.pd = S->pd; R.best_a = S->best_a;
+    R.ec = S->ec; R.ed = S->ed; R.best = S->best;
+    R.have_c = S->have_c; R.have_d = S->have_d; R.it = S->it; R.done = S->done;
+    return R;
+}
+
+__device__ __forceinline__ void gs_store(ActState* S, const GsRegs& R)
+{
+    S->lo_a = R.lo_a; S->hi_a = R.hi_a; S->pc = R.pc; S->pd = R.pd; S->best_a = R.best_a;
+    S->ec = R.ec; S->ed = R.ed; S->best = R.best;
+    S->have_c = R.have_c; S->have_d = R.have_d; S->it = R.it; S->done = R.done;
+}
+
+// f at scale a among the n values of the last pass (the first match, as the list may hold a scale twice)
+__device__ __forceinline__ bool gs_lookup(const float (&pr)[kMaxProbes], const double (&v)[kMaxProbes], int n, float a, double& out)
+{
+    bool hit = false;
+#pragma unroll
+    for (int i = 0; i < kMaxProbes; ++i)
+        if (!hit && i < n && pr[i] == a) { out = v[i]; hit = true; }
+    return hit;
+}
+
+// Replays the sequential golden section with the values of the last pass until one is missing.
+__device__ __forceinline__ void gs_advance(GsRegs& R, const float (&pr)[kMaxProbes], const double (&v)[kMaxProbes], int n, int iters)
+{
+    while (!R.done) {
+        if (!R.have_c) {
+            if (!gs_lookup(pr, v, n, R.pc, R.ec)) break;
+            R.have_c = 1;
+            if (R.ec < R.best) { R.best = R.ec; R.best_a = R.pc; }
+        }
+        if (!R.have_d) {
+            if (!gs_lookup(pr, v, n, R.pd, R.ed)) break;
+            R.have_d = 1;
+            if (R.ed < R.best) { R.best = R.ed; R.best_a = R.pd; }
+        }
+        if (R.it == iters) { R.done = 1; break; }
+        if (R.ec <= R.ed) {
+            R.hi_a = R.pd; R.pd = R.pc; R.ed = R.ec;
+            R.pc = __builtin_fmaf(-kPhi, R.hi_a - R.lo_a, R.hi_a);
+            R.have_c = 0;
+        } else {
+            R.lo_a = R.pc; R.pc = R.pd; R.ec = R.ed;
+            R.pd = __builtin_fmaf(kPhi, R.hi_a - R.lo_a, R.lo_a);
+            R.have_d = 0;
+        }
+        ++R.it;
+    }
+}
+
+// The scales of the next pass.  max_depth: iterations to look ahead (0: only the scale(s) the search waits for;
+// 2: up to 1 + 2 + 4 scales).  with_inv: also store their reciprocals.
+// The scales of the next pass: the one(s) the search waits for, then what its next one or two iterations could
+// ask for -- after "keep [lo, pd]" (L) or "keep [pc, hi]" (R), and after each of those again (LL, LR, RL, RR) --
+// by the same fp32 expressions gs_advance uses.  Every index below is a constant (no array in scratch memory).
+__device__ __forceinline__ int gs_plan_list(const GsRegs& R, int iters, int max_depth, float (&list)[kMaxProbes])
+{
+    int depth = iters - R.it;
+    if (depth > max_depth) depth = max_depth;
+    if (R.done) depth = 0;
+    const float L = __builtin_fmaf(-kPhi, R.pd - R.lo_a, R.pd);
+    const float Rr = __builtin_fmaf(kPhi, R.hi_a - R.pc, R.pc);
+    const float LL = __builtin_fmaf(-kPhi, R.pc - R.lo_a, R.pc);
+    const float LR = __builtin_fmaf(kPhi, R.pd - L, L);
+    const float RL = __builtin_fmaf(-kPhi, Rr - R.pc, Rr);
+    const float RR = __builtin_fmaf(kPhi, R.hi_a - R.pd, R.pd);
+    const int ncand = depth <= 0 ? 0 : (depth == 1 ? 2 : 6);
+    float cand[6] = {L, Rr, LL, LR, RL, RR};
+#pragma unroll
+    for (int i = 0; i < 6; ++i) cand[i] = i < ncand ? cand[i] : 1.0f;
+    const int npend = R.done ? 0 : (R.have_c ? 0 : 1) + (R.have_d ? 0 : 1);
+    const float p0 = !R.have_c ? R.pc : R.pd;         // first pending scale (when there is one)
+    // list = [pending..., cand...], padded with 1.0
+    const float a0[kMaxProbes] = {cand[0], cand[1], cand[2], cand[3], cand[4], cand[5], 1.0f, 1.0f};
+    const float a1[kMaxProbes] = {p0, cand[0], cand[1], cand[2], cand[3], cand[4], cand[5], 1.0f};
+    const float a2[kMaxProbes] = {R.pc, R.pd, cand[0], cand[1], cand[2], cand[3], cand[4], cand[5]};
+#pragma unroll
+    for (int i = 0; i < kMaxProbes; ++i) list[i] = npend == 0 ? a0[i] : (npend == 1 ? a1[i] : a2[i]);
+    return npend + ncand;
+}
+
+__device__ __forceinline__ void gs_plan(ActState* S, const GsRegs& R, int iters, int max_depth, bool with_inv)
+{
+    float list[kMaxProbes];
+    const int n = gs_plan_list(R, iters, max_depth, list);
+    S->nprobe = n;
+#pragma unroll
+    for (int i = 0; i < kMaxProbes; ++i) {
+        const float a = i < n ? list[i] : 1.0f;
+        S->probes[i] = a;
+        if (with_inv) S->probe_inv[i] = 1.0f / a;
+    }
+}
+
+__device__ void act_plan(ActState* S, int iters, int max_depth = 2, bool with_inv = true)
+{
+    const GsRegs R = gs_load(S);
+    gs_plan(S, R, iters, max_depth, with_inv);
+}
+
+// advance with the values of the last pass, then plan the next one
+__device__ void act_advance_plan(ActState* S, const double* vals, int iters, int max_depth = 2, bool with_inv = true)
+{
+    GsRegs R = gs_load(S);
+    const int n = S->nprobe;
+    float pr[kMaxProbes];
+    double v[kMaxProbes];
+#pragma unroll
+    for (int i = 0; i < kMaxProbes; ++i) { pr[i] = S->probes[i]; v[i] = vals[i]; }
+    gs_advance(R, pr, v, n, iters);
+    gs_store(S, R);
+    gs_plan(S, R, iters, max_depth, with_inv);
 }
 
 // Tensor that owns workgroup bid, and that workgroup's number inside the tensor.

@@ -81,6 +81,7 @@ inline void trace_mark(hipStream_t s, int stage)
 // number of kernels or blocks (1024 only for kernels of more than 32768 elements, of which a tensor has fewer
 // than 65536), so launches are cut at this many workgroups.
 constexpr long long kMaxLaunchWG = 1LL << 22;
+constexpr long long kFusedMaxKernels = 1024;      // calls of at most this many kernels take the single-launch search
 static_assert(kMaxLaunchWG == MMSE_MAX_KERNELS, "one workgroup per kernel");
 
 int check_params(const mmse_params_t* p)
@@ -140,6 +141,7 @@ struct WeightShape {        // launch shape of the call: the same for host and d
     int CS;                 // candidates per lane of the one-wave-per-kernel path (0: not used)
     int do_search;
     int iters;
+    int fused;              // the sweep launch also refines and codes (small calls)
 };
 
 __host__ __device__ inline int refine_class(int n)
@@ -158,14 +160,14 @@ __host__ __device__ inline long long stage_wgs(int stage, long long K, int n, bo
     }
     if (stage >= ST_REF0 && stage <= ST_REF3) {
         const int cls = stage - ST_REF0;
-        if (!sh.do_search || sh.iters <= 0 || refine_class(n) != cls) return 0;
+        if (!sh.do_search || sh.iters <= 0 || sh.fused || refine_class(n) != cls) return 0;
         const int lanes = cls == 0 ? 1 : (n + kChunk - 1) / kChunk;
         const int cpw = refine_threads(cls) / lanes;
         return (K + cpw - 1) / cpw;
     }
     // codes: everything without a search; with one, what the refinement kernel did not code itself (odd n, or no refinement)
     if (!has_packed) return 0;
-    if (sh.do_search && sh.iters > 0 && (n & 1) == 0) return 0;
+    if (sh.do_search && (sh.iters > 0 || sh.fused) && (n & 1) == 0) return 0;
     const long long per_wg = (long long)kPackThreads * kPackPerThread;
     return (K * n + per_wg - 1) / per_wg;
 }
@@ -187,19 +189,26 @@ void launch_sweep_lv(const Batch& B, dim3 grid, dim3 block, size_t lds, int chun
 {
     // binary-counter levels for the longest kernel of the launch: each level is two registers per candidate
     if constexpr (CS > 0) {
-        hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall, CS>), grid, block, lds, s, B);
+        hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall, CS, false>), grid, block, lds, s, B);
     } else {
-        if (chunks <= 128) hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall, 0>), grid, block, lds, s, B);
-        else if (chunks < 512) hipLaunchKernelGGL((k_sweep_kernelwise<C, 9, 0>), grid, block, lds, s, B);
-        else if (chunks < 1024) hipLaunchKernelGGL((k_sweep_kernelwise<C, 10, 0>), grid, block, lds, s, B);
-        else hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW, 0>), grid, block, lds, s, B);
+        if (chunks <= 128) hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKWSmall, 0, false>), grid, block, lds, s, B);
+        else if (chunks < 512) hipLaunchKernelGGL((k_sweep_kernelwise<C, 9, 0, false>), grid, block, lds, s, B);
+        else if (chunks < 1024) hipLaunchKernelGGL((k_sweep_kernelwise<C, 10, 0, false>), grid, block, lds, s, B);
+        else hipLaunchKernelGGL((k_sweep_kernelwise<C, kLevelsKW, 0, false>), grid, block, lds, s, B);
     }
 }
 
-// CS > 0 only together with kernels of at most 128 chunks (the caller checks)
-int launch_sweep(int C, int CS, const Batch& B, int nwg, int waves, size_t lds, int chunks, hipStream_t s)
+// CS > 0 and fused only together with kernels of at most 128 chunks (the caller checks)
+int launch_sweep(int C, int CS, bool fused, const Batch& B, int nwg, int waves, size_t lds, int chunks, hipStream_t s)
 {
     const dim3 grid(nwg), block(64 * waves);
+    if (fused) {
+        if (C == 1) hipLaunchKernelGGL((k_sweep_kernelwise<1, kLevelsKWSmall, 0, true>), grid, block, lds, s, B);
+        else if (C == 2) hipLaunchKernelGGL((k_sweep_kernelwise<2, kLevelsKWSmall, 0, true>), grid, block, lds, s, B);
+        else hipLaunchKernelGGL((k_sweep_kernelwise<4, kLevelsKWSmall, 0, true>), grid, block, lds, s, B);
+        trace_mark(s, MMSE_STAGE_W_FUSED);
+        return hipGetLastError() == hipSuccess ? MMSE_OK : MMSE_ERR_LAUNCH;
+    }
     if (C == 1 && CS == 0) launch_sweep_lv<1, 0>(B, grid, block, lds, chunks, s);
     else if (C == 1 && CS == 1) launch_sweep_lv<1, 1>(B, grid, block, lds, chunks, s);
     else if (C == 1 && CS == 2) launch_sweep_lv<1, 2>(B, grid, block, lds, chunks, s);
@@ -225,8 +234,10 @@ int launch_stage(int stage, const Batch& B, int nwg, int C, const WeightShape& s
                  hipStream_t s)
 {
     if (nwg <= 0) return MMSE_OK;
-    if (stage == ST_SWEEP)
-        return launch_sweep(C, sh.CS, B, nwg, sh.waves, (size_t)lds_floats * sizeof(float), chunks, s);
+    if (stage == ST_SWEEP)   // fused: the reduction buffers of the refinement (two doubles per thread) follow the slice
+        return launch_sweep(C, sh.CS, sh.fused != 0, B, nwg, sh.waves,
+                            (size_t)lds_floats * sizeof(float) + (sh.fused ? (size_t)sh.waves * 64 * 2 * sizeof(double) : 0),
+                            chunks, s);
     if (stage == ST_PACK) {
         hipLaunchKernelGGL(k_pack_int4, dim3(nwg), dim3(kPackThreads), 0, s, B);
         trace_mark(s, MMSE_STAGE_W_PACK);
@@ -273,14 +284,23 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
     sh.waves = (G + 64 * C - 1) / (64 * C);
     sh.do_search = do_search ? 1 : 0;
     sh.iters = p->refine_iters;
+    // A call of few kernels is a chain of dependent launches that mostly wait for each other; then one launch does
+    // the whole search (k_sweep_kernelwise, FUSED): every kernel must fit one LDS tile and have at most as many
+    // chunks as a sweep workgroup has lanes.
+    long long sumK = 0;
+    for (int i = 0; i < count; ++i) sumK += items[i].a.K;
+    sh.fused = (do_search && sumK <= kFusedMaxKernels && max_n <= kTile &&
+                (max_n + kChunk - 1) / kChunk <= 64 * sh.waves) ? 1 : 0;
     // tiny kernels take the one-wave-per-kernel path inside the sweep launch, when that variant is compiled for this
     // grid and no kernel of the call needs more than the short binary counter
-    sh.CS = (any_small && max_n <= kTile) ? small_cs(C, G) : 0;
+    sh.CS = (!sh.fused && any_small && max_n <= kTile) ? small_cs(C, G) : 0;
 
-    // sweep launch: LDS for the longest kernel that is staged whole, or the streaming tile of the longer ones
+    // sweep launch: LDS for the longest kernel that is staged whole (chunks padded apart in the fused search), or
+    // the streaming tile of the longer ones
     auto sweep_lds = [&](const TensorArgs& a) -> int {
         if (sh.CS > 0 && a.n <= kChunk) return 0;
         const int npad = (a.n + kChunk - 1) & ~(kChunk - 1);
+        if (sh.fused) return npad / kChunk * (kChunk + 4);
         return npad <= kTile ? npad : kTileStream;
     };
 
@@ -305,6 +325,7 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
             if (nb == 0) return MMSE_OK;
             B.start[nb] = wg;
             B.count = nb;
+            B.fused_part_off = lds_floats;
             WeightShape gsh = sh;
             const int chunks = ((gmax_n + kChunk - 1) & ~(kChunk - 1)) / kChunk;
             const int rc = launch_stage(st, B, wg, C, gsh, lds_floats, chunks, gxf, s);

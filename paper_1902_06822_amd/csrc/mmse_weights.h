@@ -13,7 +13,14 @@ template <int CS> __device__ __forceinline__ void sweep_small_wave(const Batch& 
 // LV: binary-counter levels, enough for the longest kernel of the launch.  CS > 0: kernels of at most 64
 // elements take the one-wave-per-kernel path (sweep_small_wave with CS candidates per lane), as many per
 // workgroup as it has waves; the host counts their workgroups accordingly.
-template <int C, int LV, int CS>
+// FUSED: the whole search of a kernel in this one launch, for calls so small that the chain of dependent
+// launches, not the arithmetic, is what takes the time: after the argmin the workgroup refines the scale from the
+// slice it still holds in LDS (chunks padded apart by four floats so that lanes reading different chunks hit
+// different banks; lane = (scale, chunk), the scales of a round being the one the golden section waits for and
+// those its next iterations could ask for, as many as the workgroup has lanes for) and writes the codes.  The
+// host only picks this variant when every kernel fits one LDS tile and has at most as many chunks as the
+// workgroup has lanes.  Same arithmetic, same order, same bits as the separate kernels.
+template <int C, int LV, int CS, bool FUSED>
 __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
 {
     extern __shared__ float4 smem4[];
@@ -42,14 +49,15 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
     const long long flat0 = (long long)k * n;
 
     const int npad = (n + kChunk - 1) & ~(kChunk - 1);
-    const bool single = npad <= kTile;
+    const bool single = FUSED || npad <= kTile;
+    constexpr int CSTRIDE = FUSED ? kChunk + 4 : kChunk;      // floats between chunk starts in LDS
 
     // ---- pass 1: abs-max (and, when the kernel fits one tile, the LDS staging)
     unsigned amax = 0;
     if (single) {
         for (int i = tid; i < npad; i += nthreads) {
             const float v = i < n ? xform_apply(X, src[i], flat0 + i, lo, hi) : 0.0f;
-            slice[i] = v;
+            slice[FUSED ? i + 4 * (i >> 6) : i] = v;
             const unsigned b = abs_bits(v);
             amax = b > amax ? b : amax;
         }
@@ -77,6 +85,12 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
         }
         if (A.grid_sse)
             for (int j = tid; j < G; j += nthreads) A.grid_sse[(size_t)k * G + j] = (double)__uint_as_float(0x7fc00000u);
+        if constexpr (FUSED) {                // a rejected kernel is coded as zeros
+            if (A.packed != nullptr && (n & 1) == 0) {
+                uint8_t* dst = A.packed + (((size_t)k * n) >> 1);
+                for (int i = tid; i < (n >> 1); i += nthreads) dst[i] = 0;
+            }
+        }
         return;
     }
     const bool tiny = a < kTiny;              // coded as all-zero with scale 1
@@ -102,7 +116,7 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
         for (int l = 0; l < LV; ++l) st[u][l] = 0.0;
     unsigned ci = 0;
     if (single) {
-        sweep_slice<C, LV>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st);
+        sweep_slice<C, LV, CSTRIDE>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st);
     } else {
         for (int t0 = 0; t0 < npad; t0 += kTileStream) {
             const int tlen = (npad - t0) < kTileStream ? (npad - t0) : kTileStream;
@@ -143,8 +157,124 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
         if (bJ == INT_MAX) bJ = 0;            // only if every f overflowed to inf
         if (A.absmax) A.absmax[k] = a;
         if (A.idx) A.idx[k] = bJ;
-        if (A.sse) A.sse[k] = bE;
-        if (A.scale) A.scale[k] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, bJ);
+        if constexpr (!FUSED) {
+            if (A.sse) A.sse[k] = bE;
+            if (A.scale) A.scale[k] = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, bJ);
+        }
+    }
+    if constexpr (FUSED) {
+        // ---- refinement between the grid neighbours of the argmin, from the slice in LDS.  Every thread keeps the
+        // state of the search in registers and does the same bookkeeping (it is a few dozen instructions; one thread
+        // doing it for all would cost a barrier and a trip through LDS per round).
+        __shared__ double vals2[2][kMaxProbes];   // f at the scales of a round; rounds alternate between the halves, so
+                                                  // that a round's values are never written while the last one's are read
+        __shared__ double s_argE;
+        __shared__ int s_argJ;
+        double* part = reinterpret_cast<double*>(slice + B.fused_part_off);      // two buffers of nthreads doubles
+        const int m = npad / kChunk;                          // chunks = lanes per scale (host: m <= nthreads)
+        const int S = nthreads / m;                           // scales evaluated at a time
+        const int max_depth = S >= 8 ? 2 : (S >= 4 ? 1 : 0);
+        const int iters = B.iters;
+        if (tid == 0) { s_argE = bE; s_argJ = bJ; }
+        __syncthreads();
+        const int j = s_argJ;
+        const float aj = tiny ? 1.0f : grid_alpha(a, qmaxf, Gf, j);
+        GsRegs R;
+        R.it = 0; R.best = s_argE; R.best_a = aj; R.done = 1; R.have_c = R.have_d = 0;
+        R.lo_a = R.hi_a = R.pc = R.pd = 1.0f; R.ec = R.ed = 0.0;
+        if (!tiny && iters > 0) {
+            R.lo_a = j == 0 ? 0.0f : grid_alpha(a, qmaxf, Gf, j - 1);
+            R.hi_a = j == G - 1 ? aj : grid_alpha(a, qmaxf, Gf, j + 1);
+            const float w = R.hi_a - R.lo_a;
+            R.pc = __builtin_fmaf(-kPhi, w, R.hi_a);
+            R.pd = __builtin_fmaf(kPhi, w, R.lo_a);
+            R.done = 0;
+        }
+        float pr[kMaxProbes];
+        int np = gs_plan_list(R, iters, max_depth, pr);
+        const int slot = tid / m, c = tid - slot * m;
+        const float4* my4 = reinterpret_cast<const float4*>(slice + c * CSTRIDE);
+        int par = 0;
+        while (!R.done) {                                     // uniform: every thread holds the same state
+            double* vals = vals2[par];
+            par ^= 1;
+            for (int base = 0; base < np; base += S) {
+                const int pi = base + slot;
+                const bool on = slot < S && pi < np;
+                double v = 0.0;
+                if (on) {
+                    float al[1] = {1.0f};
+#pragma unroll
+                    for (int i = 0; i < kMaxProbes; ++i) al[0] = (i == pi) ? pr[i] : al[0];
+                    const float iv[1] = {1.0f / al[0]};
+                    float sum[1] = {0.0f};
+                    // the chunk comes from LDS two 8-element groups ahead of its use
+                    float4 q[4] = {my4[0], my4[1], my4[2], my4[3]};
+#pragma unroll
+                    for (int e = 0; e < kChunk / 8; ++e) {
+                        const float4 p0 = q[(2 * e) & 3], p1 = q[(2 * e + 1) & 3];
+                        const float xs[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                        if (e + 2 < kChunk / 8) { q[(2 * e) & 3] = my4[2 * e + 4]; q[(2 * e + 1) & 3] = my4[2 * e + 5]; }
+                        __builtin_amdgcn_sched_barrier(0);
+                        eval_stage<8, 1>(xs, al, iv, lo, hi, sum);
+                    }
+                    v = (double)sum[0];
+                }
+                // pairwise tree over the m chunk sums of every scale: aligned groups of sixteen per step; the step
+                // that leaves one value writes it to vals
+                double* cur = part;
+                double* nxt = part + nthreads;
+                if (m == 1) { if (on) vals[pi] = v; } else cur[tid] = v;
+                __syncthreads();
+                int cnt = m;
+                while (cnt > 1) {
+                    const int ncnt = (cnt + 15) >> 4;
+                    if (on && c < ncnt) {
+                        double e16[16];
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) e16[i] = (16 * c + i < cnt) ? cur[slot * m + 16 * c + i] : 0.0;
+#pragma unroll
+                        for (int w = 1; w < 16; w <<= 1)
+#pragma unroll
+                            for (int i = 0; i < 16; i += 2 * w) e16[i] = e16[i] + e16[i + w];
+                        if (ncnt == 1) vals[pi] = e16[0]; else nxt[slot * m + c] = e16[0];
+                    }
+                    __syncthreads();
+                    double* tmp = cur; cur = nxt; nxt = tmp;
+                    cnt = ncnt;
+                }
+            }
+            double v8[kMaxProbes];
+#pragma unroll
+            for (int i = 0; i < kMaxProbes; ++i) v8[i] = vals[i];
+            gs_advance(R, pr, v8, np, iters);
+            np = gs_plan_list(R, iters, max_depth, pr);
+        }
+        const float best_a = R.best_a;
+        if (tid == 0) {
+            if (A.scale) A.scale[k] = best_a;
+            if (A.sse) A.sse[k] = R.best;
+        }
+        // ---- codes, for even n (bytes of a kernel with odd n straddle its neighbours: k_pack_int4 does those)
+        if (A.packed != nullptr && (n & 1) == 0) {
+            const float invb = 1.0f / best_a;
+            uint8_t* dst = A.packed + (((size_t)k * n) >> 1);
+            const bool word_ok = (reinterpret_cast<uintptr_t>(dst) & 3u) == 0;
+            for (int e0 = tid * 8; e0 < n; e0 += nthreads * 8) {
+                const float4* p4 = reinterpret_cast<const float4*>(slice + e0 + 4 * (e0 >> 6));
+                const float4 p0 = p4[0], p1 = p4[1];
+                const float xs[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                unsigned word = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) word |= ((unsigned)(int)code_of(xs[i], invb, lo, hi) & 0xFu) << (4 * i);
+                const int len = (n - e0) < 8 ? (n - e0) : 8;         // even
+                if (len == 8 && word_ok) {
+                    *reinterpret_cast<unsigned*>(dst + (e0 >> 1)) = word;
+                } else {
+                    for (int b = 0; b < (len >> 1); ++b) dst[(e0 >> 1) + b] = (uint8_t)(word >> (8 * b));
+                }
+            }
+        }
     }
 }
 
