@@ -310,6 +310,14 @@ class BatchedPlan:
                "mmse_scale_search_batched")
         return self.results
 
+    def run_subset(self, indices: Sequence[int]) -> List[SearchResult]:
+        """One batched call over some of the plan's tensors (their buffers exist already; only the host-side
+        descriptor table of the call is built here)."""
+        sub = (MmseTensorDesc * len(indices))(*[self.descs[i] for i in indices])
+        _check(load_library().mmse_scale_search_batched(sub, len(indices), C.byref(self.p), self.ws.data_ptr(),
+                                                        self.ws.numel(), _stream()), "mmse_scale_search_batched")
+        return [self.results[i] for i in indices]
+
     def run_traced(self, trace: StageTrace) -> List[SearchResult]:
         _check(load_library().mmse_scale_search_batched_traced(self.descs, len(self.weights), C.byref(self.p),
                                                                self.ws.data_ptr(), self.ws.numel(), _stream(),

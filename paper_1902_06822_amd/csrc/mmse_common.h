@@ -178,25 +178,58 @@ __device__ __forceinline__ void store_stream_u32(unsigned* p, unsigned v) { __bu
 
 __device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
-__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+// Cross-lane exchange inside rows of 16 lanes without LDS: the partner of lane i is i ^ 1, i ^ 2, then 7 - i inside
+// its group of eight and 15 - i inside its row; for a reduction whose operation is symmetric, after the four
+// steps every lane of a row holds the row's result.  The four row results then meet as scalar operands.
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1, 0, 3, 2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2, 3, 0, 1]
+constexpr int kDppHalfMirror = 0x141;   // row_half_mirror
+constexpr int kDppMirror = 0x140;       // row_mirror
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) { return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const unsigned o = (unsigned)__shfl_xor((int)v, off, 64);
-        v = o > v ? o : v;
-    }
-    return v;
+    return __hiloint2double(dpp_i32<CTRL>(__double2hiint(v)), dpp_i32<CTRL>(__double2loint(v)));
 }
 
-// (value, index) minimum over a wave; the lower index wins among equal values.
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+    unsigned o;
+    o = (unsigned)dpp_i32<kDppXor1>((int)v); v = o > v ? o : v;
+    o = (unsigned)dpp_i32<kDppXor2>((int)v); v = o > v ? o : v;
+    o = (unsigned)dpp_i32<kDppHalfMirror>((int)v); v = o > v ? o : v;
+    o = (unsigned)dpp_i32<kDppMirror>((int)v); v = o > v ? o : v;
+    const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0), r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+    const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32), r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+    const unsigned a = r0 > r1 ? r0 : r1, b = r2 > r3 ? r2 : r3;
+    return a > b ? a : b;
+}
+
+// (value, index) minimum over a wave; the lower index wins among equal values.  Every lane returns the result.
+template <int CTRL>
+__device__ __forceinline__ void argmin_step(double& e, int& j)
+{
+    const double oe = dpp_f64<CTRL>(e);
+    const int oj = dpp_i32<CTRL>(j);
+    if (oe < e || (oe == e && oj < j)) { e = oe; j = oj; }
+}
+
 __device__ __forceinline__ void wave_argmin(double& e, int& j)
 {
+    argmin_step<kDppXor1>(e, j);
+    argmin_step<kDppXor2>(e, j);
+    argmin_step<kDppHalfMirror>(e, j);
+    argmin_step<kDppMirror>(e, j);
+    double be = readlane_f64(e, 0);
+    int bj = __builtin_amdgcn_readlane(j, 0);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const double oe = __shfl_xor(e, off, 64);
-        const int oj = __shfl_xor(j, off, 64);
-        if (oe < e || (oe == e && oj < j)) { e = oe; j = oj; }
+    for (int r = 16; r < 64; r += 16) {
+        const double oe = readlane_f64(e, r);
+        const int oj = __builtin_amdgcn_readlane(j, r);
+        if (oe < be || (oe == be && oj < bj)) { be = oe; bj = oj; }
     }
+    e = be; j = bj;
 }
 
 // Binary-counter form of the pairwise sum: after chunk number ci has been pushed,

@@ -81,7 +81,8 @@ inline void trace_mark(hipStream_t s, int stage)
 // number of kernels or blocks (1024 only for kernels of more than 32768 elements, of which a tensor has fewer
 // than 65536), so launches are cut at this many workgroups.
 constexpr long long kMaxLaunchWG = 1LL << 22;
-constexpr long long kFusedMaxKernels = 1024;      // calls of at most this many kernels take the single-launch search
+constexpr long long kFusedMaxKernels = 1024;      // calls of at most this many kernels and elements take the single-launch
+constexpr long long kFusedMaxElements = 1 << 20;  // search: beyond, the separate refinement kernel packs its lanes better
 static_assert(kMaxLaunchWG == MMSE_MAX_KERNELS, "one workgroup per kernel");
 
 int check_params(const mmse_params_t* p)
@@ -287,9 +288,9 @@ int run_weight_tensors(Item* items, int count, const mmse_params_t* p, bool do_s
     // A call of few kernels is a chain of dependent launches that mostly wait for each other; then one launch does
     // the whole search (k_sweep_kernelwise, FUSED): every kernel must fit one LDS tile and have at most as many
     // chunks as a sweep workgroup has lanes.
-    long long sumK = 0;
-    for (int i = 0; i < count; ++i) sumK += items[i].a.K;
-    sh.fused = (do_search && sumK <= kFusedMaxKernels && max_n <= kTile &&
+    long long sumK = 0, sumKn = 0;
+    for (int i = 0; i < count; ++i) { sumK += items[i].a.K; sumKn += (long long)items[i].a.K * items[i].a.n; }
+    sh.fused = (do_search && sumK <= kFusedMaxKernels && sumKn <= kFusedMaxElements && max_n <= kTile &&
                 (max_n + kChunk - 1) / kChunk <= 64 * sh.waves) ? 1 : 0;
     // tiny kernels take the one-wave-per-kernel path inside the sweep launch, when that variant is compiled for this
     // grid and no kernel of the call needs more than the short binary counter
