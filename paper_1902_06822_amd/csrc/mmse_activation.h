@@ -511,8 +511,8 @@ __global__ void __launch_bounds__(kPackThreads) k_act_pack(const ActBatch B, con
         const int cnt = (N - e0) < kPackPerThread ? (int)(N - e0) : kPackPerThread;
         float v[kPackPerThread];
         if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
-            const float4 p0 = load_stream_f4(x + e0);
-            const float4 p1 = load_stream_f4(x + e0 + 4);
+            const float4 p0 = reinterpret_cast<const float4*>(x + e0)[0];     // plain loads and stores: the streaming hints
+            const float4 p1 = reinterpret_cast<const float4*>(x + e0)[1];     // gain nothing on a read + write pass
             v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w;
             v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
         } else {
@@ -529,7 +529,7 @@ __global__ void __launch_bounds__(kPackThreads) k_act_pack(const ActBatch B, con
         }
         uint8_t* dst = packed + (e0 >> 1);
         if (cnt == kPackPerThread && (reinterpret_cast<uintptr_t>(packed) & 3u) == 0) {
-            store_stream_u32(reinterpret_cast<unsigned*>(dst), word);
+            *reinterpret_cast<unsigned*>(dst) = word;
         } else {
             const int nbytes = (cnt + 1) >> 1;
             for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(word >> (8 * b));

@@ -165,16 +165,16 @@ __device__ __forceinline__ double readlane_f64(double v, int l)
     return __hiloint2double(hi, lo);
 }
 
-// 16-byte load / 4-byte store for data that is streamed through once (a whole activation tensor per pass):
-// the non-temporal hint keeps such lines from displacing what the caches hold for others, which on MI355X is
-// worth about a tenth of the read bandwidth of a pass over a tensor much larger than the caches.
+// 16-byte load for data that is streamed through once (a whole activation tensor per read-only pass): the
+// non-temporal hint keeps such lines from displacing what the caches hold for others, which on MI355X is worth
+// about a tenth of the read bandwidth of a pass over a tensor much larger than the caches (6.9 against 6.2 TB/s);
+// a pass that also writes (the code passes) gains nothing from it and loses when the tensor fits the caches.
 typedef float mmse_vf4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 load_stream_f4(const float* p)
 {
     const mmse_vf4 v = __builtin_nontemporal_load(reinterpret_cast<const mmse_vf4*>(p));
     return make_float4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ void store_stream_u32(unsigned* p, unsigned v) { __builtin_nontemporal_store(v, p); }
 
 __device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
