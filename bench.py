@@ -484,8 +484,12 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
     tw = traced(plan_w)
     sw_l = tw.get(1, (0, 0.0))[0] + tw.get(2, (0, 0.0))[0] + tw.get(6, (0, 0.0))[0]
     sw_ms = tw.get(1, (0, 0.0))[1] + tw.get(2, (0, 0.0))[1] + tw.get(6, (0, 0.0))[1]
-    e_w = _alu_entry("k_sweep_kernelwise (+ k_sweep_small): abs-max, grid sweep, argmin of all weight tensors",
-                     w_elems * G, sw_l, sw_ms, traffic.get(("k_sweep_kernelwise", wl), (None,))[0])
+    def tr_of(kernel):
+        t = traffic.get((kernel, wl))
+        return (t[0] + t[1]) if t else None
+
+    e_w = _alu_entry("k_sweep_kernelwise: abs-max, grid sweep, argmin of all weight tensors",
+                     w_elems * G, sw_l, sw_ms, tr_of("k_sweep_kernelwise"))
     kernels.append(e_w)
     rf_l = tw.get(3, (0, 0.0))[0] + tw.get(4, (0, 0.0))[0]
     rf_ms = tw.get(3, (0, 0.0))[1] + tw.get(4, (0, 0.0))[1]
@@ -499,7 +503,7 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
         l2 = tr2.get(1, (0, 0.0))[0] + tr2.get(2, (0, 0.0))[0]
         m2 = tr2.get(1, (0, 0.0))[1] + tr2.get(2, (0, 0.0))[1]
         kernels.append(_alu_entry("k_sweep_kernelwise on the residual of the first tensor (second tensor, all layers)",
-                                  w_elems * G, l2, m2))
+                                  w_elems * G, l2, m2, tr_of("k_sweep_kernelwise")))
         second_alone_ms = sum(t for _, t in tr2.values())
     acts_alone_ms = 0.0
     hbm = []
@@ -507,25 +511,19 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
         ta = traced(plan_a)
         acts_alone_ms = sum(t for _, t in ta.values())
         l, m = ta[12]
-        kernels.append(_alu_entry("k_act_sweep: grid sweep of all activation tensors", a_elems * G, l, m,
-                                  traffic.get(("k_act_sweep", wl), (None,))[0]))
+        kernels.append(_alu_entry("k_act_sweep: grid sweep of all activation tensors", a_elems * G, l, m, tr_of("k_act_sweep")))
         l, m = ta[11]
-        tf = traffic.get(("k_act_absmax", wl))
-        hbm.append(_hbm_entry("k_act_absmax: max |x| of every activation tensor", 4.0 * a_elems, l, m,
-                              tf[0] + tf[1] if tf else None))
+        hbm.append(_hbm_entry("k_act_absmax: max |x| of every activation tensor", 4.0 * a_elems, l, m, tr_of("k_act_absmax")))
         if 15 in ta:
             l, m = ta[15]
-            tf = traffic.get(("k_act_probe", wl))
             hbm.append(_hbm_entry("k_act_probe: one refinement pass over every activation tensor (up to 8 scales per element)",
-                                  4.0 * a_elems * l, l, m, tf[0] + tf[1] if tf else None))
+                                  4.0 * a_elems * l, l, m, tr_of("k_act_probe")))
             if iters == 20:      # 2+2+4 scales per element in the first pass, 1+2+4 in each of the others
                 ev = (8 + 7 * (l - 1)) * a_elems
                 hbm[-1]["scales_evaluated_per_element"] = 8 + 7 * (round(l) - 1)
                 hbm[-1]["alu_frac"] = round(ev * OPS_PER_EVAL / (m * 1e-3) / LANE_OPS_PER_S, 4)
         l, m = ta[18]
-        tf = traffic.get(("k_act_pack", wl))
-        hbm.append(_hbm_entry("k_act_pack: INT4 codes of every activation tensor", 4.5 * a_elems, l, m,
-                              tf[0] + tf[1] if tf else None))
+        hbm.append(_hbm_entry("k_act_pack: INT4 codes of every activation tensor", 4.5 * a_elems, l, m, tr_of("k_act_pack")))
     trace.close()
     dominant = max(kernels, key=lambda e: e["avg_launch_ms"] * e["launches_per_step"])
     roofline = dict(dominant)
@@ -533,6 +531,9 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
                         "vector when every instruction is an FMA); an evaluation is 5 instructions / 7 flops, so the peak in "
                         "flops of this mix is 110.1 TFLOP/s; frac = lane-ops/s over 78.6e12.  Each kernel timed by itself "
                         "between HIP events on its launch stream, after the timed steps.")
+    roofline["traffic_note"] = ("fetched + written bytes per launch at the memory side of L2, from rocprofv3 --pmc FETCH_SIZE / "
+                                "WRITE_SIZE runs of this command (profiles/hbm_traffic.txt); algorithmic bytes: 4 per element read "
+                                "once, plus 8 * grid_points per 4096 elements written by k_act_sweep")
     roofline["all_alu_kernels"] = kernels
     roofline["hbm"] = hbm
     roofline["hbm_note"] = (f"activation set {4 * a_elems / 1e6:.0f} MB, read once per pass; the chip's last-level cache is 256 MB"
@@ -767,6 +768,7 @@ def main() -> int:
         # HBM-side bytes per step from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/hbm_traffic.txt)
         "traffic": (lambda t: (t[0] + t[1]) if t else None)(_traffic_table().get(("k_sweep_kernelwise", f"cfg{args.config}"))
                                                             if args.grid_points == 0 else None),
+        "traffic_note": "fetched + written bytes per launch at the memory side of L2 (profiles/hbm_traffic.txt)",
         "algorithmic_bytes": 4 * elements,
         "avg_launch_ms": round(sweep_ms / nlaunch, 5),
         "launches_per_step": nlaunch,
