@@ -278,8 +278,9 @@ int mmse_grid_sse_activation(const float *x_dev, int64_t N, const mmse_params_t 
 typedef struct mmse_trace mmse_trace_t;
 enum {
     MMSE_STAGE_START = 0,
-    MMSE_STAGE_W_SWEEP = 1,         /* k_sweep_kernelwise: abs-max, grid sweep, argmin (Section 3.4)      */
-    MMSE_STAGE_W_SWEEP_SMALL = 2,   /* k_sweep_small: the same for kernels of <= 64 elements             */
+    MMSE_STAGE_W_SWEEP = 1,         /* k_sweep_kernelwise: abs-max, grid sweep, argmin (Section 3.4);
+                                       kernels of <= 64 elements one wave each in the same launch      */
+    /* 2: not used */
     MMSE_STAGE_W_REFINE = 3,        /* k_refine_kernelwise<64>: refinement (+ codes when n is even)      */
     MMSE_STAGE_W_REFINE_SMALL = 4,  /* k_refine_kernelwise<16>                                           */
     MMSE_STAGE_W_PACK = 5,          /* k_pack_int4                                                       */

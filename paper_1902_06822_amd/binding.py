@@ -33,7 +33,7 @@ EXPORTS = (
 VOID_EXPORTS = ("mmse_trace_destroy",)
 
 # MMSE_STAGE_* of include/mmse.h: the kernel a traced launch ran
-STAGE_NAMES = {1: "k_sweep_kernelwise", 2: "k_sweep_small", 3: "k_refine_kernelwise<64>", 4: "k_refine_kernelwise<16>",
+STAGE_NAMES = {1: "k_sweep_kernelwise", 3: "k_refine_kernelwise<64>", 4: "k_refine_kernelwise<16>",
                5: "k_pack_int4", 6: "k_sweep_kernelwise (fused search)", 10: "k_act_init", 11: "k_act_absmax", 12: "k_act_sweep", 13: "k_act_reduce64 (grid sums)",
                14: "k_act_argmin", 15: "k_act_probe", 16: "k_act_reduce64 (probe sums)", 17: "k_act_finish",
                18: "k_act_pack"}

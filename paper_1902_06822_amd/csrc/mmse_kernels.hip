@@ -18,7 +18,7 @@
 //
 // Files: this translation unit holds the host side (validation, launch plans) and the C ABI; the kernels are in
 //   mmse_common.h      constants, element arithmetic, summation tree, the LDS-fed sweep core
-//   mmse_weights.h     k_sweep_kernelwise, k_sweep_small, k_refine_kernelwise, k_pack_int4
+//   mmse_weights.h     k_sweep_kernelwise (with sweep_small_wave and the fused search), k_refine_kernelwise, k_pack_int4
 //   mmse_dual.h        Algorithm 1 iterated (bookkeeping kernels) and the dual line search of Eq. 12
 //   mmse_compare.h     the alternating optimiser of the paper's comparison
 //   mmse_activation.h  k_act_*: per-layer activation path, batched over tensors, with its variants
