@@ -97,6 +97,32 @@ def run_activation_cases(B, seed, count):
                                           err_msg=tag)
 
 
+def run_multi_tensor_case(B, seed):
+    """Several random tensors in one batched call: tiny, short, ordinary and streaming kernels share the launches."""
+    import torch
+    rng = np.random.default_rng(seed)
+    G = int(rng.choice([64, 128, 256, 500, 512, 1024]))
+    iters = int(rng.choice([0, 3, 20]))
+    q = RANGES[int(rng.integers(len(RANGES)))]
+    ws = []
+    for _ in range(int(rng.integers(2, 9))):
+        n = int(rng.choice([rng.integers(1, 17), rng.integers(1, 70), rng.integers(60, 700), rng.integers(600, 5000),
+                            rng.integers(8000, 12000)]))
+        K = int(max(1, min(rng.integers(1, 3000), 400000 // n)))
+        w = synth.small_weights(K, n, int(rng.integers(1 << 30)), KINDS[int(rng.integers(len(KINDS)))])
+        ws.append(np.abs(w) if q[0] == 0 else w)
+    tag = f"multi seed={seed} G={G} iters={iters} q={q} shapes={[w.shape for w in ws]}"
+    say(tag)
+    res = B.mmse_scale_search_batched([dev(w) for w in ws], B.params(*q, G, iters), want_packed=True)
+    torch.cuda.synchronize()
+    for w, r in zip(ws, res):
+        s, j, e = oracle.can_search_kernelwise(w, *q, G, iters)
+        np.testing.assert_array_equal(r.idx.cpu().numpy(), j, err_msg=tag)
+        np.testing.assert_array_equal(r.scale.cpu().numpy(), s, err_msg=tag)
+        np.testing.assert_array_equal(r.sse.cpu().numpy(), e, err_msg=tag)
+        np.testing.assert_array_equal(r.packed.cpu().numpy(), oracle.can_quantize_pack_int4(w, s, *q), err_msg=tag)
+
+
 @pytest.mark.parametrize("seed", [11, 12, 13])
 def test_random_weight_cases(B, seed):
     run_weight_cases(B, seed, 14)
@@ -105,3 +131,8 @@ def test_random_weight_cases(B, seed):
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_activation_cases(B, seed):
     run_activation_cases(B, seed, 10)
+
+
+@pytest.mark.parametrize("seed", [31, 32, 33, 34])
+def test_random_multi_tensor_calls(B, seed):
+    run_multi_tensor_case(B, seed)
