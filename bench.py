@@ -466,6 +466,18 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
                       "streams": "one" if (args.serial or plan_a is None) else "weights on the main stream, activations on a side stream",
                       "evals_per_step": evals}}
 
+    # ---- the scales back on the host (not part of a step: the results stay on the device)
+    scales = [r.scale for r in plan_w.results] + ([r.scale for r in res_all.results] if res_all is not None else []) \
+        + [r.scale for r in act_out]
+    d2h = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        host_scales = torch.cat(scales).cpu()
+        d2h.append((time.perf_counter() - t1) * 1e3)
+    out["d2h_scales_ms"] = {"median_ms": sorted(d2h)[1], "floats": int(host_scales.numel()),
+                            "note": "all scales of the network gathered on the device and copied to the host; outside the timed step"}
+
     # ---- every kernel by itself: the weight path, the second tensor and the activation path one after the other on
     # one stream, HIP events on that stream around every launch (mmse_trace_*)
     reps = max(3, min(10, steps))
@@ -628,7 +640,8 @@ def bench_whole(args, cfg, torch, B) -> int:
         "metric": METRIC, "value": res["value"], "unit": "evals/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": res["config"], "alone_ms": res["alone_ms"], "roofline": res["roofline"],
+        "config": res["config"], "alone_ms": res["alone_ms"], "d2h_scales_ms": res["d2h_scales_ms"],
+        "roofline": res["roofline"],
         "cpu_baseline": res["cpu_baseline"], "matches_oracle": res["matches_oracle"],
         "other_configs": others}))
     return 0
