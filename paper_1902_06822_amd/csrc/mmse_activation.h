@@ -205,6 +205,7 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
 {
     __shared__ float4 slice4[kBlockElems / 4];
     __shared__ double xbuf[kMaxSplitCands];
+    __shared__ unsigned s_bounds[kBlockChunks];             // largest bound_key of every chunk of the block
     float* slice = reinterpret_cast<float*>(slice4);
     const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
     const int wps = split ? (nthreads >> 7) : (nthreads >> 6);          // waves per set
@@ -220,7 +221,12 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
     const int npad = (len + kChunk - 1) & ~(kChunk - 1);
     const ActPreV V = act_pre_load(pre);
-    for (int i = tid; i < npad; i += nthreads) slice[i] = i < len ? act_pre(V, x[base + i]) : 0.0f;
+    for (int i = tid; i < npad; i += nthreads) {              // a wave stages one whole chunk per turn
+        const float v = i < len ? act_pre(V, x[base + i]) : 0.0f;
+        slice[i] = v;
+        const unsigned kb = wave_max_u32(bound_key(v, lo));
+        if (lane == 0) s_bounds[i >> 6] = kb;
+    }
     __syncthreads();
 
     const float qmaxf = (float)qmax, Gf = (float)G;
@@ -244,7 +250,11 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     const int e0 = set * half;
     int nel = ((len + 7) & ~7) - e0;
     nel = nel < 0 ? 0 : (nel < half ? nel : half);
-    if (nel > 0) sweep_slice<C, kLevelsBlk>(slice + e0, nel, ci, alpha, inv, lo, hi, st);
+    if (nel > 0) {
+        const float inv_min = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv[0])));   // lane 0: the wave's smallest scale
+        const unsigned long long in0 = chunks_inside_range(s_bounds + e0 / kChunk, nel / kChunk, inv_min, lo, hi, lane);
+        sweep_slice<C, kLevelsBlk>(slice + e0, nel, ci, alpha, inv, lo, hi, st, in0);
+    }
     double E[C];
     tree_fold<C, kLevelsBlk>(st, ci, E);                    // 0.0 when this set has no chunk
     if (split) {

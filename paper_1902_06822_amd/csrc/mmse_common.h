@@ -279,7 +279,9 @@ __device__ __forceinline__ void tree_fold(const double (&st)[C][L], unsigned m, 
 // Scheduling fences keep the compiler from re-serialising the stages; LDS/VMEM/SALU
 // instructions may still move across them.
 #define MMSE_STAGE_FENCE() __builtin_amdgcn_sched_barrier(0x94)
-template <int NE, int C>
+// CLAMP = false leaves the saturation out: for callers that have shown it to be the identity for every one of
+// these evaluations (sweep_slice), where it then is four instructions per evaluation instead of five.
+template <int NE, int C, bool CLAMP = true>
 __device__ __forceinline__ void eval_stage(const float (&x)[NE], const float (&alpha)[C], const float (&inv)[C],
                                            float lo, float hi, float (&s)[C])
 {
@@ -294,11 +296,13 @@ __device__ __forceinline__ void eval_stage(const float (&x)[NE], const float (&a
 #pragma unroll
         for (int u = 0; u < C; ++u) t[i][u] = __builtin_rintf(t[i][u]);
     MMSE_STAGE_FENCE();
+    if constexpr (CLAMP) {
 #pragma unroll
-    for (int i = 0; i < NE; ++i)
+        for (int i = 0; i < NE; ++i)
 #pragma unroll
-        for (int u = 0; u < C; ++u) t[i][u] = __builtin_amdgcn_fmed3f(t[i][u], lo, hi);
-    MMSE_STAGE_FENCE();
+            for (int u = 0; u < C; ++u) t[i][u] = __builtin_amdgcn_fmed3f(t[i][u], lo, hi);
+        MMSE_STAGE_FENCE();
+    }
 #pragma unroll
     for (int i = 0; i < NE; ++i)
 #pragma unroll
@@ -312,43 +316,89 @@ __device__ __forceinline__ void eval_stage(const float (&x)[NE], const float (&a
     }
 }
 
+// What a chunk's elements contribute to its entry of the bounds array (the entry is the largest key of the chunk):
+// |x| as a bit pattern, or +inf for a negative element of an unsigned range, which no scale brings into the range.
+__device__ __forceinline__ unsigned bound_key(float v, float lo)
+{
+    return (lo == 0.0f && v < 0.0f) ? 0x7f800000u : abs_bits(v);
+}
+
+// Which of up to 64 chunks a wave may evaluate without the saturation (bit c: chunk c): those whose largest
+// magnitude (bounds[c], a bound_key, in LDS; zero counts as an element) rounds to a code inside the range at
+// inv_min = 1 / the smallest scale any lane of the wave sweeps.  x*inv, the rounding and the reciprocal are
+// monotonic, so no code of such a chunk at any scale of the wave has a larger magnitude than that one; the
+// saturation would return its argument, and the bits are the same without it.  (Sufficient, not necessary: the
+// magnitude is tested against the smaller of the two ends of a signed range.)  One chunk per lane, then a vote.
+__device__ __forceinline__ unsigned long long chunks_inside_range(const unsigned* bounds, int nchunks, float inv_min,
+                                                                   float lo, float hi, int lane)
+{
+    const float limit = (lo == 0.0f || hi < -lo) ? hi : -lo;
+    bool in = false;
+    if (lane < nchunks) in = __builtin_rintf(__uint_as_float(bounds[lane]) * inv_min) <= limit;
+    return __ballot(in);
+}
+
+// The elements of one whole chunk at s4 against the C candidates of this lane, fetched from LDS one group ahead of
+// their use (same address in every lane: broadcast).
+template <int C, bool CLAMP>
+__device__ __forceinline__ void sweep_chunk(const float4* s4, const float (&alpha)[C], const float (&inv)[C],
+                                            float lo, float hi, float (&s)[C])
+{
+    constexpr int NE = (C >= 2) ? 4 : 8;            // elements per stage group (8 temporaries either way with C <= 2)
+    float4 nxt[NE / 4];
+#pragma unroll
+    for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[q];
+#pragma unroll
+    for (int e = 0; e < kChunk / NE; ++e) {
+        float x[NE];
+#pragma unroll
+        for (int q = 0; q < NE / 4; ++q) {
+            x[4 * q + 0] = nxt[q].x; x[4 * q + 1] = nxt[q].y; x[4 * q + 2] = nxt[q].z; x[4 * q + 3] = nxt[q].w;
+        }
+        if (e + 1 < kChunk / NE) {
+#pragma unroll
+            for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[(e + 1) * (NE / 4) + q];
+        }
+        __builtin_amdgcn_sched_barrier(0);       // the prefetch is issued before this group's arithmetic
+        eval_stage<NE, C, CLAMP>(x, alpha, inv, lo, hi, s);
+    }
+}
+
 // Sweep the `nelem` elements (a multiple of 8; zero padded) that sit in LDS at `slice` for the C
 // candidates of this lane: whole 64-element chunks, then a last shorter chunk that only walks the
 // 8-element groups it has (padding zeros would be exact no-ops, so skipping them changes nothing).
 // CS: floats between the starts of consecutive chunks in LDS (kChunk, or more when the chunks are padded apart
 // so that lanes reading different chunks at the same time hit different banks).
+// inside0 / inside1: bit c set (chunks 0-63 / 64-127 of this slice): the caller has shown with chunks_inside_range
+// that the saturation is the identity for chunk c at every scale of this wave; such a chunk takes four instructions
+// per evaluation instead of five.
 template <int C, int L, int CS = kChunk>
 __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsigned& ci,
                                             const float (&alpha)[C], const float (&inv)[C],
-                                            float lo, float hi, double (&st)[C][L])
+                                            float lo, float hi, double (&st)[C][L],
+                                            unsigned long long inside0 = 0, unsigned long long inside1 = 0)
 {
     const float4* s4 = reinterpret_cast<const float4*>(slice);
-    constexpr int NE = (C >= 2) ? 4 : 8;            // elements per stage group (8 temporaries either way with C <= 2)
+    constexpr int NE = (C >= 2) ? 4 : 8;
     const int nfull = nelem / kChunk;
     const int tail = nelem - nfull * kChunk;        // 0, 8, ..., 56 elements of a last partial chunk
     const int ntotal = nfull + (tail > 0 ? 1 : 0);
+#pragma unroll 1
     for (int c = 0; c < ntotal; ++c, ++ci) {
         float s[C];
 #pragma unroll
         for (int u = 0; u < C; ++u) s[u] = 0.0f;
         if (c < nfull) {
-            // elements come from LDS one group ahead of their use (same address in every lane: broadcast)
-            float4 nxt[NE / 4];
-#pragma unroll
-            for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (CS / 4) + q];
-#pragma unroll
-            for (int e = 0; e < kChunk / NE; ++e) {
-                float x[NE];
-#pragma unroll
-                for (int q = 0; q < NE / 4; ++q) {
-                    x[4 * q + 0] = nxt[q].x; x[4 * q + 1] = nxt[q].y; x[4 * q + 2] = nxt[q].z; x[4 * q + 3] = nxt[q].w;
-                }
-                if (e + 1 < kChunk / NE) {
-#pragma unroll
-                    for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[c * (CS / 4) + (e + 1) * (NE / 4) + q];
-                }
-                __builtin_amdgcn_sched_barrier(0);       // the prefetch is issued before this group's arithmetic
-                eval_stage<NE, C>(x, alpha, inv, lo, hi, s);
+            const bool inside = (((c < 64 ? inside0 : inside1) >> (c & 63)) & 1ull) != 0;       // scalar: c is uniform
+            // (the empty statements hide from the compiler that both branches start at the same address: it would
+            // merge their first fetches ahead of the branch, at the price of registers the sweep needs for its waves)
+            int cc = c;
+            if (inside) {
+                asm volatile("" : "+s"(cc));
+                sweep_chunk<C, false>(s4 + cc * (CS / 4), alpha, inv, lo, hi, s);
+            } else {
+                asm volatile("" : "+s"(cc));
+                sweep_chunk<C, true>(s4 + cc * (CS / 4), alpha, inv, lo, hi, s);
             }
         } else {
             for (int e = 0; e < tail / NE; ++e) {

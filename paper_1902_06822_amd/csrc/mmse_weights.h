@@ -28,6 +28,7 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
     __shared__ unsigned s_amax[16];
     __shared__ double s_bestE[16];
     __shared__ int s_bestJ[16];
+    __shared__ unsigned s_bounds[kTile / kChunk];         // largest bound_key of every staged chunk
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x, nwaves = nthreads >> 6;
@@ -55,11 +56,15 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
     // ---- pass 1: abs-max (and, when the kernel fits one tile, the LDS staging)
     unsigned amax = 0;
     if (single) {
-        for (int i = tid; i < npad; i += nthreads) {
+        for (int i = tid; i < npad; i += nthreads) {       // a wave stages one whole chunk per turn
             const float v = i < n ? xform_apply(X, src[i], flat0 + i, lo, hi) : 0.0f;
             slice[FUSED ? i + 4 * (i >> 6) : i] = v;
             const unsigned b = abs_bits(v);
             amax = b > amax ? b : amax;
+            if constexpr (!FUSED) {
+                const unsigned kb = wave_max_u32(bound_key(v, lo));
+                if (lane == 0) s_bounds[i >> 6] = kb;
+            }
         }
     } else {
         for (int i = tid; i < n; i += nthreads) {
@@ -116,18 +121,31 @@ __global__ void __launch_bounds__(512) k_sweep_kernelwise(const Batch B)
         for (int l = 0; l < LV; ++l) st[u][l] = 0.0;
     unsigned ci = 0;
     if (single) {
-        sweep_slice<C, LV, CSTRIDE>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st);
+        unsigned long long in0 = 0, in1 = 0;
+        if constexpr (!FUSED) {
+            const float inv_min = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv[0])));   // lane 0: the wave's smallest scale
+            const int nfull = n / kChunk;
+            in0 = chunks_inside_range(s_bounds, nfull < 64 ? nfull : 64, inv_min, lo, hi, lane);
+            if (nfull > 64) in1 = chunks_inside_range(s_bounds + 64, nfull - 64, inv_min, lo, hi, lane);
+        }
+        sweep_slice<C, LV, CSTRIDE>(slice, (n + 7) & ~7, ci, alpha, inv, lo, hi, st, in0, in1);
     } else {
         for (int t0 = 0; t0 < npad; t0 += kTileStream) {
             const int tlen = (npad - t0) < kTileStream ? (npad - t0) : kTileStream;
             __syncthreads();
             for (int i = tid; i < tlen; i += nthreads) {
                 const int gi = t0 + i;
-                slice[i] = gi < n ? xform_apply(X, src[gi], flat0 + gi, lo, hi) : 0.0f;
+                const float v = gi < n ? xform_apply(X, src[gi], flat0 + gi, lo, hi) : 0.0f;
+                slice[i] = v;
+                const unsigned kb = wave_max_u32(bound_key(v, lo));
+                if (lane == 0) s_bounds[i >> 6] = kb;
             }
             __syncthreads();
             const int valid = ((n + 7) & ~7) - t0;       // the last tile may end in a partial chunk
-            sweep_slice<C, LV>(slice, valid < tlen ? valid : tlen, ci, alpha, inv, lo, hi, st);
+            const int nvalid = valid < tlen ? valid : tlen;
+            const float inv_min = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv[0])));
+            const unsigned long long in0 = chunks_inside_range(s_bounds, nvalid / kChunk, inv_min, lo, hi, lane);
+            sweep_slice<C, LV>(slice, nvalid, ci, alpha, inv, lo, hi, st, in0);
         }
     }
     double E[C];
