@@ -487,6 +487,8 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
 
     def traced(plan):
         rows = []
+        for _ in range(2):                  # untimed: the host work since the timed steps let the clock drop
+            plan.run()
         for _ in range(reps):
             plan.run_traced(trace)
             rows.append(trace.read())
@@ -541,8 +543,11 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
     roofline = dict(dominant)
     roofline["note"] = ("alu peak = 256 CUs x 4 SIMDs x 32 lanes/clk x 2.4 GHz = 78.6e12 VALU lane-ops/s (= 157.3 TFLOP/s fp32 "
                         "vector when every instruction is an FMA); an evaluation is 5 instructions / 7 flops, so the peak in "
-                        "flops of this mix is 110.1 TFLOP/s; frac = lane-ops/s over 78.6e12.  Each kernel timed by itself "
-                        "between HIP events on its launch stream, after the timed steps.")
+                        "flops of this mix is 110.1 TFLOP/s; frac = algorithmic lane-ops/s (5 per evaluation) over 78.6e12.  "
+                        "The sweeps leave the saturation (v_med3) out for chunks whose largest magnitude stays inside the "
+                        "integer range at the smallest scale of a wave, where it is the identity: they issue 8-13 % fewer "
+                        "instructions than 5 per evaluation (counts in profiles/), which frac does not discount.  Each kernel "
+                        "timed by itself between HIP events on its launch stream, after the timed steps.")
     roofline["traffic_note"] = ("fetched + written bytes per launch at the memory side of L2, from rocprofv3 --pmc FETCH_SIZE / "
                                 "WRITE_SIZE runs of this command (profiles/hbm_traffic.txt); algorithmic bytes: 4 per element read "
                                 "once, plus 8 * grid_points per 4096 elements written by k_act_sweep")
