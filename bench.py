@@ -118,11 +118,18 @@ def bench_activation(args, cfg, torch, B) -> int:
     torch.cuda.synchronize()
     sweep_ms = ev0.elapsed_time(ev1) / args.steps
     peak_tflops = LANE_OPS_PER_S * FLOPS_PER_EVAL / OPS_PER_EVAL / 1e12
-    ach = N * G * FLOPS_PER_EVAL / (sweep_ms * 1e-3) / 1e12
+    # the sweep drops the elements that are zero after the variant's pre-operation while staging (they add nothing to
+    # a sum at any scale): the roofline counts the others where the bench can count them (the plain variant)
+    counted = int(torch.count_nonzero(xd).item()) if variant == "plain" else N
+    ach = counted * G * FLOPS_PER_EVAL / (sweep_ms * 1e-3) / 1e12
     roofline = {"bound": "alu", "kernel": "k_act_sweep (+abs-max, block reduction, argmin in the timed region)",
                 "achieved": round(ach, 3), "peak": round(peak_tflops, 3), "unit": "TFLOP/s",
                 "frac": round(ach / peak_tflops, 4), "traffic": None, "avg_launch_ms": round(sweep_ms, 5),
-                "evals_per_s": N * G / (sweep_ms * 1e-3)}
+                "evals_per_s": N * G / (sweep_ms * 1e-3),
+                "counted": ("evaluations of non-zero elements" if variant == "plain" else
+                            "all elements (dense equivalent: can exceed 1 where the pre-operation leaves zeros)"),
+                "nonzero_fraction": round(counted / max(N, 1), 4),
+                "dense_equivalent_frac": round(N * G * FLOPS_PER_EVAL / (sweep_ms * 1e-3) / 1e12 / peak_tflops, 4)}
     cpu_baseline, parity = None, None
     if not args.no_cpu_baseline:
         import oracle
@@ -464,7 +471,9 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
                       "activation_tensors": len(dev_x), "activation_elements": a_elems, "grid_points": G,
                       "refine_iters": iters, "ranges": "weights signed INT4 (-8..7), activations unsigned INT4 (0..15)",
                       "streams": "one" if (args.serial or plan_a is None) else "weights on the main stream, activations on a side stream",
-                      "evals_per_step": evals}}
+                      "evals_per_step": evals,
+                      "evals_counted": "every element x candidate of the definition; the activation sweep does not issue "
+                                       "the evaluations of zero elements (their term is zero at every scale)"}}
 
     # ---- the scales back on the host (not part of a step: the results stay on the device)
     scales = [r.scale for r in plan_w.results] + ([r.scale for r in res_all.results] if res_all is not None else []) \
@@ -525,7 +534,15 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
         ta = traced(plan_a)
         acts_alone_ms = sum(t for _, t in ta.values())
         l, m = ta[12]
-        kernels.append(_alu_entry("k_act_sweep: grid sweep of all activation tensors", a_elems * G, l, m, tr_of("k_act_sweep")))
+        # the sweep drops zero elements while staging (a zero adds nothing to a chunk's sum at any scale), so its
+        # roofline counts the evaluations of the non-zero elements; the dense count is given beside it
+        a_nonzero = sum(int(torch.count_nonzero(x).item()) for x in dev_x)
+        e_a = _alu_entry("k_act_sweep: grid sweep of all activation tensors", a_nonzero * G, l, m, tr_of("k_act_sweep"))
+        e_a["counted"] = "evaluations of non-zero elements (zero elements are dropped while staging)"
+        e_a["nonzero_fraction"] = round(a_nonzero / max(a_elems, 1), 4)
+        e_a["dense_evals_per_launch"] = a_elems * G / max(l, 1e-9)
+        e_a["dense_equivalent_frac"] = round(a_elems * G * OPS_PER_EVAL / (m * 1e-3) / LANE_OPS_PER_S, 4)
+        kernels.append(e_a)
         l, m = ta[11]
         hbm.append(_hbm_entry("k_act_absmax: max |x| of every activation tensor", 4.0 * a_elems, l, m, tr_of("k_act_absmax")))
         if 15 in ta:
@@ -546,8 +563,10 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
                         "flops of this mix is 110.1 TFLOP/s; frac = algorithmic lane-ops/s (5 per evaluation) over 78.6e12.  "
                         "The sweeps leave the saturation (v_med3) out for chunks whose largest magnitude stays inside the "
                         "integer range at the smallest scale of a wave, where it is the identity: they issue 8-13 % fewer "
-                        "instructions than 5 per evaluation (counts in profiles/), which frac does not discount.  Each kernel "
-                        "timed by itself between HIP events on its launch stream, after the timed steps.")
+                        "instructions than 5 per evaluation (counts in profiles/), which frac does not discount.  The activation "
+                        "sweep also drops zero elements while staging (they add nothing to a sum at any scale): its frac "
+                        "counts the evaluations of non-zero elements only, and dense_equivalent_frac all of them.  Each "
+                        "kernel timed by itself between HIP events on its launch stream, after the timed steps.")
     roofline["traffic_note"] = ("fetched + written bytes per launch at the memory side of L2, from rocprofv3 --pmc FETCH_SIZE / "
                                 "WRITE_SIZE runs of this command (profiles/hbm_traffic.txt); algorithmic bytes: 4 per element read "
                                 "once, plus 8 * grid_points per 4096 elements written by k_act_sweep")

@@ -206,6 +206,7 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     __shared__ float4 slice4[kBlockElems / 4];
     __shared__ double xbuf[kMaxSplitCands];
     __shared__ unsigned s_bounds[kBlockChunks];             // largest bound_key of every chunk of the block
+    __shared__ int s_len[kBlockChunks];                     // its length once compacted to its non-zero elements
     float* slice = reinterpret_cast<float*>(slice4);
     const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
     const int wps = split ? (nthreads >> 7) : (nthreads >> 6);          // waves per set
@@ -221,11 +222,20 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
     const int npad = (len + kChunk - 1) & ~(kChunk - 1);
     const ActPreV V = act_pre_load(pre);
-    for (int i = tid; i < npad; i += nthreads) {              // a wave stages one whole chunk per turn
+    // A wave stages one whole chunk per turn, compacted to its non-zero elements (in their order) and zero-filled up
+    // to a multiple of eight: a zero leaves its chunk's sum unchanged at every scale, and post-ReLU data is half zeros.
+    for (int i = tid; i < npad; i += nthreads) {
         const float v = i < len ? act_pre(V, x[base + i]) : 0.0f;
-        slice[i] = v;
+        const bool nz = v != 0.0f;
+        const unsigned long long m = __ballot(nz);
+        const int cnt = __popcll(m);
+        const int pos = __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+        const int c0 = i & ~63;
+        const int padded = (cnt + 7) & ~7;
+        if (nz) slice[c0 + pos] = v;
+        if (lane < padded - cnt) slice[c0 + cnt + lane] = 0.0f;
         const unsigned kb = wave_max_u32(bound_key(v, lo));
-        if (lane == 0) s_bounds[i >> 6] = kb;
+        if (lane == 0) { s_bounds[i >> 6] = kb; s_len[i >> 6] = padded; }
     }
     __syncthreads();
 
@@ -248,12 +258,13 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     unsigned ci = 0;
     const int half = split ? kBlockElems / 2 : kBlockElems;
     const int e0 = set * half;
-    int nel = ((len + 7) & ~7) - e0;
+    int nel = npad - e0;                                       // whole chunks: the staging has compacted a ragged one too
     nel = nel < 0 ? 0 : (nel < half ? nel : half);
     if (nel > 0) {
         const float inv_min = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv[0])));   // lane 0: the wave's smallest scale
         const unsigned long long in0 = chunks_inside_range(s_bounds + e0 / kChunk, nel / kChunk, inv_min, lo, hi, lane);
-        sweep_slice<C, kLevelsBlk>(slice + e0, nel, ci, alpha, inv, lo, hi, st, in0);
+        const int lengths = lane < nel / kChunk ? s_len[e0 / kChunk + lane] : 0;
+        sweep_slice<C, kLevelsBlk, kChunk, true>(slice + e0, nel, ci, alpha, inv, lo, hi, st, in0, 0ull, lengths);
     }
     double E[C];
     tree_fold<C, kLevelsBlk>(st, ci, E);                    // 0.0 when this set has no chunk

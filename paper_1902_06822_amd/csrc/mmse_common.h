@@ -364,6 +364,30 @@ __device__ __forceinline__ void sweep_chunk(const float4* s4, const float (&alph
     }
 }
 
+// The same for the first `nelem` elements of a chunk (a multiple of 8, fewer than 64; may be 0), as a loop of eight
+// elements a turn: for chunks that have been compacted to their non-zero elements (sweep_slice).  Fetching a turn
+// ahead (in one buffer handed on, or in two named ones) was measured no faster: other waves cover the LDS latency.
+template <int C, bool CLAMP>
+__device__ __forceinline__ void sweep_chunk_part(const float4* s4, int nelem, const float (&alpha)[C], const float (&inv)[C],
+                                                 float lo, float hi, float (&s)[C])
+{
+    constexpr int NE = (C >= 2) ? 4 : 8;
+    const float4* p4 = s4;
+    const float4* end4 = s4 + nelem / 4;
+#pragma unroll 1
+    for (; p4 != end4; p4 += 2) {
+        const float4 a = p4[0], b = p4[1];
+        const float xs[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int g = 0; g < 8 / NE; ++g) {
+            float x[NE];
+#pragma unroll
+            for (int i = 0; i < NE; ++i) x[i] = xs[g * NE + i];
+            eval_stage<NE, C, CLAMP>(x, alpha, inv, lo, hi, s);
+        }
+    }
+}
+
 // Sweep the `nelem` elements (a multiple of 8; zero padded) that sit in LDS at `slice` for the C
 // candidates of this lane: whole 64-element chunks, then a last shorter chunk that only walks the
 // 8-element groups it has (padding zeros would be exact no-ops, so skipping them changes nothing).
@@ -372,11 +396,16 @@ __device__ __forceinline__ void sweep_chunk(const float4* s4, const float (&alph
 // inside0 / inside1: bit c set (chunks 0-63 / 64-127 of this slice): the caller has shown with chunks_inside_range
 // that the saturation is the identity for chunk c at every scale of this wave; such a chunk takes four instructions
 // per evaluation instead of five.
-template <int C, int L, int CS = kChunk>
+// SPARSE: every chunk of the slice (at most 64 of them, all of them whole) has been compacted to its non-zero
+// elements, zero-filled up to a multiple of eight; lane c holds the resulting length of chunk c in `lengths`.  An
+// element that is zero leaves the sum of its chunk unchanged at every scale (its code is zero, its residual is zero,
+// and s + 0 = s exactly), so walking only the others, in their order, gives the same bits; post-ReLU activations are
+// half zeros.
+template <int C, int L, int CS = kChunk, bool SPARSE = false>
 __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsigned& ci,
                                             const float (&alpha)[C], const float (&inv)[C],
                                             float lo, float hi, double (&st)[C][L],
-                                            unsigned long long inside0 = 0, unsigned long long inside1 = 0)
+                                            unsigned long long inside0 = 0, unsigned long long inside1 = 0, int lengths = 0)
 {
     const float4* s4 = reinterpret_cast<const float4*>(slice);
     constexpr int NE = (C >= 2) ? 4 : 8;
@@ -393,7 +422,17 @@ __device__ __forceinline__ void sweep_slice(const float* slice, int nelem, unsig
             // (the empty statements hide from the compiler that both branches start at the same address: it would
             // merge their first fetches ahead of the branch, at the price of registers the sweep needs for its waves)
             int cc = c;
-            if (inside) {
+            int len = kChunk;
+            if constexpr (SPARSE) len = __builtin_amdgcn_readlane(lengths, c);
+            if (len < kChunk) {
+                if (inside) {
+                    asm volatile("" : "+s"(cc));
+                    sweep_chunk_part<C, false>(s4 + cc * (CS / 4), len, alpha, inv, lo, hi, s);
+                } else {
+                    asm volatile("" : "+s"(cc));
+                    sweep_chunk_part<C, true>(s4 + cc * (CS / 4), len, alpha, inv, lo, hi, s);
+                }
+            } else if (inside) {
                 asm volatile("" : "+s"(cc));
                 sweep_chunk<C, false>(s4 + cc * (CS / 4), alpha, inv, lo, hi, s);
             } else {
