@@ -223,7 +223,8 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     const int npad = (len + kChunk - 1) & ~(kChunk - 1);
     const ActPreV V = act_pre_load(pre);
     // A wave stages one whole chunk per turn, compacted to its non-zero elements (in their order) and zero-filled up
-    // to a multiple of eight: a zero leaves its chunk's sum unchanged at every scale, and post-ReLU data is half zeros.
+    // to a whole stage group of the sweep: a zero leaves its chunk's sum unchanged at every scale, and post-ReLU data
+    // is half zeros.
     for (int i = tid; i < npad; i += nthreads) {
         const float v = i < len ? act_pre(V, x[base + i]) : 0.0f;
         const bool nz = v != 0.0f;
@@ -231,7 +232,7 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
         const int cnt = __popcll(m);
         const int pos = __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
         const int c0 = i & ~63;
-        const int padded = (cnt + 7) & ~7;
+        const int padded = (cnt + kPartGranule<C> - 1) & ~(kPartGranule<C> - 1);
         if (nz) slice[c0 + pos] = v;
         if (lane < padded - cnt) slice[c0 + cnt + lane] = 0.0f;
         const unsigned kb = wave_max_u32(bound_key(v, lo));

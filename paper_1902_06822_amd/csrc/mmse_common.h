@@ -364,18 +364,22 @@ __device__ __forceinline__ void sweep_chunk(const float4* s4, const float (&alph
     }
 }
 
-// The same for the first `nelem` elements of a chunk (a multiple of 8, fewer than 64; may be 0), as a loop of eight
-// elements a turn: for chunks that have been compacted to their non-zero elements (sweep_slice).  Fetching a turn
-// ahead (in one buffer handed on, or in two named ones) was measured no faster: other waves cover the LDS latency.
+// The same for the first `nelem` elements of a chunk (a multiple of the stage group: 4 with two or more candidates
+// per lane, else 8; fewer than 64; may be 0), as a loop of eight elements a turn and one last group of four: for
+// chunks that have been compacted to their non-zero elements (sweep_slice).  Fetching a turn ahead (in one buffer
+// handed on, or in two named ones) was measured no faster (other waves cover the LDS latency); single elements at
+// the end instead of zero-filling the last group gained 1 %.
+template <int C>
+constexpr int kPartGranule = (C >= 2) ? 4 : 8;
+
 template <int C, bool CLAMP>
 __device__ __forceinline__ void sweep_chunk_part(const float4* s4, int nelem, const float (&alpha)[C], const float (&inv)[C],
                                                  float lo, float hi, float (&s)[C])
 {
     constexpr int NE = (C >= 2) ? 4 : 8;
     const float4* p4 = s4;
-    const float4* end4 = s4 + nelem / 4;
 #pragma unroll 1
-    for (; p4 != end4; p4 += 2) {
+    for (int t = nelem >> 3; t > 0; --t, p4 += 2) {           // nelem is uniform: the count lives in a scalar register
         const float4 a = p4[0], b = p4[1];
         const float xs[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
@@ -384,6 +388,13 @@ __device__ __forceinline__ void sweep_chunk_part(const float4* s4, int nelem, co
 #pragma unroll
             for (int i = 0; i < NE; ++i) x[i] = xs[g * NE + i];
             eval_stage<NE, C, CLAMP>(x, alpha, inv, lo, hi, s);
+        }
+    }
+    if constexpr (NE == 4) {
+        if (nelem & 4) {
+            const float4 a = p4[0];
+            const float x[4] = {a.x, a.y, a.z, a.w};
+            eval_stage<4, C, CLAMP>(x, alpha, inv, lo, hi, s);
         }
     }
 }
@@ -397,7 +408,7 @@ __device__ __forceinline__ void sweep_chunk_part(const float4* s4, int nelem, co
 // that the saturation is the identity for chunk c at every scale of this wave; such a chunk takes four instructions
 // per evaluation instead of five.
 // SPARSE: every chunk of the slice (at most 64 of them, all of them whole) has been compacted to its non-zero
-// elements, zero-filled up to a multiple of eight; lane c holds the resulting length of chunk c in `lengths`.  An
+// elements, zero-filled up to a multiple of kPartGranule<C>; lane c holds the resulting length of chunk c in `lengths`.  An
 // element that is zero leaves the sum of its chunk unchanged at every scale (its code is zero, its residual is zero,
 // and s + 0 = s exactly), so walking only the others, in their order, gives the same bits; post-ReLU activations are
 // half zeros.
