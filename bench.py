@@ -537,6 +537,16 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
         # the sweep drops zero elements while staging (a zero adds nothing to a chunk's sum at any scale), so its
         # roofline counts the evaluations of the non-zero elements; the dense count is given beside it
         a_nonzero = sum(int(torch.count_nonzero(x).item()) for x in dev_x)
+        # what a refinement pass reads: the copy the sweep leaves in the workspace, every 64-element chunk's non-zero
+        # elements zero-filled to a multiple of eight, 4096-element blocks with 64 words about their chunks each
+        a_compact_bytes = 0
+        for x in dev_x:
+            f = x.reshape(-1)
+            pad = (-f.numel()) % 64
+            if pad:
+                f = torch.cat([f, f.new_zeros(pad)])
+            nz = (f.view(-1, 64) != 0).sum(dim=1)
+            a_compact_bytes += int((((nz + 7) // 8) * 8).sum().item()) * 4 + ((x.numel() + 4095) // 4096) * 256
         e_a = _alu_entry("k_act_sweep: grid sweep of all activation tensors", a_nonzero * G, l, m, tr_of("k_act_sweep"))
         e_a["counted"] = "evaluations of non-zero elements (zero elements are dropped while staging)"
         e_a["nonzero_fraction"] = round(a_nonzero / max(a_elems, 1), 4)
@@ -547,10 +557,12 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
         hbm.append(_hbm_entry("k_act_absmax: max |x| of every activation tensor", 4.0 * a_elems, l, m, tr_of("k_act_absmax")))
         if 15 in ta:
             l, m = ta[15]
-            hbm.append(_hbm_entry("k_act_probe: one refinement pass over every activation tensor (up to 8 scales per element)",
-                                  4.0 * a_elems * l, l, m, tr_of("k_act_probe")))
+            hbm.append(_hbm_entry("k_act_probe: one refinement pass over the compacted copy of every activation tensor "
+                                  "(up to 8 scales per non-zero element)",
+                                  1.0 * a_compact_bytes * l, l, m, tr_of("k_act_probe")))
+            hbm[-1]["dense_bytes_per_launch"] = 4.0 * a_elems
             if iters == 20:      # 2+2+4 scales per element in the first pass, 1+2+4 in each of the others
-                ev = (8 + 7 * (l - 1)) * a_elems
+                ev = (8 + 7 * (l - 1)) * a_nonzero
                 hbm[-1]["scales_evaluated_per_element"] = 8 + 7 * (round(l) - 1)
                 hbm[-1]["alu_frac"] = round(ev * OPS_PER_EVAL / (m * 1e-3) / LANE_OPS_PER_S, 4)
         l, m = ta[18]
@@ -569,10 +581,11 @@ def run_whole(args, cfg, torch, B, detail: bool, steps: int, warmup: int) -> dic
                         "kernel timed by itself between HIP events on its launch stream, after the timed steps.")
     roofline["traffic_note"] = ("fetched + written bytes per launch at the memory side of L2, from rocprofv3 --pmc FETCH_SIZE / "
                                 "WRITE_SIZE runs of this command (profiles/hbm_traffic.txt); algorithmic bytes: 4 per element read "
-                                "once, plus 8 * grid_points per 4096 elements written by k_act_sweep")
+                                "once, plus 8 * grid_points per 4096 elements and the compacted copy written by k_act_sweep; "
+                                "k_act_probe reads that copy")
     roofline["all_alu_kernels"] = kernels
     roofline["hbm"] = hbm
-    roofline["hbm_note"] = (f"activation set {4 * a_elems / 1e6:.0f} MB, read once per pass; the chip's last-level cache is 256 MB"
+    roofline["hbm_note"] = (f"activation set {4 * a_elems / 1e6:.0f} MB, read once per pass (refinement passes: its compacted copy); the chip's last-level cache is 256 MB"
                             if dev_x else "no activation tensors in this configuration")
     out["roofline"] = roofline
     out["alone_ms"] = {"weights": round(weights_alone_ms, 4), "second_tensor": round(second_alone_ms, 4),

@@ -91,7 +91,10 @@ typedef struct mmse_tensor_desc_t {
 
 /* Workspace sizes (bytes; host call, nothing enqueued).  ws_dev must be aligned
  * to 256 bytes.  For a batched call pass the sum of K over all tensors as K and
- * any n. */
+ * any n.  With refine_iters > 0 the activation workspace includes 4 bytes per
+ * element (in whole blocks of 4096 elements, plus 256 bytes per block): the grid
+ * sweep leaves the searched values there with the zeros dropped, and the
+ * refinement passes read that copy instead of the tensor. */
 int mmse_workspace_bytes_kernelwise(int64_t K, int64_t n, const mmse_params_t *p, size_t *bytes_out);
 int mmse_workspace_bytes_activation(int64_t N, const mmse_params_t *p, size_t *bytes_out);
 
@@ -124,7 +127,7 @@ int mmse_scale_search_activation(const float *x_dev, int64_t N, const mmse_param
 /* Second tensor of an activation (Section 3.7, Eq. 16): X ~ beta1*[X/beta1] + beta2*[(X - beta1*X1)/beta2].
  * scale1_dev holds beta1 (one float, device; normally the output of mmse_scale_search_activation), the
  * first codes X1 = [X/beta1] saturate to [qmin1, qmax1]; the residual X - beta1*X1 (one fused
- * multiply-add per element, never stored) is searched in p's range with p's grid and refinement
+ * multiply-add per element, formed as the tensor is read) is searched in p's range with p's grid and refinement
  * ("one iteration only" of Algorithm 1).  The residual of unsigned first codes has both signs, so the
  * second range is independent of the first: p->qmin..p->qmax, e.g. -8..7.  Outputs as in
  * mmse_scale_search_activation, plus the residual's codes in packed2_dev (ceil(N/2) bytes, layout of
@@ -135,7 +138,7 @@ int activation_residual_quantize(const float *x_dev, int64_t N, const float *sca
                                  uint8_t *packed2_dev, void *ws_dev, size_t ws_bytes, void *stream);
 
 /* Offset form (Section 3.1, Eq. 2) with the scale found by the MMSE search: delta = min_i x_i, the shifted
- * tensor x - delta (one fp32 subtraction per element, never stored) is searched in the unsigned range
+ * tensor x - delta (one fp32 subtraction per element, formed as the tensor is read) is searched in the unsigned range
  * 0..p->qmax (p->qmin must be 0); the last grid point is Eq. 2's own scale (max - delta)/qmax.
  * x ~ scale*codes + delta.  delta_dev: one float out (NaN when the tensor is rejected: a non-finite element,
  * or max - min above 2^60); sse_dev is the error of the shifted tensor; packed_dev (optional) its codes.

@@ -192,6 +192,12 @@ __global__ void k_act_offset_setup(ActState* S, float* delta_out)
     *delta_out = (range <= kHuge) ? mn : nanf_;
 }
 
+// Where a chunk of a block's compacted copy starts (floats from the start of the block's 4096-float slot, a multiple
+// of 8, at most 4096 - its length) and how many elements it has there (a multiple of 8, at most 64), as one word.
+__device__ __forceinline__ unsigned compact_meta(int off, int len) { return (unsigned)off | ((unsigned)len << 16); }
+__device__ __forceinline__ int compact_off(unsigned m) { return (int)(m & 0xffffu); }
+__device__ __forceinline__ int compact_len(unsigned m) { return (int)(m >> 16); }
+
 // Grid sweep of one 4096-element block per workgroup; waves split the candidates.  With split != 0 the waves
 // form two sets that each cover all candidates and take one half of the block (32 chunks) each: the halves are
 // the two subtrees under the root of the block's pairwise tree, so set 0 adds the two sums at the end (one
@@ -201,12 +207,14 @@ constexpr int kMaxSplitCands = 384;
 
 template <int C>
 __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int qmax,
-                                                    float lo, float hi, double* part0, const ActPre pre, int split)
+                                                    float lo, float hi, double* part0, const ActPre pre, int split,
+                                                    float* compact, unsigned* meta)
 {
     __shared__ float4 slice4[kBlockElems / 4];
     __shared__ double xbuf[kMaxSplitCands];
     __shared__ unsigned s_bounds[kBlockChunks];             // largest bound_key of every chunk of the block
-    __shared__ int s_len[kBlockChunks];                     // its length once compacted to its non-zero elements
+    __shared__ int s_len[kBlockChunks];                     // its length once compacted to its non-zero elements (low
+                                                            // byte; above it, where its copy in the workspace starts)
     float* slice = reinterpret_cast<float*>(slice4);
     const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
     const int wps = split ? (nthreads >> 7) : (nthreads >> 6);          // waves per set
@@ -240,6 +248,30 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     }
     __syncthreads();
 
+    // For the refinement passes: the block as staged (the variant's operation applied, zeros dropped) goes to the
+    // workspace, chunk after chunk without gaps, each zero-filled up to a multiple of eight elements, with where
+    // every chunk starts and how long it is (compact_meta); k_act_probe reads that instead of the tensor.
+    if (compact != nullptr) {
+        if (tid < kBlockChunks) {
+            const int l4 = tid < npad / kChunk ? s_len[tid] : 0;
+            const int l8 = (l4 + 7) & ~7;
+            int end = l8;                                        // inclusive prefix sum over the 64 chunks
+#pragma unroll
+            for (int d = 1; d < kBlockChunks; d <<= 1) {
+                const int up = __shfl_up(end, d, 64);
+                if (lane >= d) end += up;
+            }
+            s_len[tid] = l4 | ((end - l8) << 8);
+            meta[(size_t)blockIdx.x * kBlockChunks + tid] = compact_meta(end - l8, l8);
+        }
+        __syncthreads();
+        float* out = compact + (size_t)blockIdx.x * kBlockElems;
+        for (int c = tid >> 6; c < npad / kChunk; c += nthreads >> 6) {
+            const int w = s_len[c], l4 = w & 0xff;
+            if (lane < ((l4 + 7) & ~7)) out[(w >> 8) + lane] = lane < l4 ? slice[c * kChunk + lane] : 0.0f;
+        }
+    }
+
     const float qmaxf = (float)qmax, Gf = (float)G;
     float alpha[C], inv[C];
     int jcand[C];
@@ -264,7 +296,7 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     if (nel > 0) {
         const float inv_min = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv[0])));   // lane 0: the wave's smallest scale
         const unsigned long long in0 = chunks_inside_range(s_bounds + e0 / kChunk, nel / kChunk, inv_min, lo, hi, lane);
-        const int lengths = lane < nel / kChunk ? s_len[e0 / kChunk + lane] : 0;
+        const int lengths = lane < nel / kChunk ? s_len[e0 / kChunk + lane] & 0xff : 0;
         sweep_slice<C, kLevelsBlk, kChunk, true>(slice + e0, nel, ci, alpha, inv, lo, hi, st, in0, 0ull, lengths);
     }
     double E[C];
@@ -413,46 +445,39 @@ __global__ void __launch_bounds__(256) k_act_argmin(const ActBatch B, int level,
 }
 
 // One refinement pass: f at up to kMaxProbes scales for every block of 64 chunks, one workgroup of four waves
-// per block.  Both roofs bind here about equally (eight scales are 40 VALU instructions per 4 bytes read, the
-// machine's own ratio), so the kernel has the shape of the grid sweep, which keeps the VALU busy at eight waves
-// per SIMD, and streams its input like the abs-max pass: the block is staged into LDS with coalesced
-// non-temporal 16-byte loads (chunks padded apart by four floats), lane = (scale, pair of chunks): the eight
-// lanes of a scale-group read the same element (a broadcast), the eight groups of a wave read eight different
-// chunks (different banks), and every lane runs the same sweep core over its two chunks.  The chunk sums of a
-// scale are then 32 level-1 nodes of the block's pairwise tree; the first wave adds them up.
-constexpr int kProbeChunkStride = kChunk + 4;
-
-__global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, float hi, double* probe0, const ActPre pre)
+// per block.  It reads the compacted copy that k_act_sweep left in the workspace (half the bytes and half the
+// evaluations on post-ReLU data; a zero changes no sum): coalesced non-temporal 16-byte loads into LDS, the first
+// half of the slot without waiting for the block's length.  lane = (scale, pair of chunks): the eight lanes of a
+// scale-group read the same element (a broadcast), the eight groups of a wave walk eight different chunks, each
+// as far as it goes, and the wave takes as many turns as its longest chunk.  The chunk sums of a scale are then 32
+// level-1 nodes of the block's pairwise tree; the first wave adds them up.
+__global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, float hi, double* probe0,
+                                                   const float* __restrict__ compact, const unsigned* __restrict__ meta)
 {
-    __shared__ float4 tile4[kBlockChunks * kProbeChunkStride / 4];
+    __shared__ float4 tile4[kBlockElems / 4];
+    __shared__ unsigned s_meta[kBlockChunks];
     __shared__ double node[kBlockChunks / 2][kMaxProbes];
-    float* tile = reinterpret_cast<float*>(tile4);
     const int tid = threadIdx.x;
     const int t = act_find(B, blockIdx.x);
     const ActState* S = B.S + t;
     if (S->status != 0 || S->done) return;                    // uniform over the workgroup
-    const float* __restrict__ x = B.x[t];
-    const long long N = B.N[t];
-    const ActPreV V = act_pre_load(pre);
     const int np = S->nprobe;
-    const long long base = (long long)(blockIdx.x - B.start[t]) * kBlockElems;
-    const int len = (N - base) < kBlockElems ? (int)(N - base) : kBlockElems;
-
-    // stage the block: element i of the block goes to tile[i + 4 * (i / 64)]; beyond the tensor: exact zeros
-    if (len == kBlockElems && (reinterpret_cast<uintptr_t>(x) & 15u) == 0) {
-        float4 v[kBlockElems / 4 / 256];
+    const float* src = compact + (size_t)blockIdx.x * kBlockElems;
+    const unsigned* mb = meta + (size_t)blockIdx.x * kBlockChunks;
+    constexpr int R = kBlockElems / 4 / 256;                  // 16-byte pieces per thread for a whole slot
+    float4 v[R];
 #pragma unroll
-        for (int r = 0; r < kBlockElems / 4 / 256; ++r) v[r] = load_stream_f4(x + base + (size_t)(r * 256 + tid) * 4);
+    for (int r = 0; r < R / 2; ++r) v[r] = load_stream_f4(src + (size_t)(r * 256 + tid) * 4);
+    const unsigned last = mb[kBlockChunks - 1];
+    const int total = compact_off(last) + compact_len(last);  // floats of the block's copy
+    if (tid < kBlockChunks) s_meta[tid] = mb[tid];
 #pragma unroll
-        for (int r = 0; r < kBlockElems / 4 / 256; ++r) {
-            const int i = (r * 256 + tid) * 4;
-            float4 w = v[r];
-            if (V.mode != 0) { w.x = act_pre(V, w.x); w.y = act_pre(V, w.y); w.z = act_pre(V, w.z); w.w = act_pre(V, w.w); }
-            *reinterpret_cast<float4*>(tile + i + 4 * (i / kChunk)) = w;
-        }
-    } else {
-        for (int i = tid; i < kBlockElems; i += 256) tile[i + 4 * (i / kChunk)] = i < len ? act_pre(V, x[base + i]) : 0.0f;
+    for (int r = R / 2; r < R; ++r) {
+        v[r] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if ((r * 256 + tid) * 4 < total) v[r] = load_stream_f4(src + (size_t)(r * 256 + tid) * 4);
     }
+#pragma unroll
+    for (int r = 0; r < R; ++r) tile4[r * 256 + tid] = v[r];
     __syncthreads();
 
     const int p = tid & 7, g = tid >> 3;                      // scale, pair of chunks (2g, 2g + 1)
@@ -460,7 +485,24 @@ __global__ void __launch_bounds__(256) k_act_probe(const ActBatch B, float lo, f
     const float inv[1] = {S->probe_inv[p]};
     double st[1][2] = {{0.0, 0.0}};
     unsigned ci = 0;
-    sweep_slice<1, 2, kProbeChunkStride>(tile + 2 * g * kProbeChunkStride, 2 * kChunk, ci, alpha, inv, lo, hi, st);
+#pragma unroll 1
+    for (int slot = 0; slot < 2; ++slot, ++ci) {
+        const unsigned m = s_meta[2 * g + slot];
+        const int turns = compact_len(m) >> 3;                // of eight elements
+        const int most = __builtin_amdgcn_readfirstlane((int)wave_max_u32((unsigned)turns));
+        const float4* p4 = tile4 + (compact_off(m) >> 2);
+        float s[1] = {0.0f};
+#pragma unroll 1
+        for (int k = 0; k < most; ++k) {
+            if (k < turns) {
+                const float4 a = p4[2 * k], b = p4[2 * k + 1];
+                const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                eval_stage<8, 1>(x, alpha, inv, lo, hi, s);
+            }
+        }
+        double ts[1] = {(double)s[0]};
+        tree_push<1, 2>(st, ts, ci);
+    }
     double E[1];
     tree_fold<1, 2>(st, ci, E);
     node[g][p] = E[0];

@@ -363,11 +363,14 @@ struct ActPlan {
     size_t off_part[8];     // byte offsets of the grid-sum levels ([rows][G] doubles)
     size_t off_probe[8];    // byte offsets of the probe levels ([rows][kMaxProbes] doubles); only the columns below a
                             // tensor's nprobe are written in a pass, and only those are read
+    size_t off_compact;     // with a refinement: every block as k_act_sweep staged it, 4096 floats each, and
+    size_t off_meta;        // 64 words each that say where its chunks are (k_act_probe reads these)
     size_t bytes;
 };
 
-// Workspace of one launch group: the states, then the levels of the grid sums, then those of the probe sums.
-ActPlan plan_activation(const long long* N, int count, int G)
+// Workspace of one launch group: the states, then the levels of the grid sums, then those of the probe sums, then
+// (when the search refines: iters > 0) the compacted copy of the tensors for the refinement passes.
+ActPlan plan_activation(const long long* N, int count, int G, int iters)
 {
     ActPlan P{};
     P.count = count;
@@ -387,6 +390,10 @@ ActPlan plan_activation(const long long* N, int count, int G)
     size_t off = round256(sizeof(ActState) * (size_t)count);
     for (int l = 0; l <= P.levels; ++l) { P.off_part[l] = off; off += round256((size_t)P.total_rows[l] * G * sizeof(double)); }
     for (int l = 0; l <= P.plevels; ++l) { P.off_probe[l] = off; off += round256((size_t)P.total_rows[l] * kMaxProbes * sizeof(double)); }
+    if (iters > 0) {
+        P.off_compact = off; off += (size_t)P.start[count] * kBlockElems * sizeof(float);
+        P.off_meta = off; off += round256((size_t)P.start[count] * kBlockChunks * sizeof(unsigned));
+    }
     P.bytes = off;
     return P;
 }
@@ -500,7 +507,7 @@ int mmse_workspace_bytes_activation(int64_t N, const mmse_params_t* p, size_t* b
     if (rc) return rc;
     if (N <= 0 || N > MMSE_MAX_TENSOR_ELEMS) return MMSE_ERR_SIZE;
     const long long n1 = N;
-    *bytes_out = plan_activation(&n1, 1, p->grid_points).bytes;
+    *bytes_out = plan_activation(&n1, 1, p->grid_points, p->refine_iters).bytes;
     return MMSE_OK;
 }
 
@@ -517,7 +524,7 @@ int mmse_workspace_bytes_activation_batched(const int64_t* N_host, int32_t count
         const int m = act_group_size(g0, count, [&](int i) { return N_host[i]; });
         long long n[kMaxActBatch];
         for (int i = 0; i < m; ++i) n[i] = N_host[g0 + i];
-        total += plan_activation(n, m, p->grid_points).bytes;
+        total += plan_activation(n, m, p->grid_points, p->refine_iters).bytes;
         g0 += m;
     }
     *bytes_out = total;
@@ -962,9 +969,11 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
         const int C = split ? 2 : pick_cands(p);
         const int waves = (split ? 2 : 1) * ((G + 64 * C - 1) / (64 * C));
         double* part0 = reinterpret_cast<double*>(ws + P.off_part[0]);
-        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
-        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
-        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split);
+        float* compact = p->refine_iters > 0 ? reinterpret_cast<float*>(ws + P.off_compact) : nullptr;
+        unsigned* meta = p->refine_iters > 0 ? reinterpret_cast<unsigned*>(ws + P.off_meta) : nullptr;
+        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split, compact, meta);
+        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split, compact, meta);
+        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split, compact, meta);
         MMSE_CHECK_LAUNCH(MMSE_STAGE_A_SWEEP);
     }
     for (int l = 0; l < P.levels; ++l) {
@@ -983,7 +992,9 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     }
     for (int pass = 0; pass < refine_passes(p->refine_iters); ++pass) {
         hipLaunchKernelGGL(k_act_probe, dim3(total), dim3(256), 0, s, B, lo, hi,
-                           reinterpret_cast<double*>(ws + P.off_probe[0]), pre);
+                           reinterpret_cast<double*>(ws + P.off_probe[0]),
+                           reinterpret_cast<const float*>(ws + P.off_compact),
+                           reinterpret_cast<const unsigned*>(ws + P.off_meta));
         MMSE_CHECK_LAUNCH(MMSE_STAGE_A_PROBE);
         for (int l = 0; l < P.plevels; ++l) {
             hipLaunchKernelGGL(k_act_reduce64, dim3(P.total_rows[l + 1], 1), dim3(64), 0, s, B, l + 1,
@@ -1015,7 +1026,7 @@ static int run_activation(const float* x_dev, int64_t N, const mmse_params_t* p,
     if (!aligned_to(x_dev, 4) || !aligned_to(scale_dev, 4) || !aligned_to(idx_dev, 4) || !aligned_to(sse_dev, 8))
         return MMSE_ERR_ALIGN;
     const long long n1 = N;
-    const ActPlan P = plan_activation(&n1, 1, p->grid_points);
+    const ActPlan P = plan_activation(&n1, 1, p->grid_points, p->refine_iters);
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < P.bytes) return MMSE_ERR_WORKSPACE;
     const ActItem item{x_dev, n1, scale_dev, idx_dev, sse_dev, packed_dev};
     return run_activation_group(&item, 1, p, pre_mode, scale1_dev, qmin1, qmax1, delta_dev,
@@ -1033,7 +1044,7 @@ int mmse_grid_sse_activation(const float* x_dev, int64_t N, const mmse_params_t*
     const long long n1 = N;
     mmse_params_t q = *p;
     q.refine_iters = 0;
-    const ActPlan P = plan_activation(&n1, 1, q.grid_points);
+    const ActPlan P = plan_activation(&n1, 1, q.grid_points, q.refine_iters);
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < P.bytes) return MMSE_ERR_WORKSPACE;
     ActState* S = reinterpret_cast<ActState*>(ws_dev);
     const ActItem item{x_dev, n1, &S->out_scale, &S->out_idx, &S->out_sse, nullptr};   // the search results stay in the workspace
@@ -1061,7 +1072,7 @@ int mmse_scale_search_activation_batched(const mmse_act_desc_t* descs_host, int3
         const int m = act_group_size(g0, count, [&](int i) { return descs_host[i].N; });
         long long n[kMaxActBatch];
         for (int i = 0; i < m; ++i) n[i] = descs_host[g0 + i].N;
-        need += plan_activation(n, m, p->grid_points).bytes;
+        need += plan_activation(n, m, p->grid_points, p->refine_iters).bytes;
         g0 += m;
     }
     if (!ws_dev || !aligned_to(ws_dev, 256) || ws_bytes < need) return MMSE_ERR_WORKSPACE;
@@ -1075,7 +1086,7 @@ int mmse_scale_search_activation_batched(const mmse_act_desc_t* descs_host, int3
             n[i] = d.N;
             items[i] = ActItem{d.x_dev, (long long)d.N, d.scale_dev, d.idx_dev, d.sse_dev, d.packed_dev};
         }
-        const ActPlan P = plan_activation(n, m, p->grid_points);
+        const ActPlan P = plan_activation(n, m, p->grid_points, p->refine_iters);
         rc = run_activation_group(items, m, p, 0, nullptr, 0, 0, nullptr, ws, P, static_cast<hipStream_t>(stream));
         if (rc) return rc;
         ws += P.bytes;

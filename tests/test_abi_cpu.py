@@ -52,9 +52,12 @@ def test_status_strings(B):
 def test_workspace_queries(B):
     p = B.params(-8, 7, 256, 20)
     assert B.mmse_workspace_bytes_kernelwise(5800, 576, p) == 23296          # 5800 floats, rounded to 256
+    n0 = B.mmse_workspace_bytes_activation(4096, B.params(-8, 7, 256, 0))
     n1 = B.mmse_workspace_bytes_activation(4096, p)
     n2 = B.mmse_workspace_bytes_activation(51380224, B.params(0, 15, 512, 20))
-    assert 256 < n1 < 16384 and n2 > 12544 * 512 * 8
+    assert 256 < n0 < 16384
+    assert n1 == n0 + 4096 * 4 + 256          # with a refinement: the block's compacted copy and its 64 chunk words
+    assert n2 > 12544 * 512 * 8 + 12544 * (4096 * 4 + 256)
     with pytest.raises(RuntimeError):
         B.mmse_workspace_bytes_kernelwise(0, 5, p)
     with pytest.raises(RuntimeError):
