@@ -87,6 +87,12 @@ def run_activation_cases(B, seed, count):
                 synth.acts_relu_normal(n, int(rng.integers(1 << 30)))
             if q[0] < 0:
                 x = (x - np.float32(0.6)).astype(np.float32)
+            if rng.integers(3) == 0:                  # any share of zeros, in runs and scattered, also among signed data
+                keep = float(rng.choice([0.02, 0.3, 0.9]))
+                mask = rng.random(n) < keep
+                if rng.integers(2):
+                    mask &= (np.arange(n) // int(rng.integers(40, 9000))) % 2 == 0
+                x = np.where(mask, x, np.float32(0.0)).astype(np.float32)
             xs.append(x)
         res = B.mmse_scale_search_activation_batched([dev(x) for x in xs], B.params(*q, G, iters))
         torch.cuda.synchronize()
