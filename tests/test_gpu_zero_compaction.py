@@ -59,7 +59,7 @@ def sparse_tensor(nchunks, tail, signed, seed, zero_blocks=()):
 
 
 @pytest.mark.parametrize("q", [(0, 15), (-8, 7), (0, 3)])
-@pytest.mark.parametrize("G", [512, 256, 100])
+@pytest.mark.parametrize("G", [512, 256, 100, 2048])          # two candidates per lane, two sets of waves, one, four
 def test_grid_errors_of_sparse_chunks(B, q, G):
     for nchunks, tail, zb in ((64, 0, ()), (150, 31, ()), (200, 5, (1,)), (3, 1, ()), (0, 7, ())):
         x = sparse_tensor(nchunks, tail, q[0] < 0, 3 + nchunks, zb)
@@ -70,13 +70,14 @@ def test_grid_errors_of_sparse_chunks(B, q, G):
 
 
 @pytest.mark.parametrize("q", [(0, 15), (-8, 7)])
-def test_search_and_codes_of_sparse_tensors(B, q):
+@pytest.mark.parametrize("G", [512, 200, 64, 1500])
+def test_search_and_codes_of_sparse_tensors(B, q, G):
     xs = [sparse_tensor(130, 9, q[0] < 0, 21, (0,)), sparse_tensor(64, 0, q[0] < 0, 22),
           sparse_tensor(1, 3, q[0] < 0, 23), sparse_tensor(700, 63, q[0] < 0, 24, (3, 9))]
-    say(f"zero compaction search q={q} sizes={[x.size for x in xs]}")
-    got = B.mmse_scale_search_activation_batched([dev(x) for x in xs], B.params(*q, 512, 20), want_packed=True)
+    say(f"zero compaction search q={q} G={G} sizes={[x.size for x in xs]}")
+    got = B.mmse_scale_search_activation_batched([dev(x) for x in xs], B.params(*q, G, 20), want_packed=True)
     for i, (x, g) in enumerate(zip(xs, got)):
-        o = oracle.can_search(x, *q, 512, 20)
+        o = oracle.can_search(x, *q, G, 20)
         assert int(g.idx[0]) == o["idx"], f"idx of tensor {i}"
         np.testing.assert_array_equal(g.scale.cpu().numpy(), np.array([o["scale"]], np.float32), err_msg=f"scale {i}")
         np.testing.assert_array_equal(g.sse.cpu().numpy(), np.array([o["sse"]]), err_msg=f"sse {i}")
