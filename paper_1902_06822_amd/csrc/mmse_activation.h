@@ -13,7 +13,8 @@ namespace {
 //   part0[nb][G] doubles                  per-block tree sums of the grid sweep
 //   part1[ceil(nb/64)][G], part2, ...     upper tree levels, 64 blocks at a time
 //   probe0[nb], probe1[...], ...          same hierarchy for one refinement probe
-// What the activation kernels search instead of the stored tensor (never written to memory):
+// What the activation kernels search instead of the stored tensor (formed as the tensor is read; the grid sweep leaves
+// its non-zero values in the workspace for the refinement passes, see k_act_sweep):
 //   mode 1: the residual of a first tensor, x - s*[x/s] saturated to [lo1, hi1]   (Section 3.7, Eq. 16)
 //   mode 2: the shifted tensor x - delta, delta = min x                            (Section 3.1, Eq. 2)
 struct ActPre {
