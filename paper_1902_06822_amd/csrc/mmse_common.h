@@ -365,10 +365,11 @@ __device__ __forceinline__ void sweep_chunk(const float4* s4, const float (&alph
 }
 
 // The same for the first `nelem` elements of a chunk (a multiple of the stage group: 4 with two or more candidates
-// per lane, else 8; fewer than 64; may be 0), as a loop of eight elements a turn and one last group of four: for
-// chunks that have been compacted to their non-zero elements (sweep_slice).  Fetching a turn ahead (in one buffer
-// handed on, or in two named ones) was measured no faster (other waves cover the LDS latency); single elements at
-// the end instead of zero-filling the last group gained 1 %.
+// per lane, else 8; fewer than 64; may be 0): the first 32 unrolled like a whole chunk when there are that many
+// (post-ReLU chunks have 32 non-zero elements on average), then a loop of eight elements a turn and one last group of
+// four: for chunks that have been compacted to their non-zero elements (sweep_slice).  In the loop, fetching a turn
+// ahead (in one buffer handed on, or in two named ones) was measured no faster (other waves cover the LDS latency);
+// single elements at the end instead of zero-filling the last group gained 1 %.
 template <int C>
 constexpr int kPartGranule = (C >= 2) ? 4 : 8;
 
@@ -378,8 +379,30 @@ __device__ __forceinline__ void sweep_chunk_part(const float4* s4, int nelem, co
 {
     constexpr int NE = (C >= 2) ? 4 : 8;
     const float4* p4 = s4;
+    int turns = nelem >> 3;
+    if (turns >= 4) {                                         // the first 32 elements unrolled, fetched a group ahead
+        float4 nxt[NE / 4];
+#pragma unroll
+        for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[q];
+#pragma unroll
+        for (int e = 0; e < 32 / NE; ++e) {
+            float x[NE];
+#pragma unroll
+            for (int q = 0; q < NE / 4; ++q) {
+                x[4 * q + 0] = nxt[q].x; x[4 * q + 1] = nxt[q].y; x[4 * q + 2] = nxt[q].z; x[4 * q + 3] = nxt[q].w;
+            }
+            if (e + 1 < 32 / NE) {
+#pragma unroll
+                for (int q = 0; q < NE / 4; ++q) nxt[q] = s4[(e + 1) * (NE / 4) + q];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            eval_stage<NE, C, CLAMP>(x, alpha, inv, lo, hi, s);
+        }
+        turns -= 4;
+        p4 += 8;
+    }
 #pragma unroll 1
-    for (int t = nelem >> 3; t > 0; --t, p4 += 2) {           // nelem is uniform: the count lives in a scalar register
+    for (int t = turns; t > 0; --t, p4 += 2) {                // nelem is uniform: the count lives in a scalar register
         const float4 a = p4[0], b = p4[1];
         const float xs[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
