@@ -199,26 +199,28 @@ __device__ __forceinline__ unsigned compact_meta(int off, int len) { return (uns
 __device__ __forceinline__ int compact_off(unsigned m) { return (int)(m & 0xffffu); }
 __device__ __forceinline__ int compact_len(unsigned m) { return (int)(m >> 16); }
 
-// Grid sweep of one 4096-element block per workgroup; waves split the candidates.  With split != 0 the waves
-// form two sets that each cover all candidates and take one half of the block (32 chunks) each: the halves are
-// the two subtrees under the root of the block's pairwise tree, so set 0 adds the two sums at the end (one
-// exchange through LDS).  That keeps four waves per workgroup, and with them eight waves per SIMD within the
-// LDS of a CU, for grids that two candidates per lane would otherwise cover with two waves.
+// Grid sweep of one 4096-element block per workgroup; waves split the candidates.  With sets > 1 (2, 4 or 8) the
+// waves form that many sets that each cover all candidates and take one aligned part of the block (32, 16 or 8
+// chunks) each: the parts are the subtrees at one level of the block's pairwise tree, so set 0 adds their sums
+// pairwise at the end (one exchange through LDS; a part that lies beyond a ragged block contributes an exact 0).
+// Two sets keep four waves per workgroup, and with them eight waves per SIMD within the LDS of a CU, for grids that
+// two candidates per lane would otherwise cover with two waves; four and eight sets are for calls of so few blocks
+// that the machine is not full, where they shorten the one sweep every wave has to get through.
 constexpr int kMaxSplitCands = 384;
+constexpr int kMaxExchange = kBlockElems / 2;           // doubles that fit the slice once it has been swept
 
 template <int C>
 __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int qmax,
-                                                    float lo, float hi, double* part0, const ActPre pre, int split,
+                                                    float lo, float hi, double* part0, const ActPre pre, int sets,
                                                     float* compact, unsigned* meta)
 {
     __shared__ float4 slice4[kBlockElems / 4];
-    __shared__ double xbuf[kMaxSplitCands];
     __shared__ unsigned s_bounds[kBlockChunks];             // largest bound_key of every chunk of the block
     __shared__ int s_len[kBlockChunks];                     // its length once compacted to its non-zero elements (low
                                                             // byte; above it, where its copy in the workspace starts)
     float* slice = reinterpret_cast<float*>(slice4);
     const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
-    const int wps = split ? (nthreads >> 7) : (nthreads >> 6);          // waves per set
+    const int wps = (nthreads >> 6) / sets;                             // waves per set
     const int set = (tid >> 6) / wps, wave = (tid >> 6) - set * wps;     // wave: its number inside the set
     const int t = act_find(B, blockIdx.x);
     const float* __restrict__ x = B.x[t];
@@ -290,10 +292,10 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
 #pragma unroll
         for (int l = 0; l < kLevelsBlk; ++l) st[u][l] = 0.0;
     unsigned ci = 0;
-    const int half = split ? kBlockElems / 2 : kBlockElems;
-    const int e0 = set * half;
+    const int part = kBlockElems / sets;
+    const int e0 = set * part;
     int nel = npad - e0;                                       // whole chunks: the staging has compacted a ragged one too
-    nel = nel < 0 ? 0 : (nel < half ? nel : half);
+    nel = nel < 0 ? 0 : (nel < part ? nel : part);
     if (nel > 0) {
         const float inv_min = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv[0])));   // lane 0: the wave's smallest scale
         const unsigned long long in0 = chunks_inside_range(s_bounds + e0 / kChunk, nel / kChunk, inv_min, lo, hi, lane);
@@ -302,15 +304,25 @@ __global__ void __launch_bounds__(512) k_act_sweep(const ActBatch B, int G, int 
     }
     double E[C];
     tree_fold<C, kLevelsBlk>(st, ci, E);                    // 0.0 when this set has no chunk
-    if (split) {
-        if (set == 1) {
+    if (sets > 1) {
+        // the sums of sets 1 ... meet those of set 0 in the slice, which nobody reads any more after the first barrier
+        double* exch = reinterpret_cast<double*>(slice4);
+        const int ncand = wps * 64 * C;                      // candidates a set covers (>= G); sets * ncand <= kMaxExchange
+        __syncthreads();
+        if (set != 0) {
 #pragma unroll
-            for (int u = 0; u < C; ++u) xbuf[jcand[u]] = E[u];
+            for (int u = 0; u < C; ++u) exch[set * ncand + jcand[u]] = E[u];
         }
         __syncthreads();
         if (set == 0) {
 #pragma unroll
-            for (int u = 0; u < C; ++u) E[u] = E[u] + xbuf[jcand[u]];
+            for (int u = 0; u < C; ++u) {
+                const double* v = exch + jcand[u];
+                if (sets == 2) E[u] = E[u] + v[ncand];
+                else if (sets == 4) E[u] = (E[u] + v[ncand]) + (v[2 * ncand] + v[3 * ncand]);
+                else E[u] = ((E[u] + v[ncand]) + (v[2 * ncand] + v[3 * ncand]))
+                          + ((v[4 * ncand] + v[5 * ncand]) + (v[6 * ncand] + v[7 * ncand]));
+            }
         }
     }
     if (set == 0) {

@@ -81,6 +81,7 @@ inline void trace_mark(hipStream_t s, int stage)
 // number of kernels or blocks (1024 only for kernels of more than 32768 elements, of which a tensor has fewer
 // than 65536), so launches are cut at this many workgroups.
 constexpr long long kMaxLaunchWG = 1LL << 22;
+constexpr int kFewBlocks = 512;         // activation blocks in a call up to which the chip's 256 CUs are not all busy twice over
 constexpr long long kFusedMaxKernels = 1024;      // calls of at most this many kernels and elements take the single-launch
 constexpr long long kFusedMaxElements = 1 << 20;  // search: beyond, the separate refinement kernel packs its lanes better
 static_assert(kMaxLaunchWG == MMSE_MAX_KERNELS, "one workgroup per kernel");
@@ -965,15 +966,21 @@ static int run_activation_group(const ActItem* items, int count, const mmse_para
     {
         // 129 ... 384 grid points, tuning left to the library: two candidates per lane and two sets of waves that
         // take half a block each (see k_act_sweep)
-        const int split = (p->cands_per_lane == 0 && G > 128 && G <= kMaxSplitCands) ? 1 : 0;
+        const bool split = p->cands_per_lane == 0 && G > 128 && G <= kMaxSplitCands;
         const int C = split ? 2 : pick_cands(p);
-        const int waves = (split ? 2 : 1) * ((G + 64 * C - 1) / (64 * C));
+        const int wps = (G + 64 * C - 1) / (64 * C);                  // waves that cover the grid once
+        int sets = split ? 2 : 1;
+        // a call of few blocks leaves most of the machine idle while every wave walks its whole block: more sets
+        // of waves per block, each with a smaller part of it (up to eight waves a workgroup; same sums, same order)
+        if (total <= kFewBlocks)
+            while (sets < 8 && wps * sets * 2 <= 8 && sets * 2 * wps * 64 * C <= kMaxExchange) sets *= 2;
+        const int waves = sets * wps;
         double* part0 = reinterpret_cast<double*>(ws + P.off_part[0]);
         float* compact = p->refine_iters > 0 ? reinterpret_cast<float*>(ws + P.off_compact) : nullptr;
         unsigned* meta = p->refine_iters > 0 ? reinterpret_cast<unsigned*>(ws + P.off_meta) : nullptr;
-        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split, compact, meta);
-        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split, compact, meta);
-        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, split, compact, meta);
+        if (C == 1) hipLaunchKernelGGL(k_act_sweep<1>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, sets, compact, meta);
+        else if (C == 2) hipLaunchKernelGGL(k_act_sweep<2>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, sets, compact, meta);
+        else hipLaunchKernelGGL(k_act_sweep<4>, dim3(total), dim3(64 * waves), 0, s, B, G, p->qmax, lo, hi, part0, pre, sets, compact, meta);
         MMSE_CHECK_LAUNCH(MMSE_STAGE_A_SWEEP);
     }
     for (int l = 0; l < P.levels; ++l) {
