@@ -92,3 +92,19 @@ def test_one_nonzero_element_in_a_large_tensor(B):
     absmax, grid = B.mmse_grid_sse_activation(dev(x), B.params(0, 15, 512, 0))
     r = oracle.can_search(x, 0, 15, 512, 0, want_grid=True)
     np.testing.assert_array_equal(grid.cpu().numpy().reshape(-1), r["grid_sse"])
+
+
+def test_a_workspace_that_held_another_tensor(B):
+    """The compacted copy and its chunk words live in the caller's workspace: a second search in the same workspace
+    must not see what the first one left there (a larger, denser tensor, then smaller and sparser ones)."""
+    p = B.params(0, 15, 512, 20)
+    big = np.abs(np.random.default_rng(3).normal(0, 1, 4096 * 9 + 77)).astype(np.float32) + np.float32(0.01)   # no zeros
+    ws = B.alloc_workspace(B.mmse_workspace_bytes_activation(big.size, p))
+    say("zero compaction: one workspace, several tensors in a row")
+    for x in (big, sparse_tensor(300, 11, False, 5, (2,)), sparse_tensor(40, 0, False, 6), big[:4096 * 2 + 5] * (big[:4096 * 2 + 5] > 1.0)):
+        x = np.ascontiguousarray(x, np.float32)
+        got = B.mmse_scale_search_activation(dev(x), p, ws)
+        o = oracle.can_search(x, 0, 15, 512, 20)
+        assert int(got.idx[0]) == o["idx"]
+        np.testing.assert_array_equal(got.scale.cpu().numpy(), np.array([o["scale"]], np.float32))
+        np.testing.assert_array_equal(got.sse.cpu().numpy(), np.array([o["sse"]]))
